@@ -1,0 +1,337 @@
+/*
+ * gv_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain, sequential, slow CPU reference for the embedding-training hot path of
+ * GraphVite (arXiv 1903.00757): counter-based random numbers, the alias table
+ * for negative sampling, random-walk edge augmentation, and one-sample-at-a-time
+ * skip-gram SGD with negative sampling.  fp32 storage, fp64 arithmetic.  It
+ * shares no code with the HIP library and must never be called from it; only
+ * tests, the smoke check and the CPU-baseline leg of the benchmark use it.
+ *
+ * Every function names the passage of the paper it follows.  Where the paper
+ * is silent the reading taken is stated in the comment.
+ *
+ * Parity status: negative draws, alias table, augmentation, the SGD step, the
+ * loss and the AUC are pinned by tests that do not go through this file's own
+ * arithmetic (known-answer vectors, closed forms, finite differences, brute
+ * force).  Final embeddings of a long run have no printed value in the paper:
+ * "parity unpinned" in absolute terms, pinned only step by step.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): a keyed bijection on
+ * 128-bit counters.  Ten rounds; before every round but the first the key is
+ * advanced by the Weyl constants.                                            */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Random words of this reference: key = 64-bit seed, counter =
+ * (index low, index high, sub-index, stream).  Streams: 0 training negatives,
+ * 1 embedding initialisation, 2 evaluation negatives, 3 shuffle, 4 walks.
+ * (The paper does not say how random bits are produced; a counter-based
+ * generator makes every draw a pure function of its position.)              */
+enum { STREAM_NEG = 0, STREAM_INIT = 1, STREAM_EVAL = 2, STREAM_SHUFFLE = 3, STREAM_WALK = 4 };
+
+static void words(uint64_t seed, uint64_t index, uint32_t sub, uint32_t stream, uint32_t r[4])
+{
+    uint32_t ctr[4] = { (uint32_t)index, (uint32_t)(index >> 32), sub, stream };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    orc_philox4x32_10(ctr, key, r);
+}
+
+/* floor(R * n / 2^64) for a 64-bit R: a uniform integer in [0, n).           */
+static uint64_t scale64(uint32_t hi, uint32_t lo, uint64_t n)
+{
+    unsigned __int128 R = ((uint64_t)hi << 32) | lo;
+    return (uint64_t)((R * n) >> 64);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alias table (Sec. 4.3 names the alias-table trick and the 3/4 power of the
+ * degree; construction details are this reference's reading, Vose's method):
+ * weights q, scaled p_i = q_i * n / S with S the left-to-right sum; nodes with
+ * p < 1 and p >= 1 go on two stacks in increasing index order; while both are
+ * non-empty pop a small s and a large l, s keeps probability p_s and aliases
+ * to l, l loses 1 - p_s and is re-filed.  Whatever is left keeps itself with
+ * certainty.  Acceptance thresholds are stored as 32-bit integers
+ * floor(p * 2^32), saturated.                                                */
+int orc_alias_build(uint64_t n, const double *q, uint32_t *thresh, uint32_t *alias)
+{
+    if (n == 0 || n > 0xFFFFFFFFull) return -1;
+    double S = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (!(q[i] >= 0.0)) return -1;
+        S += q[i];
+    }
+    if (!(S > 0.0)) return -1;
+    double *p = (double *)malloc(n * sizeof(double));
+    uint32_t *small = (uint32_t *)malloc(n * sizeof(uint32_t));
+    uint32_t *large = (uint32_t *)malloc(n * sizeof(uint32_t));
+    double *prob = (double *)malloc(n * sizeof(double));
+    if (!p || !small || !large || !prob) { free(p); free(small); free(large); free(prob); return -2; }
+    uint64_t ns = 0, nl = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        p[i] = q[i] * (double)n / S;
+        if (p[i] < 1.0) small[ns++] = (uint32_t)i; else large[nl++] = (uint32_t)i;
+    }
+    for (uint64_t i = 0; i < n; ++i) { prob[i] = 1.0; alias[i] = (uint32_t)i; }
+    while (ns > 0 && nl > 0) {
+        uint32_t s = small[--ns];
+        uint32_t l = large[--nl];
+        prob[s] = p[s];
+        alias[s] = l;
+        p[l] = (p[l] + p[s]) - 1.0;
+        if (p[l] < 1.0) small[ns++] = l; else large[nl++] = l;
+    }
+    for (uint64_t i = 0; i < n; ++i) {
+        double t = floor(prob[i] * 4294967296.0);
+        thresh[i] = t >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)t;
+    }
+    free(p); free(small); free(large); free(prob);
+    return 0;
+}
+
+/* Negative-sampling weights: degree to the power 3/4 (Sec. 4.3), written with
+ * square roots only so that the value is correctly rounded everywhere.       */
+void orc_degree_weights(uint64_t n, const uint32_t *deg, double *q)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        double r = sqrt((double)deg[i]);
+        q[i] = r * sqrt(r);
+    }
+}
+
+/* One alias draw from four random words: bucket from the first two words,
+ * acceptance from the third.                                                 */
+static uint32_t alias_draw(const uint32_t r[4], uint64_t n, const uint32_t *thresh, const uint32_t *alias)
+{
+    uint64_t j = scale64(r[0], r[1], n);
+    return r[2] < thresh[j] ? (uint32_t)j : alias[j];
+}
+
+/* Negatives of positive samples first_g .. first_g+count-1: K per sample,
+ * out[(g-first_g)*K + k]   (Alg. 1, the NegativeSampling call).  No redraw
+ * when a negative equals u or v: the paper does not ask for one.             */
+void orc_draw_negatives(uint64_t seed, uint32_t stream, uint64_t first_g, uint64_t count, uint32_t K,
+                        uint64_t n, const uint32_t *thresh, const uint32_t *alias, uint32_t *out)
+{
+    for (uint64_t i = 0; i < count; ++i)
+        for (uint32_t k = 0; k < K; ++k) {
+            uint32_t r[4];
+            words(seed, first_g + i, k, stream, r);
+            out[i * K + k] = alias_draw(r, n, thresh, alias);
+        }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Online augmentation, sequential form (Sec. 3.1, Alg. 2): walk number w
+ * departs from a node chosen with probability proportional to degree (the
+ * owner of a uniformly chosen half-edge of the CSR adjacency), takes L steps,
+ * each to a uniformly chosen neighbour, and contributes every ordered pair
+ * (w_i, w_j), i < j <= i+s, in order of i then j.  Walks first_walk,
+ * first_walk+1, ... are concatenated until `count` pairs exist (the last walk
+ * is cut).  Returns the number of walks used.                                */
+uint64_t orc_augment(uint64_t seed, uint64_t n, const uint64_t *offsets, const uint32_t *adj,
+                     uint32_t L, uint32_t s, uint64_t first_walk, uint64_t count, uint32_t *pairs)
+{
+    uint32_t *path = (uint32_t *)malloc(((size_t)L + 1) * sizeof(uint32_t));
+    uint64_t half_edges = offsets[n];
+    uint64_t produced = 0, w = first_walk;
+    while (produced < count) {
+        uint32_t r[4];
+        words(seed, w, 0, STREAM_WALK, r);
+        uint64_t e = scale64(r[0], r[1], half_edges);
+        /* owner of half-edge e: the node x with offsets[x] <= e < offsets[x+1] */
+        uint64_t lo = 0, hi = n;
+        while (hi - lo > 1) {
+            uint64_t mid = lo + (hi - lo) / 2;
+            if (offsets[mid] <= e) lo = mid; else hi = mid;
+        }
+        path[0] = (uint32_t)lo;
+        for (uint32_t t = 1; t <= L; ++t) {
+            uint32_t x = path[t - 1];
+            uint64_t deg = offsets[x + 1] - offsets[x];
+            words(seed, w, t, STREAM_WALK, r);
+            path[t] = adj[offsets[x] + scale64(r[0], r[1], deg)];
+        }
+        for (uint32_t i = 0; i <= L && produced < count; ++i)
+            for (uint32_t j = i + 1; j <= L && j <= i + s && produced < count; ++j) {
+                pairs[2 * produced] = path[i];
+                pairs[2 * produced + 1] = path[j];
+                ++produced;
+            }
+        ++w;
+    }
+    free(path);
+    return w - first_walk;
+}
+
+/* Uniform shuffle of a pool (Alg. 2, the Shuffle call): Fisher-Yates from the
+ * last position down, position i swapped with a uniform j in [0, i].         */
+void orc_shuffle(uint64_t seed, uint64_t count, uint32_t *pairs)
+{
+    for (uint64_t i = count; i-- > 1;) {
+        uint32_t r[4];
+        words(seed, i, 0, STREAM_SHUFFLE, r);
+        uint64_t j = scale64(r[0], r[1], i + 1);
+        uint32_t a = pairs[2 * i], b = pairs[2 * i + 1];
+        pairs[2 * i] = pairs[2 * j]; pairs[2 * i + 1] = pairs[2 * j + 1];
+        pairs[2 * j] = a; pairs[2 * j + 1] = b;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Initial embeddings (the paper defers to earlier work; the benchmark
+ * configuration fixes it): vertex uniform in (-0.5/d, 0.5/d), context zero.
+ * Element (row, col) takes word col%4 of the block (row, col/4).             */
+void orc_init_embeddings(uint64_t seed, uint64_t n, uint32_t d, float *vertex, float *context)
+{
+    for (uint64_t row = 0; row < n; ++row)
+        for (uint32_t col = 0; col < d; ++col) {
+            uint32_t r[4];
+            words(seed, row, col / 4, STREAM_INIT, r);
+            double unit = ((double)r[col % 4] + 0.5) * (1.0 / 4294967296.0);
+            vertex[row * d + col] = (float)((unit - 0.5) / (double)d);
+        }
+    memset(context, 0, (size_t)n * d * sizeof(float));
+}
+
+static double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+/* log(sigmoid(z)) without overflow */
+static double log_sigmoid(double z) { return z >= 0.0 ? -log1p(exp(-z)) : z - log1p(exp(z)); }
+
+/* Learning rate of positive sample g of T (Sec. 4.3: initial value, linear
+ * decay): evaluated per sample in fp64, stored as fp32.                      */
+float orc_learning_rate(float lr0, float lr_min_ratio, uint64_t g, uint64_t T)
+{
+    double f = 1.0 - (double)g / (double)T;
+    if (f < (double)lr_min_ratio) f = (double)lr_min_ratio;
+    return (float)((double)lr0 * f);
+}
+
+/* Sequential SGD over `count` positive samples (Alg. 1, the training loop):
+ * for sample (u, v) with negatives u'_1..u'_K the scores are the dot products
+ * of vertex[u] with context[v] and context[u'_k] (Sec. 2.1); Train(., ., label)
+ * moves both rows along the gradient of the logistic loss with coefficient
+ * lr * (label - sigmoid(score)), the negative's coefficient scaled by w
+ * (Sec. 4.3: one negative, its gradient scaled by 5).  All scores of a sample
+ * are taken before any of its rows moves, i.e. the sample performs one exact
+ * gradient step of
+ *     loss = -log sigmoid(x_u . c_v) - w * sum_k log sigmoid(-x_u . c_{u'_k});
+ * rows named twice within a sample receive the sum of their updates.
+ * `negatives` may be NULL (then they are drawn here from stream 0) or hold K
+ * indices per sample.                                                        */
+void orc_train(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
+               const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
+               float lr0, float lr_min_ratio, float w, uint64_t seed,
+               const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives)
+{
+    double *dx = (double *)malloc((size_t)d * sizeof(double));
+    double *xu = (double *)malloc((size_t)d * sizeof(double));
+    uint32_t *neg = (uint32_t *)malloc(((size_t)K + 1) * sizeof(uint32_t));
+    double *coef = (double *)malloc(((size_t)K + 1) * sizeof(double));
+    for (uint64_t i = 0; i < count; ++i) {
+        uint64_t g = first_g + i;
+        uint32_t u = pairs[2 * i], v = pairs[2 * i + 1];
+        double lr = (double)orc_learning_rate(lr0, lr_min_ratio, g, T);
+        float *x = vertex + (size_t)u * d;
+        /* row 0 of the sample is the positive context row, rows 1..K the negatives */
+        neg[0] = v;
+        for (uint32_t k = 0; k < K; ++k) {
+            if (negatives) neg[k + 1] = negatives[i * K + k];
+            else {
+                uint32_t r[4];
+                words(seed, g, k, STREAM_NEG, r);
+                neg[k + 1] = alias_draw(r, n, thresh, alias);
+            }
+        }
+        for (uint32_t k = 0; k <= K; ++k) {
+            const float *c = context + (size_t)neg[k] * d;
+            double score = 0.0;
+            for (uint32_t j = 0; j < d; ++j) score += (double)x[j] * (double)c[j];
+            coef[k] = k == 0 ? lr * (1.0 - sigmoid(score)) : -lr * (double)w * sigmoid(score);
+        }
+        for (uint32_t j = 0; j < d; ++j) { xu[j] = (double)x[j]; dx[j] = 0.0; }
+        for (uint32_t k = 0; k <= K; ++k) {
+            const float *c = context + (size_t)neg[k] * d;
+            for (uint32_t j = 0; j < d; ++j) dx[j] += coef[k] * (double)c[j];
+        }
+        /* context rows: a row named several times gets the summed coefficient once */
+        for (uint32_t k = 0; k <= K; ++k) {
+            int seen = 0;
+            for (uint32_t k2 = 0; k2 < k; ++k2) if (neg[k2] == neg[k]) seen = 1;
+            if (seen) continue;
+            double total = 0.0;
+            for (uint32_t k2 = k; k2 <= K; ++k2) if (neg[k2] == neg[k]) total += coef[k2];
+            float *c = context + (size_t)neg[k] * d;
+            for (uint32_t j = 0; j < d; ++j) c[j] = (float)((double)c[j] + total * xu[j]);
+        }
+        for (uint32_t j = 0; j < d; ++j) x[j] = (float)(xu[j] + dx[j]);
+    }
+    free(dx); free(xu); free(neg); free(coef);
+}
+
+/* Mean per-sample loss (the objective the step above descends) over a fixed
+ * evaluation pool, negatives from stream 2 with sample index i.              */
+double orc_loss(const float *vertex, const float *context, uint64_t n, uint32_t d, uint32_t K,
+                const uint32_t *pairs, uint64_t count, float w, uint64_t seed, uint32_t stream,
+                const uint32_t *thresh, const uint32_t *alias)
+{
+    double total = 0.0;
+    for (uint64_t i = 0; i < count; ++i) {
+        const float *x = vertex + (size_t)pairs[2 * i] * d;
+        const float *c = context + (size_t)pairs[2 * i + 1] * d;
+        double score = 0.0;
+        for (uint32_t j = 0; j < d; ++j) score += (double)x[j] * (double)c[j];
+        double loss = -log_sigmoid(score);
+        for (uint32_t k = 0; k < K; ++k) {
+            uint32_t r[4];
+            words(seed, i, k, stream, r);
+            const float *cn = context + (size_t)alias_draw(r, n, thresh, alias) * d;
+            double sn = 0.0;
+            for (uint32_t j = 0; j < d; ++j) sn += (double)x[j] * (double)cn[j];
+            loss -= (double)w * log_sigmoid(-sn);
+        }
+        total += loss;
+    }
+    return total / (double)count;
+}
+
+/* Cosine similarity of vertex rows a[i], b[i] (Sec. 4.5: an edge is scored by
+ * the cosine of its two node embeddings).  A zero row scores 0.              */
+void orc_cosine(const float *vertex, uint32_t d, const uint32_t *a, const uint32_t *b, uint64_t count, double *out)
+{
+    for (uint64_t i = 0; i < count; ++i) {
+        const float *x = vertex + (size_t)a[i] * d;
+        const float *y = vertex + (size_t)b[i] * d;
+        double xy = 0.0, xx = 0.0, yy = 0.0;
+        for (uint32_t j = 0; j < d; ++j) {
+            xy += (double)x[j] * (double)y[j];
+            xx += (double)x[j] * (double)x[j];
+            yy += (double)y[j] * (double)y[j];
+        }
+        out[i] = (xx > 0.0 && yy > 0.0) ? xy / (sqrt(xx) * sqrt(yy)) : 0.0;
+    }
+}
