@@ -1,0 +1,147 @@
+/*
+ * gvhot.h -- C boundary of the GPU training hot path of GraphVite
+ * (arXiv 1903.00757) on one AMD MI355X (gfx950).
+ *
+ * The library holds a vertex- and a context-embedding matrix (|V| x d, fp32,
+ * row-major, Sec. 2.1) in device memory and trains them with pools of positive
+ * edge samples (u, v): per sample, K negative context rows are drawn on the
+ * device from the degree^(3/4) alias table (Sec. 4.3), the dot products
+ * vertex[u].context[.] are formed, and the rows are moved in place by one
+ * logistic-loss gradient step (Alg. 1, the Train calls), asynchronously and
+ * without locks across samples (Sec. 4.3, asynchronous SGD).
+ *
+ * Conventions
+ *   - Every call returns GV_OK (0) or a negative error code; nothing aborts or
+ *     throws across this boundary.  gv_last_error() gives the text of the last
+ *     failure of that context.
+ *   - Pointers named `host_*` are host memory owned by the caller; the library
+ *     has finished reading or writing them when the call returns unless stated
+ *     otherwise.  Pointers named `dev_*` are device memory of the context's GPU
+ *     owned by the caller.  All other device memory is owned by the library.
+ *   - Node ids are uint32, sample/edge counts uint64 (Table 1: 4-byte ids,
+ *     8-byte samples).  A sample pool is uint32[count][2] = (u, v) pairs.
+ *   - One context must not be used from two threads at once; contexts are
+ *     independent of each other.
+ *   - Random numbers: Philox4x32-10, key = 64-bit seed, counter =
+ *     (index low, index high, sub-index, stream); stream 0 = training
+ *     negatives (index = global position of the positive sample, sub-index =
+ *     k), stream 1 = initial embeddings (index = row, sub-index = column / 4).
+ */
+#ifndef GVHOT_H
+#define GVHOT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gv_ctx gv_ctx;
+
+enum { GV_OK = 0, GV_EINVAL = -1, GV_ENOMEM = -2, GV_ESTATE = -3, GV_EHIP = -4 };
+enum { GV_MODE_HOGWILD = 0, GV_MODE_DETERMINISTIC = 1 };
+enum { GV_VERTEX = 0, GV_CONTEXT = 1 };
+/* How embedding rows travel between compute units and memory while a training
+ * kernel runs.  PLAIN: ordinary cached accesses (each XCD's L2 holds its own
+ * copy of a hot row until the kernel ends).  AGENT: device-scope accesses, so
+ * an update made on one XCD is seen by the others within the same kernel.     */
+enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT = 2, GV_COHERENCE_ATOMIC_L2 = 3 };
+
+typedef struct gv_config {
+    uint32_t dim;            /* d: 64, 128, 256 or 512                                        */
+    uint32_t num_neg;        /* K negatives per positive sample, 1..5                         */
+    float lr0;               /* initial learning rate (0.025 in Sec. 4.3)                      */
+    float lr_min_ratio;      /* floor of the linear decay as a fraction of lr0 (0 = none)      */
+    float neg_weight;        /* w: factor on every negative's gradient (5 at K = 1, Sec. 4.3)  */
+    uint32_t mode;           /* GV_MODE_*                                                      */
+    uint64_t total_samples;  /* T: planned positive samples; lr(g) = lr0 * max(1 - g/T, floor) */
+    uint64_t seed;           /* key of the negative-sampling stream                            */
+    uint64_t pool_capacity;  /* largest pool (in samples) that will be pushed; sizes the two
+                                pinned host slots and the two device buffers (8 B / sample)    */
+    int32_t device;          /* HIP device ordinal                                             */
+    uint32_t coherence;      /* GV_COHERENCE_*                                                 */
+    uint32_t profile;        /* nonzero: time every training launch with HIP events            */
+    uint32_t reserved;       /* must be 0                                                      */
+} gv_config;
+
+typedef struct gv_stats {
+    uint64_t samples_trained;   /* positive samples consumed so far = next global position g   */
+    uint64_t pools_trained;
+    uint64_t train_launches;    /* training kernel launches (deterministic mode: one per batch) */
+    uint64_t batches;           /* deterministic mode: conflict-free batches cut so far         */
+    double train_kernel_ms;     /* sum of event-timed launch durations (profile != 0), resolved
+                                   by gv_sync                                                   */
+    uint64_t timed_launches;    /* launches contributing to train_kernel_ms                    */
+    double h2d_ms;              /* event-timed pool copies host -> device (profile != 0)        */
+    uint64_t h2d_bytes;
+} gv_stats;
+
+/* Create a context on cfg->device.  Allocates the pool slots only; the graph
+ * decides the matrix sizes later.  *out is NULL on failure.                    */
+int gv_create(const gv_config *cfg, gv_ctx **out);
+void gv_destroy(gv_ctx *ctx);
+const char *gv_last_error(const gv_ctx *ctx); /* ctx may be NULL: error of a failed gv_create */
+
+/* Graph G = (V, E), undirected (Sec. 2.1, Sec. 4.3): m edges (host_src[i],
+ * host_dst[i]), ids < n; only the degrees are kept.  Allocates both n x d
+ * matrices (zero) and the alias table.  GV_EINVAL on an id >= n.               */
+int gv_set_graph(gv_ctx *ctx, uint32_t n, uint64_t m, const uint32_t *host_src, const uint32_t *host_dst);
+/* Same, from degrees alone (for graphs whose edge list the caller streams).    */
+int gv_set_degrees(gv_ctx *ctx, uint32_t n, const uint32_t *host_deg);
+
+/* Alias table over nodes with weights degree^power (Sec. 4.3: power 3/4).
+ * power must be 0.75 (exact, via square roots), 1.0 or 0.0.  Built on the host
+ * with Vose's method in fp64 (index-ordered stacks), thresholds stored as
+ * floor(p * 2^32) saturated; uploaded to the device.                           */
+int gv_build_alias(gv_ctx *ctx, double power);
+/* Copy the table out: host_thresh[n], host_alias[n].                           */
+int gv_get_alias(gv_ctx *ctx, uint32_t *host_thresh, uint32_t *host_alias);
+
+/* vertex ~ U(-0.5/d, 0.5/d) from stream 1 of `seed`, context = 0.              */
+int gv_init_embeddings(gv_ctx *ctx, uint64_t seed);
+/* Overwrite rows [row0, row0+rows) of one matrix from host_rows[rows][d].      */
+int gv_set_embeddings(gv_ctx *ctx, int which, const float *host_rows, uint64_t row0, uint64_t rows);
+/* Wait for all training, then copy rows [row0, row0+rows) to host_rows.        */
+int gv_read_embeddings(gv_ctx *ctx, int which, float *host_rows, uint64_t row0, uint64_t rows);
+/* Device address of a matrix (library-owned; valid until gv_destroy).          */
+int gv_device_embeddings(gv_ctx *ctx, int which, float **dev_rows);
+
+/* Pool streaming (Sec. 3.3 two pools, Sec. 3.4 batched transfer).  The context
+ * has two pinned host slots of pool_capacity samples, each paired with a device
+ * buffer.  gv_acquire_pool_slot hands out the next free slot for the producer
+ * to fill in place (blocks until the training launch that last used that slot
+ * has finished).  gv_push_pool queues `count` samples for training: if
+ * host_pairs is a pointer returned by gv_acquire_pool_slot the copy to the
+ * device starts directly from it, otherwise the samples are first copied into
+ * the next free slot (host_pairs may be reused on return).  The copy runs on
+ * its own stream and overlaps training of the previously pushed pool.  At most
+ * two pools can be queued and untrained: a third push returns GV_ESTATE.
+ * Node ids are checked on the device while training: a sample naming an id >= n
+ * is skipped, and the next gv_sync (or any call that synchronises) returns
+ * GV_EINVAL once.                                                              */
+int gv_acquire_pool_slot(gv_ctx *ctx, uint32_t **host_pairs);
+int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count);
+/* Train the oldest queued pool: positive samples g .. g+count-1 where g is the
+ * number of samples trained so far.  Returns after launching (asynchronous);
+ * GV_ESTATE if nothing is queued.                                              */
+int gv_train_pool(gv_ctx *ctx);
+/* Train a pool that already lies in device memory (dev_pairs must stay valid
+ * and unchanged until gv_sync).  Ids are checked as for pushed pools.
+ * count < 2^32.                                                                */
+int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
+
+/* The K negatives of positive samples first_g .. first_g+count-1, exactly as
+ * training draws them: host_out[count][K].                                     */
+int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out);
+
+/* Wait for all queued device work of the context; folds event timings into the
+ * statistics.                                                                   */
+int gv_sync(gv_ctx *ctx);
+int gv_get_stats(gv_ctx *ctx, gv_stats *out);
+/* Set the position g of the next positive sample (resume / tests).             */
+int gv_set_position(gv_ctx *ctx, uint64_t next_g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GVHOT_H */

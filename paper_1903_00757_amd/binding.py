@@ -1,0 +1,212 @@
+"""ctypes binding of libgvhot.so: the same calls as include/gvhot.h, with numpy
+arrays marshalled to plain pointers.  No arithmetic of the method happens here.
+The library must have been built (``python -m paper_1903_00757_amd.build``);
+loading fails loudly otherwise -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+GV_OK, GV_EINVAL, GV_ENOMEM, GV_ESTATE, GV_EHIP = 0, -1, -2, -3, -4
+GV_MODE_HOGWILD, GV_MODE_DETERMINISTIC = 0, 1
+GV_VERTEX, GV_CONTEXT = 0, 1
+GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_ATOMIC_L2 = 0, 1, 2, 3
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
+
+EXPORTS = [
+    "gv_create", "gv_destroy", "gv_last_error", "gv_set_graph", "gv_set_degrees", "gv_build_alias", "gv_get_alias",
+    "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
+    "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
+    "gv_sync", "gv_get_stats", "gv_set_position",
+]
+
+
+class gv_config(C.Structure):
+    _fields_ = [
+        ("dim", C.c_uint32), ("num_neg", C.c_uint32),
+        ("lr0", C.c_float), ("lr_min_ratio", C.c_float), ("neg_weight", C.c_float),
+        ("mode", C.c_uint32),
+        ("total_samples", C.c_uint64), ("seed", C.c_uint64), ("pool_capacity", C.c_uint64),
+        ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("reserved", C.c_uint32),
+    ]
+
+
+class gv_stats(C.Structure):
+    _fields_ = [
+        ("samples_trained", C.c_uint64), ("pools_trained", C.c_uint64), ("train_launches", C.c_uint64),
+        ("batches", C.c_uint64), ("train_kernel_ms", C.c_double), ("timed_launches", C.c_uint64),
+        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64),
+    ]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class GvError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"gvhot error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1903_00757_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, u32p, f32p = C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_float)
+    L.gv_create.argtypes = [C.POINTER(gv_config), C.POINTER(vp)]
+    L.gv_destroy.argtypes = [vp]
+    L.gv_destroy.restype = None
+    L.gv_last_error.argtypes = [vp]
+    L.gv_last_error.restype = C.c_char_p
+    L.gv_set_graph.argtypes = [vp, C.c_uint32, C.c_uint64, u32p, u32p]
+    L.gv_set_degrees.argtypes = [vp, C.c_uint32, u32p]
+    L.gv_build_alias.argtypes = [vp, C.c_double]
+    L.gv_get_alias.argtypes = [vp, u32p, u32p]
+    L.gv_init_embeddings.argtypes = [vp, C.c_uint64]
+    L.gv_set_embeddings.argtypes = [vp, C.c_int, f32p, C.c_uint64, C.c_uint64]
+    L.gv_read_embeddings.argtypes = [vp, C.c_int, f32p, C.c_uint64, C.c_uint64]
+    L.gv_device_embeddings.argtypes = [vp, C.c_int, C.POINTER(vp)]
+    L.gv_acquire_pool_slot.argtypes = [vp, C.POINTER(u32p)]
+    L.gv_push_pool.argtypes = [vp, vp, C.c_uint64]
+    L.gv_train_pool.argtypes = [vp]
+    L.gv_train_device_pool.argtypes = [vp, vp, C.c_uint64]
+    L.gv_draw_negatives.argtypes = [vp, C.c_uint64, C.c_uint64, u32p]
+    L.gv_sync.argtypes = [vp]
+    L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
+    L.gv_set_position.argtypes = [vp, C.c_uint64]
+    for name in EXPORTS:
+        if name not in ("gv_destroy", "gv_last_error"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(ctx, rc):
+    if rc != GV_OK:
+        text = load().gv_last_error(ctx)
+        raise GvError(rc, text.decode() if text else "")
+
+
+def _u32(a):
+    a = np.ascontiguousarray(a, dtype=np.uint32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=None, mode=GV_MODE_HOGWILD,
+              total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_ATOMIC_AGENT, profile=0):
+    cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio,
+                    neg_weight=(5.0 / max(num_neg, 1) if neg_weight is None else neg_weight), mode=mode,
+                    total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,
+                    coherence=coherence, profile=profile, reserved=0)
+    ctx = C.c_void_p()
+    rc = load().gv_create(C.byref(cfg), C.byref(ctx))
+    _check(None, rc)
+    return ctx
+
+
+def gv_destroy(ctx):
+    load().gv_destroy(ctx)
+
+
+def gv_last_error(ctx=None):
+    text = load().gv_last_error(ctx)
+    return text.decode() if text else ""
+
+
+def gv_set_graph(ctx, n, src, dst):
+    src, ps = _u32(src)
+    dst, pd = _u32(dst)
+    if src.size != dst.size:
+        raise ValueError("src and dst differ in length")
+    _check(ctx, load().gv_set_graph(ctx, n, src.size, ps, pd))
+
+
+def gv_set_degrees(ctx, deg):
+    deg, p = _u32(deg)
+    _check(ctx, load().gv_set_degrees(ctx, deg.size, p))
+
+
+def gv_build_alias(ctx, power=0.75):
+    _check(ctx, load().gv_build_alias(ctx, power))
+
+
+def gv_get_alias(ctx, n):
+    thresh = np.empty(n, dtype=np.uint32)
+    alias = np.empty(n, dtype=np.uint32)
+    _check(ctx, load().gv_get_alias(ctx, thresh.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                    alias.ctypes.data_as(C.POINTER(C.c_uint32))))
+    return thresh, alias
+
+
+def gv_init_embeddings(ctx, seed):
+    _check(ctx, load().gv_init_embeddings(ctx, seed))
+
+
+def gv_set_embeddings(ctx, which, rows, row0=0):
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    _check(ctx, load().gv_set_embeddings(ctx, which, rows.ctypes.data_as(C.POINTER(C.c_float)), row0, rows.shape[0]))
+
+
+def gv_read_embeddings(ctx, which, n, dim, row0=0):
+    out = np.empty((n, dim), dtype=np.float32)
+    _check(ctx, load().gv_read_embeddings(ctx, which, out.ctypes.data_as(C.POINTER(C.c_float)), row0, n))
+    return out
+
+
+def gv_device_embeddings(ctx, which):
+    p = C.c_void_p()
+    _check(ctx, load().gv_device_embeddings(ctx, which, C.byref(p)))
+    return p.value
+
+
+def gv_acquire_pool_slot(ctx, capacity):
+    """Pinned slot as a writable numpy view of shape (capacity, 2)."""
+    p = C.POINTER(C.c_uint32)()
+    _check(ctx, load().gv_acquire_pool_slot(ctx, C.byref(p)))
+    return np.ctypeslib.as_array(p, shape=(capacity, 2))
+
+
+def gv_push_pool(ctx, pairs, count=None):
+    if not (isinstance(pairs, np.ndarray) and pairs.dtype == np.uint32 and pairs.flags.c_contiguous):
+        pairs = np.ascontiguousarray(pairs, dtype=np.uint32)
+    count = pairs.shape[0] if count is None else count
+    _check(ctx, load().gv_push_pool(ctx, C.c_void_p(pairs.ctypes.data), count))
+
+
+def gv_train_pool(ctx):
+    _check(ctx, load().gv_train_pool(ctx))
+
+
+def gv_train_device_pool(ctx, dev_ptr, count):
+    _check(ctx, load().gv_train_device_pool(ctx, C.c_void_p(dev_ptr), count))
+
+
+def gv_draw_negatives(ctx, first_g, count, num_neg):
+    out = np.empty((count, num_neg), dtype=np.uint32)
+    _check(ctx, load().gv_draw_negatives(ctx, first_g, count, out.ctypes.data_as(C.POINTER(C.c_uint32))))
+    return out
+
+
+def gv_sync(ctx):
+    _check(ctx, load().gv_sync(ctx))
+
+
+def gv_get_stats(ctx):
+    s = gv_stats()
+    _check(ctx, load().gv_get_stats(ctx, C.byref(s)))
+    return s.as_dict()
+
+
+def gv_set_position(ctx, next_g):
+    _check(ctx, load().gv_set_position(ctx, next_g))

@@ -1,0 +1,689 @@
+// Host runtime behind the C boundary declared in include/gvhot.h: context,
+// alias-table builder, pinned double-buffered pool ring with asynchronous
+// host-to-device copies, launch sequencing, deterministic batch cutting.
+#include "gvhot.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "gv_internal.hpp"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+enum SlotState { kFree = 0, kFilling = 1, kQueued = 2, kTraining = 3 };
+
+struct PoolSlot {
+    uint32_t *host = nullptr;    // pinned, pool_capacity samples
+    uint32_t *dev = nullptr;     // device twin
+    hipEvent_t copied = nullptr; // host-to-device copy finished (copy stream)
+    hipEvent_t trained = nullptr;// training launch that read `dev` finished (compute stream)
+    uint64_t count = 0;
+    SlotState state = kFree;
+};
+
+struct TimedSpan {
+    hipEvent_t start, stop;
+    int kind;  // 0 training launch, 1 host-to-device copy
+};
+
+}  // namespace
+
+struct gv_ctx {
+    gv_config cfg{};
+    uint32_t n = 0;
+    std::vector<uint32_t> degree;
+    float *vertex = nullptr;
+    float *context = nullptr;
+    uint2 *alias = nullptr;
+    bool alias_ready = false;
+    uint32_t *error_flag = nullptr;       // device
+    uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
+    uint64_t negatives_capacity = 0;      // in uint32 elements
+    hipStream_t compute = nullptr;
+    hipStream_t copy = nullptr;
+    PoolSlot slot[2];
+    int queue[2] = {-1, -1};              // FIFO of queued slot indices
+    int queued = 0;
+    int next_slot = 0;                    // slots are handed out alternately
+    uint64_t next_g = 0;
+    gv_stats stats{};
+    std::vector<TimedSpan> spans;         // recorded, not yet folded into stats
+    std::vector<hipEvent_t> spare_events;
+    std::vector<uint32_t> stamp_vertex, stamp_context;  // deterministic batch cutting
+    uint32_t stamp = 0;
+    std::string error;
+};
+
+namespace {
+
+int fail(gv_ctx *ctx, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->error = buf; else g_create_error = buf;
+    return code;
+}
+
+#define GV_HIP(ctx, expr)                                                                          \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? GV_ENOMEM : GV_EHIP, "%s: %s", #expr,     \
+                        hipGetErrorString(e_));                                                    \
+    } while (0)
+
+int bind_device(gv_ctx *ctx) {
+    GV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    return GV_OK;
+}
+
+hipEvent_t take_event(gv_ctx *ctx) {
+    if (!ctx->spare_events.empty()) {
+        hipEvent_t e = ctx->spare_events.back();
+        ctx->spare_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Fold finished event pairs into the statistics (called with the device idle).
+void fold_spans(gv_ctx *ctx) {
+    for (const TimedSpan &s : ctx->spans) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, s.start, s.stop) == hipSuccess) {
+            if (s.kind == 0) {
+                ctx->stats.train_kernel_ms += ms;
+                ctx->stats.timed_launches += 1;
+            } else {
+                ctx->stats.h2d_ms += ms;
+            }
+        }
+        ctx->spare_events.push_back(s.start);
+        ctx->spare_events.push_back(s.stop);
+    }
+    ctx->spans.clear();
+}
+
+int sync_all(gv_ctx *ctx) {
+    GV_HIP(ctx, hipStreamSynchronize(ctx->copy));
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    fold_spans(ctx);
+    for (PoolSlot &s : ctx->slot)
+        if (s.state == kTraining) s.state = kFree;
+    uint32_t flag = 0;
+    GV_HIP(ctx, hipMemcpy(&flag, ctx->error_flag, sizeof flag, hipMemcpyDeviceToHost));
+    if (flag) {
+        GV_HIP(ctx, hipMemset(ctx->error_flag, 0, sizeof flag));
+        return fail(ctx, GV_EINVAL, "a trained pool named a node id >= n (%u); those samples were skipped", ctx->n);
+    }
+    return GV_OK;
+}
+
+void free_matrices(gv_ctx *ctx) {
+    if (ctx->vertex) (void)hipFree(ctx->vertex);
+    if (ctx->context) (void)hipFree(ctx->context);
+    if (ctx->alias) (void)hipFree(ctx->alias);
+    ctx->vertex = ctx->context = nullptr;
+    ctx->alias = nullptr;
+    ctx->alias_ready = false;
+}
+
+int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
+    int rc = sync_all(ctx);
+    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    free_matrices(ctx);
+    ctx->n = 0;
+    const size_t bytes = (size_t)n * ctx->cfg.dim * sizeof(float);
+    GV_HIP(ctx, hipMalloc((void **)&ctx->vertex, bytes));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->context, bytes));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint2)));
+    GV_HIP(ctx, hipMemsetAsync(ctx->vertex, 0, bytes, ctx->compute));
+    GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    ctx->degree = std::move(deg);
+    ctx->n = n;
+    ctx->stamp_vertex.clear();
+    ctx->stamp_context.clear();
+    return GV_OK;
+}
+
+int need_graph(gv_ctx *ctx) {
+    if (!ctx) return GV_EINVAL;
+    if (ctx->n == 0) return fail(ctx, GV_ESTATE, "no graph: call gv_set_graph or gv_set_degrees first");
+    return bind_device(ctx);
+}
+
+int need_trainable(gv_ctx *ctx) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (!ctx->alias_ready) return fail(ctx, GV_ESTATE, "no alias table: call gv_build_alias first");
+    return GV_OK;
+}
+
+int ensure_negatives(gv_ctx *ctx, uint64_t elements) {
+    if (elements <= ctx->negatives_capacity) return GV_OK;
+    if (ctx->negatives) {
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+        (void)hipFree(ctx->negatives);
+        ctx->negatives = nullptr;
+        ctx->negatives_capacity = 0;
+    }
+    GV_HIP(ctx, hipMalloc((void **)&ctx->negatives, elements * sizeof(uint32_t)));
+    ctx->negatives_capacity = elements;
+    return GV_OK;
+}
+
+gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_g, uint32_t count) {
+    gv::TrainArgs a{};
+    a.vertex = ctx->vertex;
+    a.context = ctx->context;
+    a.alias = ctx->alias;
+    a.pairs = dev_pairs;
+    a.negatives = nullptr;
+    a.error_flag = ctx->error_flag;
+    a.first_g = first_g;
+    a.total = ctx->cfg.total_samples;
+    a.seed = ctx->cfg.seed;
+    a.count = count;
+    a.n = ctx->n;
+    a.lr0 = ctx->cfg.lr0;
+    a.lr_min_ratio = ctx->cfg.lr_min_ratio;
+    a.neg_weight = ctx->cfg.neg_weight;
+    return a;
+}
+
+int begin_span(gv_ctx *ctx, int kind, hipStream_t stream, TimedSpan *span) {
+    span->kind = kind;
+    span->start = take_event(ctx);
+    span->stop = take_event(ctx);
+    if (!span->start || !span->stop) return fail(ctx, GV_EHIP, "hipEventCreate failed");
+    GV_HIP(ctx, hipEventRecord(span->start, stream));
+    return GV_OK;
+}
+
+int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
+    GV_HIP(ctx, hipEventRecord(span.stop, stream));
+    ctx->spans.push_back(span);
+    if (ctx->spans.size() >= 8192) {  // bound the number of live events
+        GV_HIP(ctx, hipEventSynchronize(span.stop));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->copy));
+        fold_spans(ctx);
+    }
+    return GV_OK;
+}
+
+// Asynchronous training of `count` samples at dev_pairs: one launch.
+int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
+    TimedSpan span{};
+    const bool timed = ctx->cfg.profile != 0;
+    if (timed) {
+        int rc = begin_span(ctx, 0, ctx->compute, &span);
+        if (rc) return rc;
+    }
+    gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
+    GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+    ctx->stats.train_launches += 1;
+    if (timed) return end_span(ctx, ctx->compute, span);
+    return GV_OK;
+}
+
+// Deterministic training: draw the pool's negatives on the device, bring them
+// and the pairs to the host, cut the sample sequence greedily into maximal runs
+// in which no vertex row and no context row (positive or negative) repeats, and
+// launch one conflict-free batch per run, in order.  Samples inside a run commute
+// exactly (Def. 1, Sec. 3.2), so the result is the sequential one up to fp32
+// rounding inside a sample.
+int train_deterministic(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *host_pairs, uint64_t count) {
+    const uint32_t K = ctx->cfg.num_neg;
+    int rc = ensure_negatives(ctx, count * K);
+    if (rc) return rc;
+    GV_HIP(ctx, gv::launch_draw_negatives(ctx->alias, ctx->n, ctx->cfg.seed, ctx->next_g, count, K, ctx->negatives,
+                                          ctx->compute));
+    std::vector<uint32_t> neg(count * K);
+    std::vector<uint32_t> pairs_copy;
+    GV_HIP(ctx, hipMemcpyAsync(neg.data(), ctx->negatives, neg.size() * sizeof(uint32_t), hipMemcpyDeviceToHost,
+                               ctx->compute));
+    if (!host_pairs) {
+        pairs_copy.resize(count * 2);
+        GV_HIP(ctx, hipMemcpyAsync(pairs_copy.data(), dev_pairs, pairs_copy.size() * sizeof(uint32_t),
+                                   hipMemcpyDeviceToHost, ctx->compute));
+        host_pairs = pairs_copy.data();
+    }
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+
+    if (ctx->stamp_vertex.size() != ctx->n) {
+        ctx->stamp_vertex.assign(ctx->n, 0);
+        ctx->stamp_context.assign(ctx->n, 0);
+        ctx->stamp = 0;
+    }
+    std::vector<uint64_t> starts;
+    auto open_batch = [&](uint64_t at) {
+        starts.push_back(at);
+        if (++ctx->stamp == 0) {  // stamp wrapped: clear and restart numbering
+            std::fill(ctx->stamp_vertex.begin(), ctx->stamp_vertex.end(), 0u);
+            std::fill(ctx->stamp_context.begin(), ctx->stamp_context.end(), 0u);
+            ctx->stamp = 1;
+        }
+    };
+    open_batch(0);
+    for (uint64_t i = 0; i < count; ++i) {
+        const uint32_t u = host_pairs[2 * i], v = host_pairs[2 * i + 1];
+        if (u >= ctx->n || v >= ctx->n)
+            return fail(ctx, GV_EINVAL, "sample %llu names node id >= n (%u)", (unsigned long long)i, ctx->n);
+        bool clash = ctx->stamp_vertex[u] == ctx->stamp || ctx->stamp_context[v] == ctx->stamp;
+        for (uint32_t k = 0; k < K && !clash; ++k) clash = ctx->stamp_context[neg[i * K + k]] == ctx->stamp;
+        if (clash) open_batch(i);
+        ctx->stamp_vertex[u] = ctx->stamp;
+        ctx->stamp_context[v] = ctx->stamp;
+        for (uint32_t k = 0; k < K; ++k) ctx->stamp_context[neg[i * K + k]] = ctx->stamp;
+    }
+    starts.push_back(count);
+
+    TimedSpan span{};
+    const bool timed = ctx->cfg.profile != 0;
+    if (timed) {
+        rc = begin_span(ctx, 0, ctx->compute, &span);
+        if (rc) return rc;
+    }
+    for (size_t b = 0; b + 1 < starts.size(); ++b) {
+        const uint64_t lo = starts[b], hi = starts[b + 1];
+        gv::TrainArgs a = train_args(ctx, dev_pairs + 2 * lo, ctx->next_g + lo, (uint32_t)(hi - lo));
+        a.negatives = ctx->negatives + lo * K;
+        GV_HIP(ctx, gv::launch_train_batch(a, ctx->cfg.dim, K, ctx->compute));
+    }
+    ctx->stats.train_launches += starts.size() - 1;
+    ctx->stats.batches += starts.size() - 1;
+    if (timed) return end_span(ctx, ctx->compute, span);
+    return GV_OK;
+}
+
+int train_any(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *host_pairs, uint64_t count) {
+    if (count == 0) return GV_OK;
+    int rc = ctx->cfg.mode == GV_MODE_DETERMINISTIC ? train_deterministic(ctx, dev_pairs, host_pairs, count)
+                                                    : train_hogwild(ctx, dev_pairs, count);
+    if (rc) return rc;
+    ctx->next_g += count;
+    ctx->stats.samples_trained = ctx->next_g;
+    ctx->stats.pools_trained += 1;
+    return GV_OK;
+}
+
+// Wait until a slot no longer feeds a running launch, then mark it free.
+int release_slot(gv_ctx *ctx, PoolSlot &s) {
+    if (s.state == kTraining) {
+        GV_HIP(ctx, hipEventSynchronize(s.trained));
+        s.state = kFree;
+    }
+    return GV_OK;
+}
+
+int pick_free_slot(gv_ctx *ctx, int *index) {
+    for (int t = 0; t < 2; ++t) {
+        const int i = (ctx->next_slot + t) & 1;
+        PoolSlot &s = ctx->slot[i];
+        if (s.state == kFree || s.state == kTraining) {
+            int rc = release_slot(ctx, s);
+            if (rc) return rc;
+            *index = i;
+            ctx->next_slot = i ^ 1;
+            return GV_OK;
+        }
+    }
+    return fail(ctx, GV_ESTATE, "both pool slots are filling or queued: train a pool first");
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gv_last_error(const gv_ctx *ctx) { return ctx ? ctx->error.c_str() : g_create_error.c_str(); }
+
+int gv_create(const gv_config *cfg, gv_ctx **out) {
+    if (out) *out = nullptr;
+    if (!cfg || !out) return fail(nullptr, GV_EINVAL, "null argument");
+    if (!gv::supported_shape(cfg->dim, cfg->num_neg))
+        return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (64/128/256/512), num_neg %u (1..5)", cfg->dim,
+                    cfg->num_neg);
+    if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
+    if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 32))
+        return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^32 samples");
+    if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_ATOMIC_L2 || cfg->reserved != 0)
+        return fail(nullptr, GV_EINVAL, "bad mode / coherence / reserved field");
+    if (!(cfg->lr0 >= 0.0f) || !(cfg->lr_min_ratio >= 0.0f) || !(cfg->neg_weight >= 0.0f) || !isfinite(cfg->lr0) ||
+        !isfinite(cfg->neg_weight))
+        return fail(nullptr, GV_EINVAL, "lr0, lr_min_ratio and neg_weight must be finite and >= 0");
+    int devices = 0;
+    if (hipGetDeviceCount(&devices) != hipSuccess || devices <= 0)
+        return fail(nullptr, GV_EHIP, "no HIP device available");
+    if (cfg->device < 0 || cfg->device >= devices)
+        return fail(nullptr, GV_EINVAL, "device %d out of range (%d present)", cfg->device, devices);
+    gv_ctx *ctx = new (std::nothrow) gv_ctx;
+    if (!ctx) return fail(nullptr, GV_ENOMEM, "out of host memory");
+    ctx->cfg = *cfg;
+    auto bail = [&](int code) {
+        g_create_error = ctx->error;
+        gv_destroy(ctx);
+        return code;
+    };
+#define GV_TRY(expr)                                                                                       \
+    do {                                                                                                   \
+        hipError_t e_ = (expr);                                                                            \
+        if (e_ != hipSuccess) {                                                                            \
+            fail(ctx, e_ == hipErrorOutOfMemory ? GV_ENOMEM : GV_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+            return bail(e_ == hipErrorOutOfMemory ? GV_ENOMEM : GV_EHIP);                                  \
+        }                                                                                                  \
+    } while (0)
+    GV_TRY(hipSetDevice(cfg->device));
+    GV_TRY(hipStreamCreateWithFlags(&ctx->compute, hipStreamNonBlocking));
+    GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
+    GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
+    GV_TRY(hipMemset(ctx->error_flag, 0, sizeof(uint32_t)));
+    const size_t pool_bytes = (size_t)cfg->pool_capacity * 2 * sizeof(uint32_t);
+    for (PoolSlot &s : ctx->slot) {
+        GV_TRY(hipHostMalloc((void **)&s.host, pool_bytes, hipHostMallocDefault));
+        GV_TRY(hipMalloc((void **)&s.dev, pool_bytes));
+        GV_TRY(hipEventCreateWithFlags(&s.copied, hipEventDisableTiming));
+        GV_TRY(hipEventCreateWithFlags(&s.trained, hipEventDisableTiming));
+    }
+#undef GV_TRY
+    *out = ctx;
+    return GV_OK;
+}
+
+void gv_destroy(gv_ctx *ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->cfg.device);
+    if (ctx->copy) (void)hipStreamSynchronize(ctx->copy);
+    if (ctx->compute) (void)hipStreamSynchronize(ctx->compute);
+    fold_spans(ctx);
+    for (hipEvent_t e : ctx->spare_events) (void)hipEventDestroy(e);
+    for (PoolSlot &s : ctx->slot) {
+        if (s.host) (void)hipHostFree(s.host);
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.copied) (void)hipEventDestroy(s.copied);
+        if (s.trained) (void)hipEventDestroy(s.trained);
+    }
+    free_matrices(ctx);
+    if (ctx->negatives) (void)hipFree(ctx->negatives);
+    if (ctx->error_flag) (void)hipFree(ctx->error_flag);
+    if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
+    if (ctx->compute) (void)hipStreamDestroy(ctx->compute);
+    delete ctx;
+}
+
+int gv_set_graph(gv_ctx *ctx, uint32_t n, uint64_t m, const uint32_t *host_src, const uint32_t *host_dst) {
+    if (!ctx) return GV_EINVAL;
+    if (n == 0 || (m > 0 && (!host_src || !host_dst))) return fail(ctx, GV_EINVAL, "empty graph or null edge arrays");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    std::vector<uint32_t> deg(n, 0u);
+    for (uint64_t i = 0; i < m; ++i) {
+        const uint32_t a = host_src[i], b = host_dst[i];
+        if (a >= n || b >= n)
+            return fail(ctx, GV_EINVAL, "edge %llu names node id >= n (%u)", (unsigned long long)i, n);
+        if (deg[a] == UINT32_MAX || deg[b] == UINT32_MAX) return fail(ctx, GV_EINVAL, "degree overflow");
+        ++deg[a];
+        ++deg[b];
+    }
+    return adopt_degrees(ctx, n, std::move(deg));
+}
+
+int gv_set_degrees(gv_ctx *ctx, uint32_t n, const uint32_t *host_deg) {
+    if (!ctx) return GV_EINVAL;
+    if (n == 0 || !host_deg) return fail(ctx, GV_EINVAL, "empty graph or null degree array");
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return adopt_degrees(ctx, n, std::vector<uint32_t>(host_deg, host_deg + n));
+}
+
+int gv_build_alias(gv_ctx *ctx, double power) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (power != 0.75 && power != 1.0 && power != 0.0)
+        return fail(ctx, GV_EINVAL, "power must be 0.75, 1.0 or 0.0");
+    const uint32_t n = ctx->n;
+    // scaled weights p_i = q_i * n / S, S accumulated in index order
+    std::vector<double> p(n);
+    double sum = 0.0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const double d = (double)ctx->degree[i];
+        double q;
+        if (power == 0.75) {
+            const double root = sqrt(d);
+            q = root * sqrt(root);
+        } else if (power == 1.0) {
+            q = d;
+        } else {
+            q = 1.0;
+        }
+        p[i] = q;
+        sum += q;
+    }
+    if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+    std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
+    below.reserve(n);
+    above.reserve(n);
+    for (uint32_t i = 0; i < n; ++i) {
+        p[i] = p[i] * (double)n / sum;
+        (p[i] < 1.0 ? below : above).push_back(i);
+    }
+    std::vector<uint2> table(n);
+    std::vector<double> keep(n, 1.0);
+    for (uint32_t i = 0; i < n; ++i) table[i].y = i;
+    while (!below.empty() && !above.empty()) {
+        const uint32_t poor = below.back();
+        below.pop_back();
+        const uint32_t rich = above.back();
+        above.pop_back();
+        keep[poor] = p[poor];
+        table[poor].y = rich;
+        p[rich] = (p[rich] + p[poor]) - 1.0;
+        (p[rich] < 1.0 ? below : above).push_back(rich);
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        const double scaled = floor(keep[i] * 4294967296.0);
+        table[i].x = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
+    }
+    rc = sync_all(ctx);
+    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint2), hipMemcpyHostToDevice));
+    ctx->alias_ready = true;
+    return GV_OK;
+}
+
+int gv_get_alias(gv_ctx *ctx, uint32_t *host_thresh, uint32_t *host_alias) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (!host_thresh || !host_alias) return fail(ctx, GV_EINVAL, "null output");
+    std::vector<uint2> table(ctx->n);
+    GV_HIP(ctx, hipMemcpy(table.data(), ctx->alias, (size_t)ctx->n * sizeof(uint2), hipMemcpyDeviceToHost));
+    for (uint32_t i = 0; i < ctx->n; ++i) {
+        host_thresh[i] = table[i].x;
+        host_alias[i] = table[i].y;
+    }
+    return GV_OK;
+}
+
+int gv_init_embeddings(gv_ctx *ctx, uint64_t seed) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    rc = sync_all(ctx);
+    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    GV_HIP(ctx, gv::launch_init_vertex(ctx->vertex, ctx->n, ctx->cfg.dim, seed, ctx->compute));
+    GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, (size_t)ctx->n * ctx->cfg.dim * sizeof(float), ctx->compute));
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    return GV_OK;
+}
+
+static int matrix_window(gv_ctx *ctx, int which, uint64_t row0, uint64_t rows, float **base) {
+    if (which != GV_VERTEX && which != GV_CONTEXT) return fail(ctx, GV_EINVAL, "which must be GV_VERTEX or GV_CONTEXT");
+    if (row0 > ctx->n || rows > ctx->n - row0)
+        return fail(ctx, GV_EINVAL, "rows [%llu, %llu) outside the matrix (%u rows)", (unsigned long long)row0,
+                    (unsigned long long)(row0 + rows), ctx->n);
+    *base = (which == GV_VERTEX ? ctx->vertex : ctx->context) + row0 * ctx->cfg.dim;
+    return GV_OK;
+}
+
+int gv_set_embeddings(gv_ctx *ctx, int which, const float *host_rows, uint64_t row0, uint64_t rows) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    float *base = nullptr;
+    rc = matrix_window(ctx, which, row0, rows, &base);
+    if (rc) return rc;
+    if (rows == 0) return GV_OK;
+    if (!host_rows) return fail(ctx, GV_EINVAL, "null input");
+    rc = sync_all(ctx);
+    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    GV_HIP(ctx, hipMemcpy(base, host_rows, rows * ctx->cfg.dim * sizeof(float), hipMemcpyHostToDevice));
+    return GV_OK;
+}
+
+int gv_read_embeddings(gv_ctx *ctx, int which, float *host_rows, uint64_t row0, uint64_t rows) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    float *base = nullptr;
+    rc = matrix_window(ctx, which, row0, rows, &base);
+    if (rc) return rc;
+    if (rows == 0) return GV_OK;
+    if (!host_rows) return fail(ctx, GV_EINVAL, "null output");
+    rc = sync_all(ctx);
+    if (rc) return rc;
+    GV_HIP(ctx, hipMemcpy(host_rows, base, rows * ctx->cfg.dim * sizeof(float), hipMemcpyDeviceToHost));
+    return GV_OK;
+}
+
+int gv_device_embeddings(gv_ctx *ctx, int which, float **dev_rows) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (!dev_rows) return fail(ctx, GV_EINVAL, "null output");
+    return matrix_window(ctx, which, 0, 0, dev_rows);
+}
+
+int gv_acquire_pool_slot(gv_ctx *ctx, uint32_t **host_pairs) {
+    if (!ctx || !host_pairs) return ctx ? fail(ctx, GV_EINVAL, "null output") : GV_EINVAL;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    int i = -1;
+    rc = pick_free_slot(ctx, &i);
+    if (rc) return rc;
+    ctx->slot[i].state = kFilling;
+    *host_pairs = ctx->slot[i].host;
+    return GV_OK;
+}
+
+int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (count > ctx->cfg.pool_capacity)
+        return fail(ctx, GV_EINVAL, "pool of %llu samples exceeds pool_capacity %llu", (unsigned long long)count,
+                    (unsigned long long)ctx->cfg.pool_capacity);
+    if (count > 0 && !host_pairs) return fail(ctx, GV_EINVAL, "null pool");
+    int i = -1;
+    for (int t = 0; t < 2; ++t)
+        if (ctx->slot[t].state == kFilling && ctx->slot[t].host == host_pairs) i = t;
+    if (i < 0) {
+        if (ctx->queued == 2) return fail(ctx, GV_ESTATE, "two pools already queued: train one first");
+        rc = pick_free_slot(ctx, &i);
+        if (rc) return rc;
+        memcpy(ctx->slot[i].host, host_pairs, count * 2 * sizeof(uint32_t));
+    }
+    PoolSlot &s = ctx->slot[i];
+    s.count = count;
+    TimedSpan span{};
+    const bool timed = ctx->cfg.profile != 0 && count > 0;
+    if (timed) {
+        rc = begin_span(ctx, 1, ctx->copy, &span);
+        if (rc) return rc;
+    }
+    if (count > 0)
+        GV_HIP(ctx, hipMemcpyAsync(s.dev, s.host, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->copy));
+    if (timed) {
+        rc = end_span(ctx, ctx->copy, span);
+        if (rc) return rc;
+    }
+    GV_HIP(ctx, hipEventRecord(s.copied, ctx->copy));
+    ctx->stats.h2d_bytes += count * 2 * sizeof(uint32_t);
+    s.state = kQueued;
+    ctx->queue[ctx->queued++] = i;
+    return GV_OK;
+}
+
+int gv_train_pool(gv_ctx *ctx) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (ctx->queued == 0) return fail(ctx, GV_ESTATE, "no pool queued: call gv_push_pool first");
+    const int i = ctx->queue[0];
+    ctx->queue[0] = ctx->queue[1];
+    ctx->queue[1] = -1;
+    --ctx->queued;
+    PoolSlot &s = ctx->slot[i];
+    GV_HIP(ctx, hipStreamWaitEvent(ctx->compute, s.copied, 0));
+    rc = train_any(ctx, s.dev, s.host, s.count);
+    if (rc) {
+        s.state = kFree;
+        return rc;
+    }
+    GV_HIP(ctx, hipEventRecord(s.trained, ctx->compute));
+    s.state = kTraining;
+    return GV_OK;
+}
+
+int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "at most 2^32-1 samples per call");
+    if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
+    return train_any(ctx, dev_pairs, nullptr, count);
+}
+
+int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (count == 0) return GV_OK;
+    if (!host_out) return fail(ctx, GV_EINVAL, "null output");
+    if (count > (1ull << 32)) return fail(ctx, GV_EINVAL, "at most 2^32 samples per call");
+    const uint32_t K = ctx->cfg.num_neg;
+    rc = ensure_negatives(ctx, count * K);
+    if (rc) return rc;
+    GV_HIP(ctx, gv::launch_draw_negatives(ctx->alias, ctx->n, ctx->cfg.seed, first_g, count, K, ctx->negatives,
+                                          ctx->compute));
+    GV_HIP(ctx, hipMemcpyAsync(host_out, ctx->negatives, count * K * sizeof(uint32_t), hipMemcpyDeviceToHost,
+                               ctx->compute));
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    return GV_OK;
+}
+
+int gv_sync(gv_ctx *ctx) {
+    if (!ctx) return GV_EINVAL;
+    int rc = bind_device(ctx);
+    if (rc) return rc;
+    return sync_all(ctx);
+}
+
+int gv_get_stats(gv_ctx *ctx, gv_stats *out) {
+    if (!ctx || !out) return ctx ? fail(ctx, GV_EINVAL, "null output") : GV_EINVAL;
+    *out = ctx->stats;
+    return GV_OK;
+}
+
+int gv_set_position(gv_ctx *ctx, uint64_t next_g) {
+    if (!ctx) return GV_EINVAL;
+    ctx->next_g = next_g;
+    ctx->stats.samples_trained = next_g;
+    return GV_OK;
+}
+
+}  // extern "C"

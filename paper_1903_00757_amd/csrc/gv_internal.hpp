@@ -1,0 +1,40 @@
+// Internal interface between the host runtime (gv_api.cpp) and the gfx950
+// kernels (gv_kernels.hip).  Not part of the C boundary.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gv {
+
+// Everything a training launch needs; passed by value as the kernel argument.
+struct TrainArgs {
+    float *vertex;            // |V| x d, row-major
+    float *context;           // |V| x d, row-major
+    const uint2 *alias;       // per node {threshold, alias}
+    const uint32_t *pairs;    // count x (u, v)
+    const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
+    uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
+    uint64_t first_g;         // global position of pairs[0]
+    uint64_t total;           // T of the learning-rate schedule
+    uint64_t seed;            // Philox key of the negative stream
+    uint32_t count;           // samples in this launch
+    uint32_t n;               // |V|
+    float lr0, lr_min_ratio, neg_weight;
+};
+
+// Launch shapes are chosen here; both return the HIP error of the launch.
+hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                hipStream_t stream);
+// One wave per sample over samples [0, a.count): the caller guarantees that no
+// two of them share a vertex row or a context row (negatives included).
+hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);
+// out[i*K + k] = negative k of positive sample first_g + i.
+hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
+                                 uint32_t num_neg, uint32_t *out, hipStream_t stream);
+// vertex ~ U(-0.5/d, 0.5/d) from Philox stream 1 (context is cleared by the caller).
+hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64_t seed, hipStream_t stream);
+
+bool supported_shape(uint32_t dim, uint32_t num_neg);
+
+}  // namespace gv

@@ -1,0 +1,429 @@
+// gfx950 kernels of the embedding-training hot path (GraphVite, arXiv 1903.00757).
+//
+// Work decomposition: one 64-lane wavefront owns one positive sample at a time.
+// A row of d floats is spread over the 64 lanes (d/64 floats per lane), so a row
+// gather or scatter is one fully coalesced request per 64 x 16 B, the dot product
+// is a per-lane partial followed by a cross-lane (DPP) reduction, and all node ids
+// and coefficients of the sample are wave-uniform scalars.
+#include "gv_internal.hpp"
+
+namespace gv {
+namespace {
+
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;  // 4 waves per workgroup
+// Row traffic policies (gv_config.coherence).
+constexpr int kPlain = 0;        // cached loads and stores
+constexpr int kAgent = 1;        // device-scope loads and stores
+constexpr int kAtomicAgent = 2;  // device-scope loads, updates as device-scope fp32 atomic adds
+constexpr int kAtomicL2 = 3;     // cached loads, updates as fp32 atomic adds resolved in the local L2
+constexpr bool is_atomic(int c) { return c == kAtomicAgent || c == kAtomicL2; }
+constexpr bool is_agent(int c) { return c == kAgent || c == kAtomicAgent; }
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
+// and a word permutation; the key advances by the Weyl constants between rounds.
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+// Negative k of positive sample g (Alg. 1, NegativeSampling; Sec. 4.3 alias
+// table): bucket = floor(R * n / 2^64) from the first two words, accepted when
+// the third word is below the bucket's threshold, else the bucket's alias.
+__device__ __forceinline__ uint32_t draw_negative(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
+                                                  uint64_t g, uint32_t k) {
+    const uint4 r = philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), k, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+    const uint64_t R = ((uint64_t)r.x << 32) | r.y;
+    const uint32_t j = (uint32_t)__umul64hi(R, (uint64_t)n);
+    const uint2 e = alias[j];
+    return r.z < e.x ? j : e.y;
+}
+
+// Learning rate of positive sample g (Sec. 4.3: linear decay from lr0), fp64 then fp32.
+__device__ __forceinline__ float learning_rate(float lr0, float lr_min_ratio, uint64_t g, uint64_t total) {
+    double f = 1.0 - (double)g / (double)total;
+    if (f < (double)lr_min_ratio) f = (double)lr_min_ratio;
+    return (float)((double)lr0 * f);
+}
+
+// ---------------------------------------------------------------------------
+// Cross-lane sum of a wave64 with DPP moves: quad butterflies, half-row and row
+// mirrors give every lane its 16-lane row sum; two row broadcasts carry the sums
+// to the last row; the result is read from lane 63 as a wave-uniform scalar.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_take(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, kRowMask, 0xF, false));
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+    x += dpp_take<0xB1, 0xF>(x);   // quad_perm [1,0,3,2]
+    x += dpp_take<0x4E, 0xF>(x);   // quad_perm [2,3,0,1]
+    x += dpp_take<0x141, 0xF>(x);  // row_half_mirror
+    x += dpp_take<0x140, 0xF>(x);  // row_mirror
+    x += dpp_take<0x142, 0xA>(x);  // row_bcast15 into rows 1 and 3
+    x += dpp_take<0x143, 0xC>(x);  // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ uint32_t lane_value(uint32_t x, uint32_t lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, (int)lane);
+}
+
+// ---------------------------------------------------------------------------
+// Row <-> registers.  A lane holds kV floats of the row in segments: plain
+// accesses use 16-byte segments when the row allows, device-scope accesses use
+// 8-byte segments (the widest single-copy-atomic access).  Element e of segment
+// s sits at row[s * 64 * W + lane * W + e], so each segment is one contiguous
+// 64 * W * 4 byte request per wave.
+template <int kV, int kCoherence>
+struct RowIo {
+    // atomic adds work on single floats: one float per lane and segment keeps every
+    // atomic instruction on 256 contiguous bytes
+    static constexpr int W = is_atomic(kCoherence) ? 1 : is_agent(kCoherence) ? (kV >= 2 ? 2 : 1) : (kV >= 4 ? 4 : kV);
+    static constexpr int S = kV / W;
+
+    static __device__ __forceinline__ void load(const float *row, int lane, float (&x)[kV]) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const float *p = row + s * (kWave * W) + lane * W;
+            if constexpr (is_agent(kCoherence)) {
+                if constexpr (W == 2) {
+                    const uint64_t bits =
+                        __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    x[s * W] = __uint_as_float((uint32_t)bits);
+                    x[s * W + 1] = __uint_as_float((uint32_t)(bits >> 32));
+                } else {
+                    x[s] = __uint_as_float(
+                        __hip_atomic_load((const uint32_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                }
+            } else if constexpr (W == 4) {
+                const f4 t = *(const f4 *)p;
+                x[s * 4] = t.x; x[s * 4 + 1] = t.y; x[s * 4 + 2] = t.z; x[s * 4 + 3] = t.w;
+            } else if constexpr (W == 2) {
+                const f2 t = *(const f2 *)p;
+                x[s * 2] = t.x; x[s * 2 + 1] = t.y;
+            } else {
+                x[s] = *p;
+            }
+        }
+    }
+
+    // row += delta without losing concurrent updates of other waves
+    static __device__ __forceinline__ void add(float *row, int lane, const float (&delta)[kV]) {
+        static_assert(W == 1, "atomic adds use the one-float-per-lane layout");
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            float *p = row + s * kWave + lane;
+            if constexpr (kCoherence == kAtomicAgent)
+                (void)__hip_atomic_fetch_add(p, delta[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                (void)__hip_atomic_fetch_add(p, delta[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+
+    static __device__ __forceinline__ void store(float *row, int lane, const float (&x)[kV]) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            float *p = row + s * (kWave * W) + lane * W;
+            if constexpr (is_agent(kCoherence)) {
+                if constexpr (W == 2) {
+                    const uint64_t bits =
+                        (uint64_t)__float_as_uint(x[s * W]) | ((uint64_t)__float_as_uint(x[s * W + 1]) << 32);
+                    __hip_atomic_store((uint64_t *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    __hip_atomic_store((uint32_t *)p, __float_as_uint(x[s]), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else if constexpr (W == 4) {
+                f4 t = {x[s * 4], x[s * 4 + 1], x[s * 4 + 2], x[s * 4 + 3]};
+                *(f4 *)p = t;
+            } else if constexpr (W == 2) {
+                f2 t = {x[s * 2], x[s * 2 + 1]};
+                *(f2 *)p = t;
+            } else {
+                *p = x[s];
+            }
+        }
+    }
+};
+
+__device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+// One positive sample with its K negatives (Alg. 1, the Train calls; Sec. 2.1
+// scores; Sec. 4.3 negative weight): rows[0] is the positive context row v,
+// rows[1..K] the negatives.  All 1+K scores come from the rows as loaded, then
+//   vertex[u]      += sum_k coef_k * context[rows_k]
+//   context[rows_k] += coef_k * vertex[u]
+// with coef_0 = lr (1 - sigmoid(s_0)), coef_k = -lr w sigmoid(s_k).  A context
+// row named more than once in the sample is written once with the summed
+// coefficient.  u and rows[] are wave-uniform.
+template <int kV, int kK, int kCoherence>
+__device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__restrict__ context, uint32_t u,
+                                          const uint32_t (&rows)[kK + 1], float lr, float w, int lane) {
+    constexpr int D = kV * kWave;
+    using Io = RowIo<kV, kCoherence>;
+    float *xp = vertex + (size_t)u * D;
+    float x[kV];
+    float c[kK + 1][kV];
+    Io::load(xp, lane, x);
+#pragma unroll
+    for (int k = 0; k <= kK; ++k) Io::load(context + (size_t)rows[k] * D, lane, c[k]);
+
+    float coef[kK + 1];
+#pragma unroll
+    for (int k = 0; k <= kK; ++k) {
+        float partial = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kV; ++j) partial = fmaf(x[j], c[k][j], partial);
+        const float score = wave_sum(partial);
+        coef[k] = k == 0 ? lr * (1.0f - sigmoid(score)) : -(lr * w) * sigmoid(score);
+    }
+
+    float dx[kV];
+#pragma unroll
+    for (int j = 0; j < kV; ++j) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], c[k][j], acc);
+        dx[j] = acc;
+    }
+
+#pragma unroll
+    for (int k = 0; k <= kK; ++k) {
+        bool repeated = false;
+#pragma unroll
+        for (int k2 = 0; k2 < k; ++k2) repeated |= rows[k2] == rows[k];
+        if (repeated) continue;  // wave-uniform: already folded into its first occurrence
+        float total = coef[k];
+#pragma unroll
+        for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
+        if constexpr (is_atomic(kCoherence)) {
+            float dc[kV];
+#pragma unroll
+            for (int j = 0; j < kV; ++j) dc[j] = total * x[j];
+            Io::add(context + (size_t)rows[k] * D, lane, dc);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kV; ++j) c[k][j] = fmaf(total, x[j], c[k][j]);
+            Io::store(context + (size_t)rows[k] * D, lane, c[k]);
+        }
+    }
+    if constexpr (is_atomic(kCoherence)) {
+        Io::add(xp, lane, dx);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kV; ++j) dx[j] += x[j];
+        Io::store(xp, lane, dx);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Asynchronous (Hogwild) training of one pool.  A wave takes chunks of 64
+// consecutive samples: lane l reads sample l of the chunk (one coalesced 512 B
+// read), draws that sample's negatives and learning rate, and the wave then
+// walks the 64 samples in order, fetching each one's ids from the owning lane.
+template <int kV, int kK, int kCoherence>
+__global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
+    const uint32_t waves = gridDim.x * (kBlock / kWave);
+    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
+
+    for (uint32_t chunk = wave; chunk < chunks; chunk += waves) {
+        const uint32_t base = chunk * kWave;
+        const uint32_t in_chunk = min((uint32_t)kWave, a.count - base);
+        const bool mine = (uint32_t)lane < in_chunk;
+        const uint2 p = mine ? pairs[base + lane] : make_uint2(0u, 0u);
+        const uint64_t g = a.first_g + base + lane;
+        uint32_t neg[kK];
+#pragma unroll
+        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
+        const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
+        if (mine && (p.x >= a.n || p.y >= a.n)) *a.error_flag = 1u;
+
+        for (uint32_t i = 0; i < in_chunk; ++i) {
+            const uint32_t u = lane_value(p.x, i);
+            uint32_t rows[kK + 1];
+            rows[0] = lane_value(p.y, i);
+            if (u >= a.n || rows[0] >= a.n) continue;  // reported through error_flag
+#pragma unroll
+            for (int k = 0; k < kK; ++k) rows[k + 1] = lane_value(neg[k], i);
+            const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
+            sgns_step<kV, kK, kCoherence>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane);
+        }
+    }
+}
+
+// Deterministic mode: wave i trains sample i of a batch whose samples share no
+// vertex row and no context row (Def. 1, Sec. 3.2: such samples commute), so the
+// result equals the sequential order up to fp32 rounding inside a sample.
+template <int kV, int kK>
+__global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t i = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
+    if (i >= a.count) return;
+    const uint32_t u = a.pairs[2 * (size_t)i];
+    uint32_t rows[kK + 1];
+    rows[0] = a.pairs[2 * (size_t)i + 1];
+    if (u >= a.n || rows[0] >= a.n) {
+        *a.error_flag = 1u;
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < kK; ++k) rows[k + 1] = a.negatives[(size_t)i * kK + k];
+    const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + i, a.total);
+    sgns_step<kV, kK, kPlain>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane);
+}
+
+__global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
+                                                           uint64_t first_g, uint64_t count, uint32_t num_neg,
+                                                           uint32_t *__restrict__ out) {
+    const uint64_t total = count * num_neg;
+    for (uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x; t < total; t += (uint64_t)gridDim.x * kBlock) {
+        const uint64_t i = t / num_neg;
+        const uint32_t k = (uint32_t)(t - i * num_neg);
+        out[t] = draw_negative(alias, n, seed, first_g + i, k);
+    }
+}
+
+// vertex[row][4b .. 4b+3] from the four words of Philox block (row, b) of stream 1:
+// ((word + 0.5) / 2^32 - 0.5) / d, evaluated in fp64.
+__global__ __launch_bounds__(kBlock) void k_init_vertex(float *__restrict__ vertex, uint64_t rows, uint32_t dim,
+                                                        uint64_t seed) {
+    const uint32_t blocks_per_row = dim / 4;
+    const uint64_t total = rows * blocks_per_row;
+    for (uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x; t < total; t += (uint64_t)gridDim.x * kBlock) {
+        const uint64_t row = t / blocks_per_row;
+        const uint32_t b = (uint32_t)(t - row * blocks_per_row);
+        const uint4 r = philox4x32_10((uint32_t)row, (uint32_t)(row >> 32), b, 1u, (uint32_t)seed,
+                                      (uint32_t)(seed >> 32));
+        const double inv = 1.0 / 4294967296.0;
+        f4 out;
+        out.x = (float)((((double)r.x + 0.5) * inv - 0.5) / (double)dim);
+        out.y = (float)((((double)r.y + 0.5) * inv - 0.5) / (double)dim);
+        out.z = (float)((((double)r.z + 0.5) * inv - 0.5) / (double)dim);
+        out.w = (float)((((double)r.w + 0.5) * inv - 0.5) / (double)dim);
+        *(f4 *)(vertex + row * dim + 4 * (uint64_t)b) = out;
+    }
+}
+
+uint32_t env_u32(const char *name, uint32_t fallback) {
+    const char *s = getenv(name);
+    if (!s || !*s) return fallback;
+    const long v = strtol(s, nullptr, 10);
+    return v > 0 ? (uint32_t)v : fallback;
+}
+
+template <int kV, int kK>
+hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
+    // Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy;
+    // each wave strides over the chunks.  GV_GRID_BLOCKS overrides for tuning sweeps.
+    // The number of samples in flight is also kept below |V|/8: every in-flight sample
+    // works on values that miss the updates of the others (Def. 1, Sec. 3.2: the order of
+    // updates stops mattering only while concurrent samples rarely share rows), and a
+    // small graph gains nothing from thousands of waves.
+    static const uint32_t max_blocks = env_u32("GV_GRID_BLOCKS", 256u * 8u);
+    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint32_t wanted = (chunks + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const uint32_t by_rows = (a.n / 8u) / (kBlock / kWave);
+    uint32_t blocks = wanted < max_blocks ? wanted : max_blocks;
+    if (blocks > by_rows) blocks = by_rows > 64u ? by_rows : (blocks < 64u ? blocks : 64u);
+    if (blocks == 0) return hipSuccess;
+    switch (coherence) {
+        case kAgent:
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            break;
+        case kAtomicAgent:
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            break;
+        case kAtomicL2:
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicL2>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            break;
+        default:
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+template <int kV, int kK>
+hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
+    if (a.count == 0) return hipSuccess;
+    const uint32_t blocks = (a.count + (kBlock / kWave) - 1) / (kBlock / kWave);
+    hipLaunchKernelGGL((k_train_batch<kV, kK>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool supported_shape(uint32_t dim, uint32_t num_neg) {
+    return (dim == 64 || dim == 128 || dim == 256 || dim == 512) && num_neg >= 1 && num_neg <= 5;
+}
+
+#define GV_DISPATCH_K(V, CALL)                 \
+    switch (num_neg) {                         \
+        case 1: return CALL(V, 1);             \
+        case 2: return CALL(V, 2);             \
+        case 3: return CALL(V, 3);             \
+        case 4: return CALL(V, 4);             \
+        case 5: return CALL(V, 5);             \
+        default: return hipErrorInvalidValue;  \
+    }
+#define GV_DISPATCH(CALL)                           \
+    switch (dim) {                                  \
+        case 64: GV_DISPATCH_K(1, CALL)             \
+        case 128: GV_DISPATCH_K(2, CALL)            \
+        case 256: GV_DISPATCH_K(4, CALL)            \
+        case 512: GV_DISPATCH_K(8, CALL)            \
+        default: return hipErrorInvalidValue;       \
+    }
+
+hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                hipStream_t stream) {
+#define GV_CALL(V, K) launch_hogwild_vk<V, K>(a, coherence, stream)
+    GV_DISPATCH(GV_CALL)
+#undef GV_CALL
+}
+
+hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream) {
+#define GV_CALL(V, K) launch_batch_vk<V, K>(a, stream)
+    GV_DISPATCH(GV_CALL)
+#undef GV_CALL
+}
+
+hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
+                                 uint32_t num_neg, uint32_t *out, hipStream_t stream) {
+    const uint64_t total = count * num_neg;
+    if (total == 0) return hipSuccess;
+    const uint64_t wanted = (total + kBlock - 1) / kBlock;
+    const uint32_t blocks = (uint32_t)(wanted < 65536 ? wanted : 65536);
+    hipLaunchKernelGGL(k_draw_negatives, dim3(blocks), dim3(kBlock), 0, stream, alias, n, seed, first_g, count,
+                       num_neg, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64_t seed, hipStream_t stream) {
+    const uint64_t total = rows * (dim / 4);
+    if (total == 0) return hipSuccess;
+    const uint64_t wanted = (total + kBlock - 1) / kBlock;
+    const uint32_t blocks = (uint32_t)(wanted < 65536 ? wanted : 65536);
+    hipLaunchKernelGGL(k_init_vertex, dim3(blocks), dim3(kBlock), 0, stream, vertex, rows, dim, seed);
+    return hipGetLastError();
+}
+
+}  // namespace gv

@@ -18,7 +18,9 @@ CONFIGS = {
                neg_weight=1.0, total_samples=1_000_000_000, pool=1 << 24, graph_seed=2),
     "c4": dict(number=4, graph="planted_partition", n=4_000_000, communities=400, edges=40_000_000,
                ratio=50.0, dim=128, num_neg=1, neg_weight=5.0, total_samples=4_000_000_000, pool=1 << 24),
-    "c4-small": dict(number=4, graph="planted_partition", n=40_000, communities=40, edges=400_000,
+    # scaled-down stand-in for c4 that the sequential oracle finishes in seconds and that is
+    # trained to its plateau (1600 samples per node), so that quality comparisons are stable
+    "c4-small": dict(number=4, graph="planted_partition", n=5_000, communities=10, edges=50_000,
                      ratio=50.0, dim=128, num_neg=1, neg_weight=5.0, total_samples=8_000_000, pool=1 << 20),
     "c5": dict(number=5, graph="chung_lu", n=66_000_000, edges=1_800_000_000, gamma=2.2, dim=128, num_neg=1,
                neg_weight=5.0, total_samples=10_000_000_000, pool=1 << 24),
