@@ -57,10 +57,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "tiny"])
     ap.add_argument("--pools", type=int, default=8, help="distinct pre-generated pools cycled through")
-    ap.add_argument("--coherence", type=int, default=int(os.environ.get("GV_BENCH_COHERENCE", "2")))
+    ap.add_argument("--coherence", type=int, default=int(os.environ.get("GV_BENCH_COHERENCE", "3")))
+    ap.add_argument("--schedule", type=int, default=int(os.environ.get("GV_BENCH_SCHEDULE", "1")))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streamed", action="store_true")
     ap.add_argument("--cpu-samples", type=int, default=1 << 22)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
@@ -91,7 +94,8 @@ def main():
     torch.cuda.synchronize()
 
     ctx = gv.gv_create(dim=dim, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=total,
-                       seed=W.configs.TRAIN_SEED, pool_capacity=P, coherence=args.coherence, profile=1)
+                       seed=W.configs.TRAIN_SEED, pool_capacity=P, coherence=args.coherence, schedule=args.schedule,
+                       profile=1)
     try:
         gv.gv_set_degrees(ctx, deg)
         gv.gv_build_alias(ctx, 0.75)
@@ -115,10 +119,12 @@ def main():
         after = gv.gv_get_stats(ctx)
         launches = after["timed_launches"] - before["timed_launches"]
         kernel_ms = (after["train_kernel_ms"] - before["train_kernel_ms"]) / max(launches, 1)
+        group_ms = (after["group_ms"] - before["group_ms"]) / max(launches, 1)
         value = args.steps * P / wall
         bytes_per_sample = algorithmic_bytes_per_sample(dim, K)
         achieved = bytes_per_sample * P / (kernel_ms * 1e-3) / 1e9
-        log(f"resident: {value:.4g} samples/s, kernel {kernel_ms:.3f} ms/launch, {achieved:.0f} GB/s algorithmic")
+        log(f"resident: {value:.4g} samples/s, train kernel {kernel_ms:.3f} ms/launch (+ grouping {group_ms:.3f} ms), "
+            f"{achieved:.0f} GB/s algorithmic")
 
         streamed = None
         if not args.no_streamed:
@@ -148,6 +154,15 @@ def main():
     finally:
         gv.gv_destroy(ctx)
 
+    if args.calibrate_copy:
+        src_t = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst_t = torch.empty_like(src_t)
+        for _ in range(3):
+            dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        log("calibration: 3 device copies of 1 GiB done")
+        del src_t, dst_t
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(n, deg, pools[0], dim, K, w, total, W.configs.TRAIN_SEED, args.cpu_samples)
@@ -162,10 +177,12 @@ def main():
         "config": {"workload": f"{args.workload}: {cfg['graph']} n={n} edges={src.size}, d={dim}, K={K}, "
                                f"neg_weight={w}, pool=2^{int(np.log2(P))} samples resident in HBM, "
                                f"{args.pools} distinct walk pools (L=40, s=5) cycled, Hogwild",
-                   "coherence": ["plain", "agent", "atomic-agent", "atomic-l2"][args.coherence], "samples_per_step": P},
+                   "coherence": ["plain", "agent", "atomic-agent", "mixed"][args.coherence],
+                   "schedule": ["pool-order", "grouped"][args.schedule], "samples_per_step": P},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_train_hogwild", "kernel_ms": kernel_ms, "bytes_per_sample": bytes_per_sample},
+                     "kernel": "k_train_grouped" if args.schedule else "k_train_hogwild", "kernel_ms": kernel_ms,
+                     "bytes_per_sample": bytes_per_sample, "grouping_ms_per_launch": group_ms},
         "cpu_baseline": cpu,
         "streamed": streamed,
     }

@@ -41,11 +41,28 @@ typedef struct gv_ctx gv_ctx;
 enum { GV_OK = 0, GV_EINVAL = -1, GV_ENOMEM = -2, GV_ESTATE = -3, GV_EHIP = -4 };
 enum { GV_MODE_HOGWILD = 0, GV_MODE_DETERMINISTIC = 1 };
 enum { GV_VERTEX = 0, GV_CONTEXT = 1 };
-/* How embedding rows travel between compute units and memory while a training
- * kernel runs.  PLAIN: ordinary cached accesses (each XCD's L2 holds its own
- * copy of a hot row until the kernel ends).  AGENT: device-scope accesses, so
- * an update made on one XCD is seen by the others within the same kernel.     */
-enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT = 2, GV_COHERENCE_ATOMIC_L2 = 3 };
+/* How embedding rows travel between compute units and memory while an
+ * asynchronous training kernel runs.
+ *   PLAIN        ordinary cached loads and stores: fastest, but a compute unit keeps
+ *                reading its own cached copy of a hot row, so concurrent updates of
+ *                shared rows are mostly lost (kept for measurement only).
+ *   AGENT        device-scope loads and stores: every wave sees the others' updates,
+ *                but two waves updating one row at the same time lose one update
+ *                (classic lock-free asynchronous SGD).
+ *   ATOMIC_AGENT device-scope loads, updates applied as fp32 atomic adds: no update
+ *                is ever lost, reads may be slightly stale.
+ *   MIXED        ATOMIC_AGENT for rows likely to be shared by concurrent samples,
+ *                AGENT stores for the rest (grouped schedule only; otherwise it
+ *                behaves as ATOMIC_AGENT).                                            */
+enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT = 2, GV_COHERENCE_MIXED = 3 };
+/* Order in which an asynchronous launch walks a pool.
+ *   POOL_ORDER   waves take chunks of 64 consecutive samples.
+ *   GROUPED      inside tiles of the pool, samples are sorted by their hotter row
+ *                (the higher-degree one of u, v); a wave keeps that row in
+ *                registers across the run of samples that share it and adds the
+ *                run's total change to memory once.  Each sample keeps the
+ *                negatives and learning rate of its position in the pool.          */
+enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_GROUPED = 1 };
 
 typedef struct gv_config {
     uint32_t dim;            /* d: 64, 128, 256 or 512                                        */
@@ -61,7 +78,7 @@ typedef struct gv_config {
     int32_t device;          /* HIP device ordinal                                             */
     uint32_t coherence;      /* GV_COHERENCE_*                                                 */
     uint32_t profile;        /* nonzero: time every training launch with HIP events            */
-    uint32_t reserved;       /* must be 0                                                      */
+    uint32_t schedule;       /* GV_SCHEDULE_* (asynchronous mode)                              */
 } gv_config;
 
 typedef struct gv_stats {
@@ -74,6 +91,7 @@ typedef struct gv_stats {
     uint64_t timed_launches;    /* launches contributing to train_kernel_ms                    */
     double h2d_ms;              /* event-timed pool copies host -> device (profile != 0)        */
     uint64_t h2d_bytes;
+    double group_ms;            /* event-timed pool grouping (key build + sort), grouped schedule */
 } gv_stats;
 
 /* Create a context on cfg->device.  Allocates the pool slots only; the graph

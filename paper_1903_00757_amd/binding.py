@@ -13,7 +13,8 @@ import numpy as np
 GV_OK, GV_EINVAL, GV_ENOMEM, GV_ESTATE, GV_EHIP = 0, -1, -2, -3, -4
 GV_MODE_HOGWILD, GV_MODE_DETERMINISTIC = 0, 1
 GV_VERTEX, GV_CONTEXT = 0, 1
-GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_ATOMIC_L2 = 0, 1, 2, 3
+GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_MIXED = 0, 1, 2, 3
+GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_GROUPED = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
 
@@ -31,7 +32,7 @@ class gv_config(C.Structure):
         ("lr0", C.c_float), ("lr_min_ratio", C.c_float), ("neg_weight", C.c_float),
         ("mode", C.c_uint32),
         ("total_samples", C.c_uint64), ("seed", C.c_uint64), ("pool_capacity", C.c_uint64),
-        ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("reserved", C.c_uint32),
+        ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("schedule", C.c_uint32),
     ]
 
 
@@ -39,7 +40,7 @@ class gv_stats(C.Structure):
     _fields_ = [
         ("samples_trained", C.c_uint64), ("pools_trained", C.c_uint64), ("train_launches", C.c_uint64),
         ("batches", C.c_uint64), ("train_kernel_ms", C.c_double), ("timed_launches", C.c_uint64),
-        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64),
+        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("group_ms", C.c_double),
     ]
 
     def as_dict(self):
@@ -104,11 +105,12 @@ def _u32(a):
 
 
 def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=None, mode=GV_MODE_HOGWILD,
-              total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_ATOMIC_AGENT, profile=0):
+              total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_MIXED, profile=0,
+              schedule=GV_SCHEDULE_GROUPED):
     cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio,
                     neg_weight=(5.0 / max(num_neg, 1) if neg_weight is None else neg_weight), mode=mode,
                     total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,
-                    coherence=coherence, profile=profile, reserved=0)
+                    coherence=coherence, profile=profile, schedule=schedule)
     ctx = C.c_void_p()
     rc = load().gv_create(C.byref(cfg), C.byref(ctx))
     _check(None, rc)

@@ -32,7 +32,7 @@ struct PoolSlot {
 
 struct TimedSpan {
     hipEvent_t start, stop;
-    int kind;  // 0 training launch, 1 host-to-device copy
+    int kind;  // 0 training launch, 1 host-to-device copy, 2 pool grouping (key build + sort)
 };
 
 }  // namespace
@@ -45,6 +45,12 @@ struct gv_ctx {
     float *context = nullptr;
     uint2 *alias = nullptr;
     bool alias_ready = false;
+    uint32_t *dev_degree = nullptr;       // device copy of the degrees (grouping key)
+    uint8_t *dev_warm = nullptr;          // device, per node: updates must not be lost
+    uint32_t *group_buf[4] = {nullptr, nullptr, nullptr, nullptr};  // keys in, values in, keys out, values out
+    void *sort_scratch = nullptr;
+    size_t sort_bytes = 0;
+    uint64_t group_capacity = 0;          // samples the grouping buffers hold
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
@@ -107,8 +113,10 @@ void fold_spans(gv_ctx *ctx) {
             if (s.kind == 0) {
                 ctx->stats.train_kernel_ms += ms;
                 ctx->stats.timed_launches += 1;
-            } else {
+            } else if (s.kind == 1) {
                 ctx->stats.h2d_ms += ms;
+            } else {
+                ctx->stats.group_ms += ms;
             }
         }
         ctx->spare_events.push_back(s.start);
@@ -136,8 +144,12 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->vertex) (void)hipFree(ctx->vertex);
     if (ctx->context) (void)hipFree(ctx->context);
     if (ctx->alias) (void)hipFree(ctx->alias);
+    if (ctx->dev_degree) (void)hipFree(ctx->dev_degree);
+    if (ctx->dev_warm) (void)hipFree(ctx->dev_warm);
     ctx->vertex = ctx->context = nullptr;
     ctx->alias = nullptr;
+    ctx->dev_degree = nullptr;
+    ctx->dev_warm = nullptr;
     ctx->alias_ready = false;
 }
 
@@ -150,6 +162,10 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     GV_HIP(ctx, hipMalloc((void **)&ctx->vertex, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->context, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint2)));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_degree, (size_t)n * sizeof(uint32_t)));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_warm, (size_t)n));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_degree, deg.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemset(ctx->dev_warm, 1, (size_t)n));
     GV_HIP(ctx, hipMemsetAsync(ctx->vertex, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
@@ -193,6 +209,7 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.alias = ctx->alias;
     a.pairs = dev_pairs;
     a.negatives = nullptr;
+    a.warm = ctx->dev_warm;
     a.error_flag = ctx->error_flag;
     a.first_g = first_g;
     a.total = ctx->cfg.total_samples;
@@ -225,16 +242,60 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
     return GV_OK;
 }
 
-// Asynchronous training of `count` samples at dev_pairs: one launch.
+int ensure_group_buffers(gv_ctx *ctx, uint64_t count) {
+    if (count <= ctx->group_capacity) return GV_OK;
+    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    for (uint32_t *&b : ctx->group_buf) {
+        if (b) (void)hipFree(b);
+        b = nullptr;
+    }
+    if (ctx->sort_scratch) (void)hipFree(ctx->sort_scratch);
+    ctx->sort_scratch = nullptr;
+    ctx->group_capacity = 0;
+    for (uint32_t *&b : ctx->group_buf) GV_HIP(ctx, hipMalloc((void **)&b, count * sizeof(uint32_t)));
+    GV_HIP(ctx, gv::group_scratch_bytes(count, &ctx->sort_bytes));
+    GV_HIP(ctx, hipMalloc(&ctx->sort_scratch, ctx->sort_bytes ? ctx->sort_bytes : 16));
+    ctx->group_capacity = count;
+    return GV_OK;
+}
+
+// Asynchronous training of `count` samples at dev_pairs.  Grouped schedule: the pool is
+// first sorted, inside tiles, by the hotter row of each sample, and trained by the
+// stationary-row kernel; otherwise one launch walks the pool in its own order.
 int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     TimedSpan span{};
     const bool timed = ctx->cfg.profile != 0;
-    if (timed) {
-        int rc = begin_span(ctx, 0, ctx->compute, &span);
+    const gv::GroupPlan plan =
+        ctx->cfg.schedule == GV_SCHEDULE_GROUPED ? gv::plan_grouping(count, ctx->n) : gv::GroupPlan{};
+    if (plan.valid) {
+        int rc = ensure_group_buffers(ctx, count);
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+    if (plan.valid) {
+        TimedSpan sort_span{};
+        if (timed) {
+            int rc = begin_span(ctx, 2, ctx->compute, &sort_span);
+            if (rc) return rc;
+        }
+        GV_HIP(ctx, gv::launch_group(plan, dev_pairs, count, ctx->n, ctx->dev_degree, ctx->group_buf[0],
+                                     ctx->group_buf[1], ctx->group_buf[2], ctx->group_buf[3], ctx->sort_scratch,
+                                     ctx->sort_bytes, ctx->compute));
+        if (timed) {
+            int rc = end_span(ctx, ctx->compute, sort_span);
+            if (rc) return rc;
+            rc = begin_span(ctx, 0, ctx->compute, &span);
+            if (rc) return rc;
+        }
+        GV_HIP(ctx, gv::launch_train_grouped(a, ctx->group_buf[3], ctx->cfg.dim, ctx->cfg.num_neg,
+                                             ctx->cfg.coherence, ctx->compute));
+    } else {
+        if (timed) {
+            int rc = begin_span(ctx, 0, ctx->compute, &span);
+            if (rc) return rc;
+        }
+        GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+    }
     ctx->stats.train_launches += 1;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
@@ -360,8 +421,9 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
     if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
     if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 32))
         return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^32 samples");
-    if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_ATOMIC_L2 || cfg->reserved != 0)
-        return fail(nullptr, GV_EINVAL, "bad mode / coherence / reserved field");
+    if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
+        cfg->schedule > GV_SCHEDULE_GROUPED)
+        return fail(nullptr, GV_EINVAL, "bad mode / coherence / schedule field");
     if (!(cfg->lr0 >= 0.0f) || !(cfg->lr_min_ratio >= 0.0f) || !(cfg->neg_weight >= 0.0f) || !isfinite(cfg->lr0) ||
         !isfinite(cfg->neg_weight))
         return fail(nullptr, GV_EINVAL, "lr0, lr_min_ratio and neg_weight must be finite and >= 0");
@@ -418,6 +480,9 @@ void gv_destroy(gv_ctx *ctx) {
     }
     free_matrices(ctx);
     if (ctx->negatives) (void)hipFree(ctx->negatives);
+    for (uint32_t *b : ctx->group_buf)
+        if (b) (void)hipFree(b);
+    if (ctx->sort_scratch) (void)hipFree(ctx->sort_scratch);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
     if (ctx->compute) (void)hipStreamDestroy(ctx->compute);
@@ -457,7 +522,8 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     const uint32_t n = ctx->n;
     // scaled weights p_i = q_i * n / S, S accumulated in index order
     std::vector<double> p(n);
-    double sum = 0.0;
+    double sum = 0.0, degree_sum = 0.0;
+    for (uint32_t i = 0; i < n; ++i) degree_sum += (double)ctx->degree[i];
     for (uint32_t i = 0; i < n; ++i) {
         const double d = (double)ctx->degree[i];
         double q;
@@ -473,6 +539,15 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         sum += q;
     }
     if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+    // A row is warm when, with kInFlight samples being processed at once, the chance that
+    // another of them names the same row (as a walk endpoint, share deg/sum(deg), or as a
+    // negative, share q/sum(q)) exceeds 2 %: the mixed policy then updates it with atomic adds.
+    const double kInFlight = 8192.0;
+    std::vector<uint8_t> warm(n);
+    for (uint32_t i = 0; i < n; ++i) {
+        const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
+        warm[i] = share * kInFlight > 0.02 ? 1 : 0;
+    }
     std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
     below.reserve(n);
     above.reserve(n);
@@ -500,6 +575,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     rc = sync_all(ctx);
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
     GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint2), hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_warm, warm.data(), (size_t)n, hipMemcpyHostToDevice));
     ctx->alias_ready = true;
     return GV_OK;
 }

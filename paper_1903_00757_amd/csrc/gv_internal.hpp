@@ -14,6 +14,7 @@ struct TrainArgs {
     const uint2 *alias;       // per node {threshold, alias}
     const uint32_t *pairs;    // count x (u, v)
     const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
+    const uint8_t *warm;      // per node: 1 = updates of this row must not be lost (see gv_build_alias)
     uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
     uint64_t first_g;         // global position of pairs[0]
     uint64_t total;           // T of the learning-rate schedule
@@ -26,6 +27,25 @@ struct TrainArgs {
 // Launch shapes are chosen here; both return the HIP error of the launch.
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
                                 hipStream_t stream);
+// Stationary-row training: order[i] = position in a.pairs of the i-th sample to process
+// (bits 0..30) and its stationary side (bit 31: 0 vertex[u], 1 context[v]); samples with
+// the same stationary row are adjacent.
+hipError_t launch_train_grouped(const TrainArgs &a, const uint32_t *order, uint32_t dim, uint32_t num_neg,
+                                uint32_t coherence, hipStream_t stream);
+
+// How a pool is cut into tiles and keyed for grouping (32-bit keys).
+struct GroupPlan {
+    bool valid;
+    uint32_t tile_shift;  // tile = 2^tile_shift samples
+    uint32_t id_bits;     // bits of a node id
+    uint32_t key_bits;    // id_bits + 1 (side) + tile index bits
+};
+GroupPlan plan_grouping(uint64_t count, uint32_t n);
+hipError_t group_scratch_bytes(uint64_t count, size_t *sort_bytes);
+// keys/values in -> sorted out; values_out is the `order` array of launch_train_grouped.
+hipError_t launch_group(const GroupPlan &plan, const uint32_t *pairs, uint64_t count, uint32_t n,
+                        const uint32_t *degree, uint32_t *keys_in, uint32_t *values_in, uint32_t *keys_out,
+                        uint32_t *values_out, void *sort_scratch, size_t sort_bytes, hipStream_t stream);
 // One wave per sample over samples [0, a.count): the caller guarantees that no
 // two of them share a vertex row or a context row (negatives included).
 hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);

@@ -19,9 +19,9 @@ constexpr int kBlock = 256;  // 4 waves per workgroup
 constexpr int kPlain = 0;        // cached loads and stores
 constexpr int kAgent = 1;        // device-scope loads and stores
 constexpr int kAtomicAgent = 2;  // device-scope loads, updates as device-scope fp32 atomic adds
-constexpr int kAtomicL2 = 3;     // cached loads, updates as fp32 atomic adds resolved in the local L2
-constexpr bool is_atomic(int c) { return c == kAtomicAgent || c == kAtomicL2; }
-constexpr bool is_agent(int c) { return c == kAgent || c == kAtomicAgent; }
+constexpr int kMixed = 3;        // as kAtomicAgent for rows flagged warm, plain device-scope store otherwise
+constexpr bool is_atomic(int c) { return c == kAtomicAgent || c == kMixed; }
+constexpr bool is_agent(int c) { return c == kAgent || c == kAtomicAgent || c == kMixed; }
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
@@ -123,16 +123,16 @@ struct RowIo {
         }
     }
 
-    // row += delta without losing concurrent updates of other waves
+    // row += delta without losing concurrent updates of other waves (fp32 atomic add per
+    // element; with W = 1 every instruction covers 256 contiguous bytes)
     static __device__ __forceinline__ void add(float *row, int lane, const float (&delta)[kV]) {
-        static_assert(W == 1, "atomic adds use the one-float-per-lane layout");
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            float *p = row + s * kWave + lane;
-            if constexpr (kCoherence == kAtomicAgent)
-                (void)__hip_atomic_fetch_add(p, delta[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
-                (void)__hip_atomic_fetch_add(p, delta[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+            for (int e = 0; e < W; ++e) {
+                float *p = row + s * (kWave * W) + lane * W + e;
+                (void)__hip_atomic_fetch_add(p, delta[s * W + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 
@@ -270,6 +270,203 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
     }
 }
 
+// Update of a row that is not held in registers: row += total * other.  Atomic adds keep
+// every concurrent update; the plain variant writes back loaded + total * other and can
+// lose an update that another wave makes between this wave's load and store.
+template <int kV, int kCoherence>
+__device__ __forceinline__ void remote_update(float *row, int lane, bool warm, float total, const float (&other)[kV],
+                                              const float (&loaded)[kV]) {
+    using Io = RowIo<kV, kCoherence>;
+    if (kCoherence == kAtomicAgent || (kCoherence == kMixed && warm)) {
+        float d[kV];
+#pragma unroll
+        for (int j = 0; j < kV; ++j) d[j] = total * other[j];
+        Io::add(row, lane, d);
+    } else {
+        float r[kV];
+#pragma unroll
+        for (int j = 0; j < kV; ++j) r[j] = fmaf(total, other[j], loaded[j]);
+        Io::store(row, lane, r);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Stationary-row training of a grouped pool.  Each sample is tagged with the side that
+// stays in registers: vertex[u] (side 0) or context[v] (side 1), and samples with the
+// same stationary row are adjacent.  A wave takes chunks of 64 consecutive samples and
+// keeps the stationary row in registers for as long as consecutive samples name it: the
+// row is read once per run, the run's updates are applied to the register copy in
+// order, and the run's total change is added to memory once with fp32 atomic adds
+// (nothing another wave adds meanwhile is lost).  A row that half of a tile's samples
+// share is thus touched in memory twice per 64 samples instead of 128 times.  The other rows of a sample are
+// fetched and updated per sample with the given policy.  order[i] names the i-th sample
+// to process: its position in the pool (which also fixes its negatives and learning
+// rate) in bits 0..30 and its stationary side in bit 31.
+template <int kV, int kK, int kCoherence>
+__global__ __launch_bounds__(kBlock) void k_train_grouped(TrainArgs a, const uint32_t *__restrict__ order) {
+    constexpr int D = kV * kWave;
+    using Io = RowIo<kV, kCoherence>;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
+    const uint32_t waves = gridDim.x * (kBlock / kWave);
+    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
+
+    float *held = nullptr;  // address of the row kept in y[]
+    float y[kV], moved[kV];
+#pragma unroll
+    for (int j = 0; j < kV; ++j) y[j] = moved[j] = 0.0f;
+
+    // chunks are dealt round-robin, so the launch moves through the grouped pool front to
+    // back (tile after tile) with all waves working close to each other
+    for (uint32_t chunk = wave; chunk < chunks; chunk += waves) {
+        const uint32_t base = chunk * kWave;
+        const uint32_t in_chunk = min((uint32_t)kWave, a.count - base);
+        const bool mine = (uint32_t)lane < in_chunk;
+        const uint32_t tag = mine ? order[base + lane] : 0u;
+        const uint32_t pos = tag & 0x7FFFFFFFu;
+        const uint2 p = mine && pos < a.count ? pairs[pos] : make_uint2(0u, 0u);
+        const uint64_t g = a.first_g + pos;
+        uint32_t neg[kK];
+#pragma unroll
+        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
+        const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
+        const bool bad = p.x >= a.n || p.y >= a.n;
+        if (mine && bad) *a.error_flag = 1u;
+        uint32_t warm = 0;  // bit 0: u, bit 1: v, bit 2+k: negative k
+        if constexpr (kCoherence == kMixed) {
+            if (!bad) {
+                warm = (uint32_t)a.warm[p.x] | ((uint32_t)a.warm[p.y] << 1);
+#pragma unroll
+                for (int k = 0; k < kK; ++k) warm |= (uint32_t)a.warm[neg[k]] << (2 + k);
+            }
+        }
+
+        for (uint32_t i = 0; i < in_chunk; ++i) {
+            const uint32_t u = lane_value(p.x, i);
+            const uint32_t v = lane_value(p.y, i);
+            if (u >= a.n || v >= a.n) continue;  // reported through error_flag
+            const bool context_side = (lane_value(tag, i) >> 31) != 0;
+            const uint32_t warm_i = lane_value(warm, i);
+            uint32_t nk[kK];
+#pragma unroll
+            for (int k = 0; k < kK; ++k) nk[k] = lane_value(neg[k], i);
+            const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
+            const float lrw = lr_i * a.neg_weight;
+            float *want = context_side ? a.context + (size_t)v * D : a.vertex + (size_t)u * D;
+            if (want != held) {
+                if (held) Io::add(held, lane, moved);
+                Io::load(want, lane, y);
+#pragma unroll
+                for (int j = 0; j < kV; ++j) moved[j] = 0.0f;
+                held = want;
+            }
+
+            if (!context_side) {
+                // y is vertex[u]; context rows v, nk[] are remote
+                uint32_t rows[kK + 1];
+                rows[0] = v;
+#pragma unroll
+                for (int k = 0; k < kK; ++k) rows[k + 1] = nk[k];
+                float c[kK + 1][kV];
+#pragma unroll
+                for (int k = 0; k <= kK; ++k) Io::load(a.context + (size_t)rows[k] * D, lane, c[k]);
+                float coef[kK + 1];
+#pragma unroll
+                for (int k = 0; k <= kK; ++k) {
+                    float partial = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) partial = fmaf(y[j], c[k][j], partial);
+                    const float score = wave_sum(partial);
+                    coef[k] = k == 0 ? lr_i * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                }
+#pragma unroll
+                for (int k = 0; k <= kK; ++k) {
+                    bool repeated = false;
+#pragma unroll
+                    for (int k2 = 0; k2 < k; ++k2) repeated |= rows[k2] == rows[k];
+                    if (repeated) continue;
+                    float total = coef[k];
+#pragma unroll
+                    for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
+                    remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, (warm_i >> (k + 1)) & 1u, total, y,
+                                                  c[k]);
+                }
+#pragma unroll
+                for (int j = 0; j < kV; ++j) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], c[k][j], acc);
+                    y[j] += acc;
+                    moved[j] += acc;
+                }
+            } else {
+                // y is context[v]; vertex[u] and the negatives' context rows are remote
+                float *xp = a.vertex + (size_t)u * D;
+                float x[kV];
+                Io::load(xp, lane, x);
+                float c[kK][kV];
+#pragma unroll
+                for (int k = 0; k < kK; ++k) {
+                    if (nk[k] == v) {
+#pragma unroll
+                        for (int j = 0; j < kV; ++j) c[k][j] = y[j];
+                    } else {
+                        Io::load(a.context + (size_t)nk[k] * D, lane, c[k]);
+                    }
+                }
+                float coef[kK + 1];
+                {
+                    float partial = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) partial = fmaf(x[j], y[j], partial);
+                    coef[0] = lr_i * (1.0f - sigmoid(wave_sum(partial)));
+                }
+#pragma unroll
+                for (int k = 0; k < kK; ++k) {
+                    float partial = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) partial = fmaf(x[j], c[k][j], partial);
+                    coef[k + 1] = -lrw * sigmoid(wave_sum(partial));
+                }
+                float dx[kV];
+#pragma unroll
+                for (int j = 0; j < kV; ++j) {
+                    float acc = coef[0] * y[j];
+#pragma unroll
+                    for (int k = 0; k < kK; ++k) acc = fmaf(coef[k + 1], c[k][j], acc);
+                    dx[j] = acc;
+                }
+                remote_update<kV, kCoherence>(xp, lane, warm_i & 1u, 1.0f, dx, x);
+                float stay = coef[0];  // coefficient on the stationary row, negatives equal to v included
+#pragma unroll
+                for (int k = 0; k < kK; ++k) {
+                    if (nk[k] == v) {
+                        stay += coef[k + 1];
+                        continue;
+                    }
+                    bool repeated = false;
+#pragma unroll
+                    for (int k2 = 0; k2 < k; ++k2) repeated |= nk[k2] == nk[k];
+                    if (repeated) continue;
+                    float total = coef[k + 1];
+#pragma unroll
+                    for (int k2 = k + 1; k2 < kK; ++k2) total += nk[k2] == nk[k] ? coef[k2 + 1] : 0.0f;
+                    remote_update<kV, kCoherence>(a.context + (size_t)nk[k] * D, lane, (warm_i >> (k + 2)) & 1u, total, x,
+                                                  c[k]);
+                }
+#pragma unroll
+                for (int j = 0; j < kV; ++j) {
+                    const float d = stay * x[j];
+                    y[j] += d;
+                    moved[j] += d;
+                }
+            }
+        }
+    }
+    if (held) Io::add(held, lane, moved);
+}
+
 // Deterministic mode: wave i trains sample i of a batch whose samples share no
 // vertex row and no context row (Def. 1, Sec. 3.2: such samples commute), so the
 // result equals the sequential order up to fp32 rounding inside a sample.
@@ -330,20 +527,25 @@ uint32_t env_u32(const char *name, uint32_t fallback) {
     return v > 0 ? (uint32_t)v : fallback;
 }
 
-template <int kV, int kK>
-hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
-    // Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy;
-    // each wave strides over the chunks.  GV_GRID_BLOCKS overrides for tuning sweeps.
-    // The number of samples in flight is also kept below |V|/8: every in-flight sample
-    // works on values that miss the updates of the others (Def. 1, Sec. 3.2: the order of
-    // updates stops mattering only while concurrent samples rarely share rows), and a
-    // small graph gains nothing from thousands of waves.
+// Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy; each
+// wave strides over the chunks.  The number of samples in flight is also kept below
+// |V|/8: every in-flight sample works on values that miss the updates of the others
+// (Def. 1, Sec. 3.2: the order of updates stops mattering only while concurrent samples
+// rarely share rows), and a small graph gains nothing from thousands of waves.
+// GV_GRID_BLOCKS overrides the upper limit for tuning sweeps.
+uint32_t hogwild_blocks(uint32_t count, uint32_t n) {
     static const uint32_t max_blocks = env_u32("GV_GRID_BLOCKS", 256u * 8u);
-    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint32_t chunks = (count + kWave - 1) / kWave;
     const uint32_t wanted = (chunks + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const uint32_t by_rows = (a.n / 8u) / (kBlock / kWave);
+    const uint32_t by_rows = (n / 8u) / (kBlock / kWave);
     uint32_t blocks = wanted < max_blocks ? wanted : max_blocks;
     if (blocks > by_rows) blocks = by_rows > 64u ? by_rows : (blocks < 64u ? blocks : 64u);
+    return blocks;
+}
+
+template <int kV, int kK>
+hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
+    const uint32_t blocks = hogwild_blocks(a.count, a.n);
     if (blocks == 0) return hipSuccess;
     switch (coherence) {
         case kAgent:
@@ -352,12 +554,25 @@ hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t
         case kAtomicAgent:
             hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
-        case kAtomicL2:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicL2>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        case kMixed:  // the per-row choice exists in the grouped kernel only
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
         default:
             hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain>), dim3(blocks), dim3(kBlock), 0, stream, a);
     }
+    return hipGetLastError();
+}
+
+template <int kV, int kK>
+hipError_t launch_grouped_vk(const TrainArgs &a, const uint32_t *order, uint32_t coherence, hipStream_t stream) {
+    if (a.count == 0 || order == nullptr) return a.count == 0 ? hipSuccess : hipErrorInvalidValue;
+    const uint32_t blocks = hogwild_blocks(a.count, a.n);
+    if (coherence == kAgent)
+        hipLaunchKernelGGL((k_train_grouped<kV, kK, kAgent>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
+    else if (coherence == kMixed)
+        hipLaunchKernelGGL((k_train_grouped<kV, kK, kMixed>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
+    else
+        hipLaunchKernelGGL((k_train_grouped<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
     return hipGetLastError();
 }
 
@@ -396,6 +611,13 @@ bool supported_shape(uint32_t dim, uint32_t num_neg) {
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
                                 hipStream_t stream) {
 #define GV_CALL(V, K) launch_hogwild_vk<V, K>(a, coherence, stream)
+    GV_DISPATCH(GV_CALL)
+#undef GV_CALL
+}
+
+hipError_t launch_train_grouped(const TrainArgs &a, const uint32_t *order, uint32_t dim, uint32_t num_neg,
+                                uint32_t coherence, hipStream_t stream) {
+#define GV_CALL(V, K) launch_grouped_vk<V, K>(a, order, coherence, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }

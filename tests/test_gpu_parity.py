@@ -221,10 +221,20 @@ def test_learning_rate_floor_and_resume_position(gv, tiny_graph):
 
 
 # --------------------------------------------------------------------------- asynchronous mode
-def hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, T, seed, coherence, device_pool=False):
+# (schedule, coherence) pairs of the asynchronous mode
+POOL_ORDER, GROUPED = 0, 1
+PLAIN, AGENT, ATOMIC, MIXED = 0, 1, 2, 3
+ALL_POLICIES = [(POOL_ORDER, PLAIN), (POOL_ORDER, AGENT), (POOL_ORDER, ATOMIC), (GROUPED, AGENT), (GROUPED, ATOMIC),
+                (GROUPED, MIXED)]
+# policies that never drop an update of a contended row: these are held to the quality gate
+LOSSLESS_POLICIES = [(POOL_ORDER, ATOMIC), (GROUPED, ATOMIC), (GROUPED, MIXED)]
+
+
+def hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, T, seed, policy):
     cap = max(p.shape[0] for p in pools)
+    schedule, coherence = policy
     with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
-                     pool_capacity=cap, lr0=LR0, coherence=coherence) as ctx:
+                     pool_capacity=cap, lr0=LR0, coherence=coherence, schedule=schedule) as ctx:
         gv.gv_set_degrees(ctx, deg)
         gv.gv_build_alias(ctx, 0.75)
         gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
@@ -264,9 +274,9 @@ def check_single_steps(pool, negs, idx, first_g, T, K, w, seed, vertex, context,
     return worst
 
 
-@pytest.mark.parametrize("coherence", [0, 1, 2, 3])
+@pytest.mark.parametrize("policy", ALL_POLICIES)
 @pytest.mark.parametrize("d,K", [(128, 1), (64, 1), (256, 2), (512, 5)])
-def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, coherence, d, K):
+def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, policy, d, K):
     """A sparse pool over many nodes: most samples share no row with any other sample, so whatever
     the interleaving their rows must equal one sequential step from the initial values; rows never
     named must be bit-identical to the input.  4099 = 64 chunks and a ragged tail."""
@@ -277,7 +287,7 @@ def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, coherence, d, K):
     vertex, context = random_embeddings(n, d, seed=3)
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias)
-    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, 10 * count, seed, coherence)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, 10 * count, seed, policy)
     idx, cu, cc = singly_touched(pool, negs, n)
     assert idx.size > 0.3 * count
     worst = check_single_steps(pool, negs, idx[:1500], 0, 10 * count, K, w, seed, vertex, context, got_v, got_c,
@@ -293,8 +303,8 @@ def evaluation_loss(deg, vertex, context, eval_pool, K, w):
     return oracle.loss(vertex, context, eval_pool, K=K, w=w, seed=99, thresh=thresh, alias=alias)
 
 
-@pytest.mark.parametrize("coherence", [2])
-def test_hogwild_quality_matches_oracle_on_tiny(gv, coherence):
+@pytest.mark.parametrize("policy", LOSSLESS_POLICIES)
+def test_hogwild_quality_matches_oracle_on_tiny(gv, policy):
     """Configuration 1 in asynchronous mode: final evaluation loss within 2 % of the sequential
     oracle's and link-prediction AUC within 0.005 (5 % of the edges held out)."""
     n, src, dst = W.make_graph("tiny", cache=False)
@@ -305,21 +315,21 @@ def test_hogwild_quality_matches_oracle_on_tiny(gv, coherence):
     pool, _ = oracle.augment(101, offsets, adj, 40, 5, total, shuffle_seed=7)
     eval_pool, _ = oracle.augment(202, offsets, adj, 40, 5, 1 << 18, shuffle_seed=8)
     vertex, context = oracle.init_embeddings(1, n, d)
-    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, total, 1234, coherence)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, total, 1234, policy)
     ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, total, 1234)
     loss_gpu = evaluation_loss(deg, got_v, got_c, eval_pool, K, w)
     loss_ref = evaluation_loss(deg, ref_v, ref_c, eval_pool, K, w)
     na, nb = W.uniform_negative_pairs(n, te_s.size, seed=32)
     auc_gpu = oracle.link_prediction_auc(got_v, te_s, te_d, na, nb)
     auc_ref = oracle.link_prediction_auc(ref_v, te_s, te_d, na, nb)
-    print(f"tiny hogwild coherence={coherence}: loss {loss_gpu:.5f} vs {loss_ref:.5f}; auc {auc_gpu:.4f} vs {auc_ref:.4f}")
+    print(f"tiny hogwild policy={policy}: loss {loss_gpu:.5f} vs {loss_ref:.5f}; auc {auc_gpu:.4f} vs {auc_ref:.4f}")
     assert np.isfinite(got_v).all() and np.isfinite(got_c).all()
     assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
     assert abs(auc_gpu - auc_ref) <= 0.005
 
 
-@pytest.mark.parametrize("coherence", [2])
-def test_hogwild_quality_on_planted_partition(gv, coherence):
+@pytest.mark.parametrize("policy", LOSSLESS_POLICIES)
+def test_hogwild_quality_on_planted_partition(gv, policy):
     """Scaled-down configuration 4 (5000 nodes, 10 communities, 5*10^4 edges, 5 % held out,
     8*10^6 samples in 2^20-sample pools, trained to the plateau): loss within 2 %, AUC within
     0.005 of the oracle."""
@@ -334,14 +344,14 @@ def test_hogwild_quality_on_planted_partition(gv, coherence):
     pools = [pool[i:i + cfg["pool"]] for i in range(0, total, cfg["pool"])]
     eval_pool, _ = oracle.augment(204, offsets, adj, 40, 5, 1 << 18, shuffle_seed=8)
     vertex, context = oracle.init_embeddings(1, n, d)
-    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, total, 1234, coherence)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, total, 1234, policy)
     ref_v, ref_c = run_oracle(deg, K, w, pools, vertex, context, total, 1234)
     loss_gpu = evaluation_loss(deg, got_v, got_c, eval_pool, K, w)
     loss_ref = evaluation_loss(deg, ref_v, ref_c, eval_pool, K, w)
     na, nb = W.uniform_negative_pairs(n, te_s.size, seed=42)
     auc_gpu = oracle.link_prediction_auc(got_v, te_s, te_d, na, nb)
     auc_ref = oracle.link_prediction_auc(ref_v, te_s, te_d, na, nb)
-    print(f"sbm hogwild coherence={coherence}: loss {loss_gpu:.5f} vs {loss_ref:.5f}; auc {auc_gpu:.4f} vs {auc_ref:.4f}")
+    print(f"sbm hogwild policy={policy}: loss {loss_gpu:.5f} vs {loss_ref:.5f}; auc {auc_gpu:.4f} vs {auc_ref:.4f}")
     assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
     assert abs(auc_gpu - auc_ref) <= 0.005
     assert auc_ref > 0.85
