@@ -119,12 +119,10 @@ def main():
         after = gv.gv_get_stats(ctx)
         launches = after["timed_launches"] - before["timed_launches"]
         kernel_ms = (after["train_kernel_ms"] - before["train_kernel_ms"]) / max(launches, 1)
-        group_ms = (after["group_ms"] - before["group_ms"]) / max(launches, 1)
         value = args.steps * P / wall
         bytes_per_sample = algorithmic_bytes_per_sample(dim, K)
         achieved = bytes_per_sample * P / (kernel_ms * 1e-3) / 1e9
-        log(f"resident: {value:.4g} samples/s, train kernel {kernel_ms:.3f} ms/launch (+ grouping {group_ms:.3f} ms), "
-            f"{achieved:.0f} GB/s algorithmic")
+        log(f"resident: {value:.4g} samples/s, train kernel {kernel_ms:.3f} ms/launch, {achieved:.0f} GB/s algorithmic")
 
         streamed = None
         if not args.no_streamed:
@@ -178,11 +176,11 @@ def main():
                                f"neg_weight={w}, pool=2^{int(np.log2(P))} samples resident in HBM, "
                                f"{args.pools} distinct walk pools (L=40, s=5) cycled, Hogwild",
                    "coherence": ["plain", "agent", "atomic-agent", "mixed"][args.coherence],
-                   "schedule": ["pool-order", "grouped"][args.schedule], "samples_per_step": P},
+                   "schedule": ["pool-order", "tiled"][args.schedule], "samples_per_step": P},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_train_grouped" if args.schedule else "k_train_hogwild", "kernel_ms": kernel_ms,
-                     "bytes_per_sample": bytes_per_sample, "grouping_ms_per_launch": group_ms},
+                     "kernel": "k_train_tiled" if args.schedule else "k_train_hogwild", "kernel_ms": kernel_ms,
+                     "bytes_per_sample": bytes_per_sample},
         "cpu_baseline": cpu,
         "streamed": streamed,
     }

@@ -52,17 +52,18 @@ enum { GV_VERTEX = 0, GV_CONTEXT = 1 };
  *   ATOMIC_AGENT device-scope loads, updates applied as fp32 atomic adds: no update
  *                is ever lost, reads may be slightly stale.
  *   MIXED        ATOMIC_AGENT for rows likely to be shared by concurrent samples,
- *                AGENT stores for the rest (grouped schedule only; otherwise it
+ *                AGENT stores for the rest (tiled schedule only; otherwise it
  *                behaves as ATOMIC_AGENT).                                            */
 enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT = 2, GV_COHERENCE_MIXED = 3 };
 /* Order in which an asynchronous launch walks a pool.
  *   POOL_ORDER   waves take chunks of 64 consecutive samples.
- *   GROUPED      inside tiles of the pool, samples are sorted by their hotter row
- *                (the higher-degree one of u, v); a wave keeps that row in
- *                registers across the run of samples that share it and adds the
- *                run's total change to memory once.  Each sample keeps the
+ *   TILED        workgroups take tiles of 1024 consecutive samples and sort each tile
+ *                by the hotter row of every sample (the higher-degree one of u, v); a
+ *                wave keeps that row in registers across the run of samples sharing it
+ *                and adds the run's total change to memory once.  The launch still
+ *                moves through the pool front to back, and each sample keeps the
  *                negatives and learning rate of its position in the pool.          */
-enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_GROUPED = 1 };
+enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1 };
 
 typedef struct gv_config {
     uint32_t dim;            /* d: 64, 128, 256 or 512                                        */
@@ -91,7 +92,6 @@ typedef struct gv_stats {
     uint64_t timed_launches;    /* launches contributing to train_kernel_ms                    */
     double h2d_ms;              /* event-timed pool copies host -> device (profile != 0)        */
     uint64_t h2d_bytes;
-    double group_ms;            /* event-timed pool grouping (key build + sort), grouped schedule */
 } gv_stats;
 
 /* Create a context on cfg->device.  Allocates the pool slots only; the graph

@@ -14,7 +14,7 @@ GV_OK, GV_EINVAL, GV_ENOMEM, GV_ESTATE, GV_EHIP = 0, -1, -2, -3, -4
 GV_MODE_HOGWILD, GV_MODE_DETERMINISTIC = 0, 1
 GV_VERTEX, GV_CONTEXT = 0, 1
 GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_MIXED = 0, 1, 2, 3
-GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_GROUPED = 0, 1
+GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
 
@@ -40,7 +40,7 @@ class gv_stats(C.Structure):
     _fields_ = [
         ("samples_trained", C.c_uint64), ("pools_trained", C.c_uint64), ("train_launches", C.c_uint64),
         ("batches", C.c_uint64), ("train_kernel_ms", C.c_double), ("timed_launches", C.c_uint64),
-        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("group_ms", C.c_double),
+        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64),
     ]
 
     def as_dict(self):
@@ -63,6 +63,10 @@ def load():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1903_00757_amd.build`")
+    # PyTorch-ROCm ships its own HIP runtime; it has to be in the process before this library
+    # so that both use one runtime (two runtimes in one process do not both get the GPU).
+    import torch  # noqa: F401
+
     L = C.CDLL(LIB_PATH)
     vp, u32p, f32p = C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_float)
     L.gv_create.argtypes = [C.POINTER(gv_config), C.POINTER(vp)]
@@ -106,7 +110,7 @@ def _u32(a):
 
 def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=None, mode=GV_MODE_HOGWILD,
               total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_MIXED, profile=0,
-              schedule=GV_SCHEDULE_GROUPED):
+              schedule=GV_SCHEDULE_TILED):
     cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio,
                     neg_weight=(5.0 / max(num_neg, 1) if neg_weight is None else neg_weight), mode=mode,
                     total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,

@@ -32,7 +32,7 @@ struct PoolSlot {
 
 struct TimedSpan {
     hipEvent_t start, stop;
-    int kind;  // 0 training launch, 1 host-to-device copy, 2 pool grouping (key build + sort)
+    int kind;  // 0 training launch, 1 host-to-device copy
 };
 
 }  // namespace
@@ -47,10 +47,6 @@ struct gv_ctx {
     bool alias_ready = false;
     uint32_t *dev_degree = nullptr;       // device copy of the degrees (grouping key)
     uint8_t *dev_warm = nullptr;          // device, per node: updates must not be lost
-    uint32_t *group_buf[4] = {nullptr, nullptr, nullptr, nullptr};  // keys in, values in, keys out, values out
-    void *sort_scratch = nullptr;
-    size_t sort_bytes = 0;
-    uint64_t group_capacity = 0;          // samples the grouping buffers hold
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
@@ -113,10 +109,8 @@ void fold_spans(gv_ctx *ctx) {
             if (s.kind == 0) {
                 ctx->stats.train_kernel_ms += ms;
                 ctx->stats.timed_launches += 1;
-            } else if (s.kind == 1) {
-                ctx->stats.h2d_ms += ms;
             } else {
-                ctx->stats.group_ms += ms;
+                ctx->stats.h2d_ms += ms;
             }
         }
         ctx->spare_events.push_back(s.start);
@@ -146,6 +140,7 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->alias) (void)hipFree(ctx->alias);
     if (ctx->dev_degree) (void)hipFree(ctx->dev_degree);
     if (ctx->dev_warm) (void)hipFree(ctx->dev_warm);
+
     ctx->vertex = ctx->context = nullptr;
     ctx->alias = nullptr;
     ctx->dev_degree = nullptr;
@@ -242,60 +237,21 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
     return GV_OK;
 }
 
-int ensure_group_buffers(gv_ctx *ctx, uint64_t count) {
-    if (count <= ctx->group_capacity) return GV_OK;
-    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
-    for (uint32_t *&b : ctx->group_buf) {
-        if (b) (void)hipFree(b);
-        b = nullptr;
-    }
-    if (ctx->sort_scratch) (void)hipFree(ctx->sort_scratch);
-    ctx->sort_scratch = nullptr;
-    ctx->group_capacity = 0;
-    for (uint32_t *&b : ctx->group_buf) GV_HIP(ctx, hipMalloc((void **)&b, count * sizeof(uint32_t)));
-    GV_HIP(ctx, gv::group_scratch_bytes(count, &ctx->sort_bytes));
-    GV_HIP(ctx, hipMalloc(&ctx->sort_scratch, ctx->sort_bytes ? ctx->sort_bytes : 16));
-    ctx->group_capacity = count;
-    return GV_OK;
-}
-
-// Asynchronous training of `count` samples at dev_pairs.  Grouped schedule: the pool is
-// first sorted, inside tiles, by the hotter row of each sample, and trained by the
-// stationary-row kernel; otherwise one launch walks the pool in its own order.
+// Asynchronous training of `count` samples at dev_pairs: one launch of the tiled
+// stationary-row kernel, or of the plain pool-order kernel.
 int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     TimedSpan span{};
     const bool timed = ctx->cfg.profile != 0;
-    const gv::GroupPlan plan =
-        ctx->cfg.schedule == GV_SCHEDULE_GROUPED ? gv::plan_grouping(count, ctx->n) : gv::GroupPlan{};
-    if (plan.valid) {
-        int rc = ensure_group_buffers(ctx, count);
+    if (timed) {
+        int rc = begin_span(ctx, 0, ctx->compute, &span);
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    if (plan.valid) {
-        TimedSpan sort_span{};
-        if (timed) {
-            int rc = begin_span(ctx, 2, ctx->compute, &sort_span);
-            if (rc) return rc;
-        }
-        GV_HIP(ctx, gv::launch_group(plan, dev_pairs, count, ctx->n, ctx->dev_degree, ctx->group_buf[0],
-                                     ctx->group_buf[1], ctx->group_buf[2], ctx->group_buf[3], ctx->sort_scratch,
-                                     ctx->sort_bytes, ctx->compute));
-        if (timed) {
-            int rc = end_span(ctx, ctx->compute, sort_span);
-            if (rc) return rc;
-            rc = begin_span(ctx, 0, ctx->compute, &span);
-            if (rc) return rc;
-        }
-        GV_HIP(ctx, gv::launch_train_grouped(a, ctx->group_buf[3], ctx->cfg.dim, ctx->cfg.num_neg,
-                                             ctx->cfg.coherence, ctx->compute));
-    } else {
-        if (timed) {
-            int rc = begin_span(ctx, 0, ctx->compute, &span);
-            if (rc) return rc;
-        }
+    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u)
+        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->dev_degree, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence,
+                                           ctx->compute));
+    else
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
-    }
     ctx->stats.train_launches += 1;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
@@ -422,7 +378,7 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
     if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 32))
         return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^32 samples");
     if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
-        cfg->schedule > GV_SCHEDULE_GROUPED)
+        cfg->schedule > GV_SCHEDULE_TILED)
         return fail(nullptr, GV_EINVAL, "bad mode / coherence / schedule field");
     if (!(cfg->lr0 >= 0.0f) || !(cfg->lr_min_ratio >= 0.0f) || !(cfg->neg_weight >= 0.0f) || !isfinite(cfg->lr0) ||
         !isfinite(cfg->neg_weight))
@@ -480,9 +436,6 @@ void gv_destroy(gv_ctx *ctx) {
     }
     free_matrices(ctx);
     if (ctx->negatives) (void)hipFree(ctx->negatives);
-    for (uint32_t *b : ctx->group_buf)
-        if (b) (void)hipFree(b);
-    if (ctx->sort_scratch) (void)hipFree(ctx->sort_scratch);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
     if (ctx->compute) (void)hipStreamDestroy(ctx->compute);

@@ -27,25 +27,10 @@ struct TrainArgs {
 // Launch shapes are chosen here; both return the HIP error of the launch.
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
                                 hipStream_t stream);
-// Stationary-row training: order[i] = position in a.pairs of the i-th sample to process
-// (bits 0..30) and its stationary side (bit 31: 0 vertex[u], 1 context[v]); samples with
-// the same stationary row are adjacent.
-hipError_t launch_train_grouped(const TrainArgs &a, const uint32_t *order, uint32_t dim, uint32_t num_neg,
-                                uint32_t coherence, hipStream_t stream);
-
-// How a pool is cut into tiles and keyed for grouping (32-bit keys).
-struct GroupPlan {
-    bool valid;
-    uint32_t tile_shift;  // tile = 2^tile_shift samples
-    uint32_t id_bits;     // bits of a node id
-    uint32_t key_bits;    // id_bits + 1 (side) + tile index bits
-};
-GroupPlan plan_grouping(uint64_t count, uint32_t n);
-hipError_t group_scratch_bytes(uint64_t count, size_t *sort_bytes);
-// keys/values in -> sorted out; values_out is the `order` array of launch_train_grouped.
-hipError_t launch_group(const GroupPlan &plan, const uint32_t *pairs, uint64_t count, uint32_t n,
-                        const uint32_t *degree, uint32_t *keys_in, uint32_t *values_in, uint32_t *keys_out,
-                        uint32_t *values_out, void *sort_scratch, size_t sort_bytes, hipStream_t stream);
+// Tiled stationary-row training (see k_train_tiled); degree[] is the device copy of the
+// node degrees and decides which row of a sample is kept in registers.
+hipError_t launch_train_tiled(const TrainArgs &a, const uint32_t *degree, uint32_t dim, uint32_t num_neg,
+                              uint32_t coherence, hipStream_t stream);
 // One wave per sample over samples [0, a.count): the caller guarantees that no
 // two of them share a vertex row or a context row (negatives included).
 hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);

@@ -291,76 +291,120 @@ __device__ __forceinline__ void remote_update(float *row, int lane, bool warm, f
 }
 
 // ---------------------------------------------------------------------------
-// Stationary-row training of a grouped pool.  Each sample is tagged with the side that
-// stays in registers: vertex[u] (side 0) or context[v] (side 1), and samples with the
-// same stationary row are adjacent.  A wave takes chunks of 64 consecutive samples and
-// keeps the stationary row in registers for as long as consecutive samples name it: the
-// row is read once per run, the run's updates are applied to the register copy in
-// order, and the run's total change is added to memory once with fp32 atomic adds
-// (nothing another wave adds meanwhile is lost).  A row that half of a tile's samples
-// share is thus touched in memory twice per 64 samples instead of 128 times.  The other rows of a sample are
-// fetched and updated per sample with the given policy.  order[i] names the i-th sample
-// to process: its position in the pool (which also fixes its negatives and learning
-// rate) in bits 0..30 and its stationary side in bit 31.
-template <int kV, int kK, int kCoherence>
-__global__ __launch_bounds__(kBlock) void k_train_grouped(TrainArgs a, const uint32_t *__restrict__ order) {
-    constexpr int D = kV * kWave;
-    using Io = RowIo<kV, kCoherence>;
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
-    const uint32_t waves = gridDim.x * (kBlock / kWave);
-    const uint32_t chunks = (a.count + kWave - 1) / kWave;
-    const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
-
-    float *held = nullptr;  // address of the row kept in y[]
-    float y[kV], moved[kV];
-#pragma unroll
-    for (int j = 0; j < kV; ++j) y[j] = moved[j] = 0.0f;
-
-    // chunks are dealt round-robin, so the launch moves through the grouped pool front to
-    // back (tile after tile) with all waves working close to each other
-    for (uint32_t chunk = wave; chunk < chunks; chunk += waves) {
-        const uint32_t base = chunk * kWave;
-        const uint32_t in_chunk = min((uint32_t)kWave, a.count - base);
-        const bool mine = (uint32_t)lane < in_chunk;
-        const uint32_t tag = mine ? order[base + lane] : 0u;
-        const uint32_t pos = tag & 0x7FFFFFFFu;
-        const uint2 p = mine && pos < a.count ? pairs[pos] : make_uint2(0u, 0u);
-        const uint64_t g = a.first_g + pos;
-        uint32_t neg[kK];
-#pragma unroll
-        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
-        const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
-        const bool bad = p.x >= a.n || p.y >= a.n;
-        if (mine && bad) *a.error_flag = 1u;
-        uint32_t warm = 0;  // bit 0: u, bit 1: v, bit 2+k: negative k
-        if constexpr (kCoherence == kMixed) {
-            if (!bad) {
-                warm = (uint32_t)a.warm[p.x] | ((uint32_t)a.warm[p.y] << 1);
-#pragma unroll
-                for (int k = 0; k < kK; ++k) warm |= (uint32_t)a.warm[neg[k]] << (2 + k);
+// Tiled stationary-row training.  A workgroup takes a tile of kTile consecutive samples
+// of the pool, tags every sample with its hotter row (the higher-degree one of u, v:
+// vertex[u] = side 0, context[v] = side 1) and sorts the tile by that row in LDS, so
+// that samples sharing their hot row become adjacent.  Each of its four waves then walks
+// a quarter of the sorted tile and keeps the hot row in registers for as long as
+// consecutive samples name it: the row is read once per run, the run's updates are
+// applied to the register copy in order, and the run's total change is added to memory
+// once with fp32 atomic adds (nothing another wave adds meanwhile is lost).  The other
+// rows of a sample are fetched and updated per sample with the given policy.
+// Tiles are dealt round-robin to workgroups, so the launch still moves through the pool
+// front to back and a row's samples stay spread over time; only the memory traffic of
+// the few rows that a large share of all samples name shrinks (16 samples of one tile
+// sharing a row cost 2 row transfers instead of 32).  Every sample keeps the negatives
+// and the learning rate of its position in the pool.
+template <int kTile>
+__device__ __forceinline__ void sort_tile(uint32_t *key, uint32_t *pos) {
+    for (uint32_t k = 2; k <= (uint32_t)kTile; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t t = threadIdx.x; t < (uint32_t)kTile / 2; t += kBlock) {
+                const uint32_t lo = 2 * t - (t & (j - 1));  // partner pairs (lo, lo + j) of this bitonic step
+                const uint32_t hi = lo + j;
+                const bool ascending = (lo & k) == 0;
+                const uint32_t ka = key[lo], kb = key[hi];
+                if ((ka > kb) == ascending) {
+                    key[lo] = kb;
+                    key[hi] = ka;
+                    const uint32_t pa = pos[lo];
+                    pos[lo] = pos[hi];
+                    pos[hi] = pa;
+                }
             }
+            __syncthreads();
         }
+    }
+}
 
-        for (uint32_t i = 0; i < in_chunk; ++i) {
-            const uint32_t u = lane_value(p.x, i);
-            const uint32_t v = lane_value(p.y, i);
-            if (u >= a.n || v >= a.n) continue;  // reported through error_flag
-            const bool context_side = (lane_value(tag, i) >> 31) != 0;
-            const uint32_t warm_i = lane_value(warm, i);
-            uint32_t nk[kK];
-#pragma unroll
-            for (int k = 0; k < kK; ++k) nk[k] = lane_value(neg[k], i);
-            const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
-            const float lrw = lr_i * a.neg_weight;
-            float *want = context_side ? a.context + (size_t)v * D : a.vertex + (size_t)u * D;
-            if (want != held) {
-                if (held) Io::add(held, lane, moved);
-                Io::load(want, lane, y);
-#pragma unroll
-                for (int j = 0; j < kV; ++j) moved[j] = 0.0f;
-                held = want;
+template <int kV, int kK, int kCoherence, int kTile>
+__global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint32_t *__restrict__ degree) {
+    constexpr int D = kV * kWave;
+    constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
+    constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
+    static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
+    using Io = RowIo<kV, kCoherence>;
+    __shared__ uint32_t s_key[kTile];
+    __shared__ uint32_t s_pos[kTile];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
+    const uint32_t tiles = (a.count + kTile - 1) / kTile;
+
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const uint32_t tile_base = tile * kTile;
+        for (uint32_t t = threadIdx.x; t < (uint32_t)kTile; t += kBlock) {
+            uint32_t key = kSkip;
+            if (tile_base + t < a.count) {
+                const uint2 p = pairs[tile_base + t];
+                if (p.x < a.n && p.y < a.n) {
+                    const bool context_side = degree[p.x] < degree[p.y];
+                    key = context_side ? (0x80000000u | p.y) : p.x;
+                } else {
+                    *a.error_flag = 1u;  // the sample is skipped and reported at the next synchronisation
+                }
             }
+            s_key[t] = key;
+            s_pos[t] = t;
+        }
+        __syncthreads();
+        sort_tile<kTile>(s_key, s_pos);
+
+        float *held = nullptr;  // address of the row kept in y[]
+        float y[kV], moved[kV];
+#pragma unroll
+        for (int j = 0; j < kV; ++j) y[j] = moved[j] = 0.0f;
+
+        for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
+            const uint32_t tag = s_key[base + lane];
+            const bool mine = tag != kSkip;
+            const uint32_t pos = tile_base + s_pos[base + lane];
+            const uint2 p = mine ? pairs[pos] : make_uint2(0u, 0u);
+            const uint64_t g = a.first_g + pos;
+            uint32_t neg[kK];
+#pragma unroll
+            for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
+            const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
+            uint32_t warm = 0;  // bit 0: u, bit 1: v, bit 2+k: negative k
+            if constexpr (kCoherence == kMixed) {
+                if (mine) {
+                    warm = (uint32_t)a.warm[p.x] | ((uint32_t)a.warm[p.y] << 1);
+#pragma unroll
+                    for (int k = 0; k < kK; ++k) warm |= (uint32_t)a.warm[neg[k]] << (2 + k);
+                }
+            }
+            // sorted order puts the skipped slots last: the first one ends this wave's work
+            const uint64_t live = __ballot(mine);
+            const uint32_t in_chunk = live == ~0ull ? (uint32_t)kWave : (uint32_t)__builtin_ctzll(~live);
+
+            for (uint32_t i = 0; i < in_chunk; ++i) {
+                const uint32_t u = lane_value(p.x, i);
+                const uint32_t v = lane_value(p.y, i);
+                const bool context_side = (lane_value(tag, i) >> 31) != 0;
+                const uint32_t warm_i = lane_value(warm, i);
+                uint32_t nk[kK];
+#pragma unroll
+                for (int k = 0; k < kK; ++k) nk[k] = lane_value(neg[k], i);
+                const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
+                const float lrw = lr_i * a.neg_weight;
+                float *want = context_side ? a.context + (size_t)v * D : a.vertex + (size_t)u * D;
+                if (want != held) {
+                    if (held) Io::add(held, lane, moved);
+                    Io::load(want, lane, y);
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) moved[j] = 0.0f;
+                    held = want;
+                }
 
             if (!context_side) {
                 // y is vertex[u]; context rows v, nk[] are remote
@@ -462,9 +506,12 @@ __global__ __launch_bounds__(kBlock) void k_train_grouped(TrainArgs a, const uin
                     moved[j] += d;
                 }
             }
+            }
+            if (in_chunk < (uint32_t)kWave) break;
         }
+        if (held) Io::add(held, lane, moved);
+        __syncthreads();  // the next tile overwrites the LDS arrays
     }
-    if (held) Io::add(held, lane, moved);
 }
 
 // Deterministic mode: wave i trains sample i of a batch whose samples share no
@@ -529,7 +576,7 @@ uint32_t env_u32(const char *name, uint32_t fallback) {
 
 // Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy; each
 // wave strides over the chunks.  The number of samples in flight is also kept below
-// |V|/8: every in-flight sample works on values that miss the updates of the others
+// |V|/32: every in-flight sample works on values that miss the updates of the others
 // (Def. 1, Sec. 3.2: the order of updates stops mattering only while concurrent samples
 // rarely share rows), and a small graph gains nothing from thousands of waves.
 // GV_GRID_BLOCKS overrides the upper limit for tuning sweeps.
@@ -537,7 +584,7 @@ uint32_t hogwild_blocks(uint32_t count, uint32_t n) {
     static const uint32_t max_blocks = env_u32("GV_GRID_BLOCKS", 256u * 8u);
     const uint32_t chunks = (count + kWave - 1) / kWave;
     const uint32_t wanted = (chunks + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const uint32_t by_rows = (n / 8u) / (kBlock / kWave);
+    const uint32_t by_rows = (n / 32u) / (kBlock / kWave);
     uint32_t blocks = wanted < max_blocks ? wanted : max_blocks;
     if (blocks > by_rows) blocks = by_rows > 64u ? by_rows : (blocks < 64u ? blocks : 64u);
     return blocks;
@@ -563,17 +610,30 @@ hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t
     return hipGetLastError();
 }
 
-template <int kV, int kK>
-hipError_t launch_grouped_vk(const TrainArgs &a, const uint32_t *order, uint32_t coherence, hipStream_t stream) {
-    if (a.count == 0 || order == nullptr) return a.count == 0 ? hipSuccess : hipErrorInvalidValue;
-    const uint32_t blocks = hogwild_blocks(a.count, a.n);
+template <int kV, int kK, int kTile>
+hipError_t launch_tiled_vkt(const TrainArgs &a, const uint32_t *degree, uint32_t coherence, uint32_t blocks,
+                            hipStream_t stream) {
     if (coherence == kAgent)
-        hipLaunchKernelGGL((k_train_grouped<kV, kK, kAgent>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a, degree);
     else if (coherence == kMixed)
-        hipLaunchKernelGGL((k_train_grouped<kV, kK, kMixed>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a, degree);
     else
-        hipLaunchKernelGGL((k_train_grouped<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a, order);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a,
+                           degree);
     return hipGetLastError();
+}
+
+template <int kV, int kK>
+hipError_t launch_tiled_vk(const TrainArgs &a, const uint32_t *degree, uint32_t coherence, hipStream_t stream) {
+    if (a.count == 0) return hipSuccess;
+    if (degree == nullptr || a.n > 0x80000000u) return hipErrorInvalidValue;
+    static const uint32_t tile = env_u32("GV_TILE", 1024u);  // tuning sweeps: 512, 1024 or 2048
+    uint32_t blocks = hogwild_blocks(a.count, a.n);
+    const uint32_t tiles = (a.count + tile - 1) / tile;
+    if (blocks > tiles) blocks = tiles;
+    if (tile == 512) return launch_tiled_vkt<kV, kK, 512>(a, degree, coherence, blocks, stream);
+    if (tile == 2048) return launch_tiled_vkt<kV, kK, 2048>(a, degree, coherence, blocks, stream);
+    return launch_tiled_vkt<kV, kK, 1024>(a, degree, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -615,9 +675,9 @@ hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_n
 #undef GV_CALL
 }
 
-hipError_t launch_train_grouped(const TrainArgs &a, const uint32_t *order, uint32_t dim, uint32_t num_neg,
-                                uint32_t coherence, hipStream_t stream) {
-#define GV_CALL(V, K) launch_grouped_vk<V, K>(a, order, coherence, stream)
+hipError_t launch_train_tiled(const TrainArgs &a, const uint32_t *degree, uint32_t dim, uint32_t num_neg,
+                              uint32_t coherence, hipStream_t stream) {
+#define GV_CALL(V, K) launch_tiled_vk<V, K>(a, degree, coherence, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }

@@ -43,7 +43,7 @@ def test_config_struct_layout_matches_header(gv):
     assert ctypes.sizeof(gv.binding.gv_config) == 64
     assert gv.binding.gv_config.total_samples.offset == 24
     assert gv.binding.gv_config.device.offset == 48
-    assert ctypes.sizeof(gv.binding.gv_stats) == 72
+    assert ctypes.sizeof(gv.binding.gv_stats) == 64
 
 
 def test_argument_errors_need_no_device(gv):

@@ -222,12 +222,12 @@ def test_learning_rate_floor_and_resume_position(gv, tiny_graph):
 
 # --------------------------------------------------------------------------- asynchronous mode
 # (schedule, coherence) pairs of the asynchronous mode
-POOL_ORDER, GROUPED = 0, 1
+POOL_ORDER, TILED = 0, 1
 PLAIN, AGENT, ATOMIC, MIXED = 0, 1, 2, 3
-ALL_POLICIES = [(POOL_ORDER, PLAIN), (POOL_ORDER, AGENT), (POOL_ORDER, ATOMIC), (GROUPED, AGENT), (GROUPED, ATOMIC),
-                (GROUPED, MIXED)]
+ALL_POLICIES = [(POOL_ORDER, PLAIN), (POOL_ORDER, AGENT), (POOL_ORDER, ATOMIC), (TILED, AGENT), (TILED, ATOMIC),
+                (TILED, MIXED)]
 # policies that never drop an update of a contended row: these are held to the quality gate
-LOSSLESS_POLICIES = [(POOL_ORDER, ATOMIC), (GROUPED, ATOMIC), (GROUPED, MIXED)]
+LOSSLESS_POLICIES = [(POOL_ORDER, ATOMIC), (TILED, ATOMIC), (TILED, MIXED)]
 
 
 def hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, T, seed, policy):
@@ -355,3 +355,253 @@ def test_hogwild_quality_on_planted_partition(gv, policy):
     assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
     assert abs(auc_gpu - auc_ref) <= 0.005
     assert auc_ref > 0.85
+
+
+# --------------------------------------------------------------------------- full size, bench configuration
+@pytest.fixture(scope="module")
+def c2_workload():
+    """Configuration 2 at full size: Chung-Lu graph, 10^6 nodes / 5*10^6 edges, one 2^24-sample walk pool."""
+    n, src, dst = W.make_graph("c2")
+    deg = W.degrees(n, src, dst)
+    offsets, adj = W.csr_from_edges(n, src, dst)
+    pool = W.walk_pool(offsets, adj, 1 << 24, 40, 5, seed=202)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    return dict(n=n, deg=deg, pool=pool, thresh=thresh, alias=alias)
+
+
+def test_full_size_tables_and_negatives(gv, c2_workload):
+    c2 = c2_workload
+    with context_for(gv, dim=128, num_neg=1, total_samples=2_000_000_000, pool_capacity=1, seed=1234) as ctx:
+        gv.gv_set_degrees(ctx, c2["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        thresh, alias = gv.gv_get_alias(ctx, c2["n"])
+        assert np.array_equal(thresh, c2["thresh"]) and np.array_equal(alias, c2["alias"])
+        for first_g in (0, 1_999_000_000, 2**33 + 5):
+            got = gv.gv_draw_negatives(ctx, first_g, 1 << 20, 1)
+            assert np.array_equal(got, oracle.draw_negatives(1234, first_g, 1 << 20, 1, c2["thresh"], c2["alias"]))
+
+
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, ATOMIC)])
+def test_full_size_pool_in_bench_configuration(gv, c2_workload, policy):
+    """One 2^24-sample pool of configuration 2 through the launch configuration bench.py times
+    (device-resident pool, d=128, K=1, w=5, T=2*10^9).  Checked on what the oracle can compute one
+    by one: every sample whose three rows are named exactly once in the pool must leave exactly one
+    sequential step behind, whatever happened around it; rows nobody names stay bit-identical."""
+    import torch
+
+    c2 = c2_workload
+    n, d, K, w, T, seed = c2["n"], 128, 1, 5.0, 2_000_000_000, 1234
+    first_g = 1_000_000_000  # mid-run: learning rate 0.0125, 64-bit positions
+    # A walk pool names every node several times, so no sample is isolated by itself.  Plant some:
+    # at positions whose negative is drawn nowhere else and is nobody's v, put a pair of isolated
+    # (degree 0) nodes that nothing else names.  Those samples share no row with any other sample.
+    pool = c2["pool"].copy()
+    negs = oracle.draw_negatives(seed, first_g, pool.shape[0], K, c2["thresh"], c2["alias"])
+    context_use = np.bincount(np.concatenate([pool[:, 1], negs.reshape(-1)]), minlength=n)
+    where = np.nonzero(context_use[negs[:, 0]] == 1)[0]
+    lonely = np.nonzero(c2["deg"] == 0)[0].astype(np.uint32)
+    planted = min(where.size, lonely.size // 2, 4096)
+    assert planted >= 256, (where.size, lonely.size)
+    where = where[np.linspace(0, where.size - 1, planted).astype(np.int64)]
+    pool[where, 0] = lonely[:planted]
+    pool[where, 1] = lonely[planted:2 * planted]
+    vertex, context = random_embeddings(n, d, seed=11, scale=0.2)
+    dev_pool = torch.from_numpy(pool.view(np.int32)).cuda()
+    torch.cuda.synchronize()
+    schedule, coherence = policy
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=1, lr0=LR0, coherence=coherence, schedule=schedule) as ctx:
+        gv.gv_set_degrees(ctx, c2["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+        gv.gv_set_position(ctx, first_g)
+        gv.gv_train_device_pool(ctx, dev_pool.data_ptr(), pool.shape[0])
+        gv.gv_sync(ctx)
+        got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+        got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+        assert gv.gv_get_stats(ctx)["samples_trained"] == first_g + pool.shape[0]
+    idx, cu, cc = singly_touched(pool, negs, n)
+    assert idx.size >= 256, idx.size
+    rng = np.random.default_rng(0)
+    sample = rng.choice(idx, size=min(3000, idx.size), replace=False)
+    worst = check_single_steps(pool, negs, sample, first_g, T, K, w, seed, vertex, context, got_v, got_c,
+                               c2["thresh"], c2["alias"])
+    print(f"full size {policy}: {idx.size} isolated samples, {sample.size} checked, worst rel. error {worst:.2e}")
+    assert worst <= 1e-5, worst
+    assert np.array_equal(got_v[cu == 0], vertex[cu == 0])
+    assert np.array_equal(got_c[cc == 0], context[cc == 0])
+    assert np.isfinite(got_v).all() and np.isfinite(got_c).all()
+    # the hottest rows did move, and by a bounded amount (no runaway accumulation)
+    hot = np.argsort(c2["deg"])[-16:]
+    moved = np.abs(got_v[hot] - vertex[hot]).max(axis=1)
+    assert (moved > 0).all() and moved.max() < 4.0  # the sequential oracle moves these rows by about 1.4
+
+
+# --------------------------------------------------------------------------- streaming and errors
+def test_streamed_pools_equal_resident_pools(gv, tiny_graph):
+    """Pinned-slot producer path (acquire, fill, push, train, double-buffered) gives the same bits
+    as pushing plain host arrays and as training device-resident pools (deterministic mode)."""
+    import torch
+
+    g = tiny_graph
+    d, K, w, seed = 128, 1, 5.0, 5
+    counts = [40_000, 65_536, 1, 30_011, 64]
+    total = sum(counts)
+    pool, _ = oracle.augment(77, g["offsets"], g["adj"], 40, 5, total, shuffle_seed=3)
+    cuts = np.cumsum([0] + counts)
+    pools = [pool[a:b] for a, b in zip(cuts, cuts[1:])]
+    vertex, context = random_embeddings(g["n"], d, seed=9)
+    results = []
+    for how in ("host", "slot", "device"):
+        with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_DETERMINISTIC, total_samples=total,
+                         seed=seed, pool_capacity=65_536, lr0=LR0) as ctx:
+            gv.gv_set_degrees(ctx, g["deg"])
+            gv.gv_build_alias(ctx, 0.75)
+            gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+            gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+            if how == "host":
+                for p in pools:
+                    gv.gv_push_pool(ctx, p)
+                    gv.gv_train_pool(ctx)
+            elif how == "slot":
+                # keep two pools in flight: fill and push pool k+1 before training pool k
+                slot = gv.gv_acquire_pool_slot(ctx, 65_536)
+                slot[:pools[0].shape[0]] = pools[0]
+                gv.gv_push_pool(ctx, slot, pools[0].shape[0])
+                for k in range(len(pools)):
+                    if k + 1 < len(pools):
+                        slot = gv.gv_acquire_pool_slot(ctx, 65_536)
+                        slot[:pools[k + 1].shape[0]] = pools[k + 1]
+                        gv.gv_push_pool(ctx, slot, pools[k + 1].shape[0])
+                    gv.gv_train_pool(ctx)
+            else:
+                keep = [torch.from_numpy(p.copy().view(np.int32)).cuda() for p in pools]
+                torch.cuda.synchronize()
+                for t, p in zip(keep, pools):
+                    gv.gv_train_device_pool(ctx, t.data_ptr(), p.shape[0])
+            gv.gv_sync(ctx)
+            stats = gv.gv_get_stats(ctx)
+            assert stats["samples_trained"] == total and stats["pools_trained"] == len(pools)
+            results.append((gv.gv_read_embeddings(ctx, gv.GV_VERTEX, g["n"], d),
+                            gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, g["n"], d)))
+    for v, c in results[1:]:
+        assert np.array_equal(v, results[0][0]) and np.array_equal(c, results[0][1])
+    ref_v, ref_c = run_oracle(g["deg"], K, w, pools, vertex, context, total, seed)
+    assert rel_errors(results[0][0], ref_v)[0] <= 1e-5 and rel_errors(results[0][1], ref_c)[0] <= 1e-5
+
+
+def test_errors_are_reported_not_fatal(gv, tiny_graph):
+    g = tiny_graph
+    n = g["n"]
+    with context_for(gv, dim=128, num_neg=1, total_samples=100_000, pool_capacity=1000) as ctx:
+        for call in (lambda: gv.gv_build_alias(ctx, 0.75), lambda: gv.gv_init_embeddings(ctx, 1),
+                     lambda: gv.gv_push_pool(ctx, np.zeros((4, 2), dtype=np.uint32)), lambda: gv.gv_train_pool(ctx),
+                     lambda: gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, 128)):
+            with pytest.raises(gv.GvError) as e:
+                call()
+            assert e.value.code == gv.GV_ESTATE  # no graph yet
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_set_graph(ctx, n, np.array([0, n], dtype=np.uint32), np.array([1, 2], dtype=np.uint32))
+        assert e.value.code == gv.GV_EINVAL and "node id" in str(e.value)
+        gv.gv_set_graph(ctx, n, g["src"], g["dst"])
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_push_pool(ctx, np.zeros((4, 2), dtype=np.uint32))
+        assert e.value.code == gv.GV_ESTATE  # no alias table yet
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_build_alias(ctx, 0.5)
+        assert e.value.code == gv.GV_EINVAL
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, 3)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_train_pool(ctx)
+        assert e.value.code == gv.GV_ESTATE  # nothing queued
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_push_pool(ctx, np.zeros((1001, 2), dtype=np.uint32))
+        assert e.value.code == gv.GV_EINVAL  # above pool_capacity
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 2, 128, row0=n - 1)
+        assert e.value.code == gv.GV_EINVAL
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_read_embeddings(ctx, 2, 1, 128)
+        assert e.value.code == gv.GV_EINVAL
+        ok = np.stack([g["src"][:500], g["dst"][:500]], axis=1)
+        gv.gv_push_pool(ctx, ok)
+        gv.gv_push_pool(ctx, ok)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_push_pool(ctx, ok)
+        assert e.value.code == gv.GV_ESTATE  # two pools already queued
+        gv.gv_train_pool(ctx)
+        gv.gv_train_pool(ctx)
+        gv.gv_sync(ctx)
+        before = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, 128)
+        # a pool naming a node that does not exist: the sample is skipped, the next sync reports it once
+        bad = ok.copy()
+        bad[7, 1] = n
+        bad[300, 0] = 0xFFFFFFFF
+        gv.gv_push_pool(ctx, bad)
+        gv.gv_train_pool(ctx)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_sync(ctx)
+        assert e.value.code == gv.GV_EINVAL and "node id" in str(e.value)
+        gv.gv_sync(ctx)  # reported once; the context stays usable
+        after = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, 128)
+        assert np.isfinite(after).all() and not np.array_equal(before, after)
+        gv.gv_push_pool(ctx, np.zeros((0, 2), dtype=np.uint32))  # empty pool is legal
+        gv.gv_train_pool(ctx)
+        gv.gv_sync(ctx)
+        assert gv.gv_get_stats(ctx)["samples_trained"] == 1500
+
+
+@pytest.fixture(scope="module")
+def c2_oracle_pool(c2_workload):
+    """The sequential oracle over one full 2^24-sample pool of configuration 2 (about 15 s)."""
+    c2 = c2_workload
+    n, d = c2["n"], 128
+    vertex, context = random_embeddings(n, d, seed=11, scale=0.2)
+    ref_v, ref_c = vertex.copy(), context.copy()
+    oracle.train(ref_v, ref_c, c2["pool"], K=1, first_g=1_000_000_000, T=2_000_000_000, lr0=LR0, lr_min_ratio=0.0,
+                 w=5.0, seed=1234, thresh=c2["thresh"], alias=c2["alias"])
+    n_, src, dst = W.make_graph("c2")
+    offsets, adj = W.csr_from_edges(n, src, dst)
+    eval_pool = W.walk_pool(offsets, adj, 1 << 18, 40, 5, seed=303)
+    return dict(vertex=vertex, context=context, ref_v=ref_v, ref_c=ref_c, eval_pool=eval_pool)
+
+
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (TILED, ATOMIC)])
+def test_full_size_pool_tracks_the_sequential_oracle(gv, c2_workload, c2_oracle_pool, policy):
+    """Same launch configuration as the benchmark (2^24 samples, 10^6 nodes, thousands of samples in
+    flight): after the pool the evaluation loss is within 2 % of the sequential oracle's, and the
+    hottest rows, which take part in tens of thousands of samples, moved as far as the oracle's."""
+    import torch
+
+    c2, o = c2_workload, c2_oracle_pool
+    n, d, K, w, T, seed = c2["n"], 128, 1, 5.0, 2_000_000_000, 1234
+    dev_pool = torch.from_numpy(c2["pool"].view(np.int32)).cuda()
+    torch.cuda.synchronize()
+    schedule, coherence = policy
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=1, lr0=LR0, coherence=coherence, schedule=schedule) as ctx:
+        gv.gv_set_degrees(ctx, c2["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, o["vertex"])
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, o["context"])
+        gv.gv_set_position(ctx, 1_000_000_000)
+        gv.gv_train_device_pool(ctx, dev_pool.data_ptr(), c2["pool"].shape[0])
+        got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+        got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+    kw = dict(K=K, w=w, seed=99, thresh=c2["thresh"], alias=c2["alias"])
+    loss_start = oracle.loss(o["vertex"], o["context"], o["eval_pool"], **kw)
+    loss_ref = oracle.loss(o["ref_v"], o["ref_c"], o["eval_pool"], **kw)
+    loss_gpu = oracle.loss(got_v, got_c, o["eval_pool"], **kw)
+    hot = np.argsort(c2["deg"])[-64:]
+    ratios = []
+    for got, ref, init in ((got_v, o["ref_v"], o["vertex"]), (got_c, o["ref_c"], o["context"])):
+        moved_gpu = np.linalg.norm((got[hot] - init[hot]).astype(np.float64), axis=1)
+        moved_ref = np.linalg.norm((ref[hot] - init[hot]).astype(np.float64), axis=1)
+        ratios.append(moved_gpu / moved_ref)
+    print(f"full size {policy}: loss {loss_start:.4f} -> gpu {loss_gpu:.4f} / oracle {loss_ref:.4f}; "
+          f"hot-row movement ratio vertex {np.median(ratios[0]):.2f} context {np.median(ratios[1]):.2f}")
+    assert loss_ref < 0.95 * loss_start  # the pool does train
+    assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
+    assert 0.8 < np.median(ratios[0]) < 1.25 and 0.8 < np.median(ratios[1]) < 1.25
