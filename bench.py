@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters
+# read for a 1 GiB device copy (profiles/k_train_tiled_c2_d128_k1_mixed.md); only for the profiled setup.
+PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 54.01e9}
 
 
 def log(*a):
@@ -61,7 +64,7 @@ def main():
     ap.add_argument("--schedule", type=int, default=int(os.environ.get("GV_BENCH_SCHEDULE", "1")))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streamed", action="store_true")
-    ap.add_argument("--cpu-samples", type=int, default=1 << 22)
+    ap.add_argument("--cpu-samples", type=int, default=1 << 24)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -178,7 +181,8 @@ def main():
                    "coherence": ["plain", "agent", "atomic-agent", "mixed"][args.coherence],
                    "schedule": ["pool-order", "tiled"][args.schedule], "samples_per_step": P},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get((args.workload, args.schedule, args.coherence)),
                      "kernel": "k_train_tiled" if args.schedule else "k_train_hogwild", "kernel_ms": kernel_ms,
                      "bytes_per_sample": bytes_per_sample},
         "cpu_baseline": cpu,

@@ -19,7 +19,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Wall", "-Wextra", "-Wno-unused-parameter",
           # packed-fp32 instructions are kept out of the generated code on purpose
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+          "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("GV_EXTRA_CFLAGS", "").split()
 
 
 def build(verbose: bool = False) -> str:

@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -492,14 +493,21 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         sum += q;
     }
     if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
-    // A row is warm when, with kInFlight samples being processed at once, the chance that
-    // another of them names the same row (as a walk endpoint, share deg/sum(deg), or as a
-    // negative, share q/sum(q)) exceeds 2 %: the mixed policy then updates it with atomic adds.
+    // A row is warm when, with kInFlight samples being processed at once, the expected number
+    // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
+    // or as a negative, share q/sum(q)) exceeds 0.1: the mixed policy then updates it with
+    // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
+    // update only when two of the few samples naming such a row are in flight together.
     const double kInFlight = 8192.0;
+    double warm_threshold = 0.1;
+    if (const char *e = getenv("GV_WARM_THRESHOLD")) {  // tuning sweeps
+        const double v = atof(e);
+        if (v > 0.0) warm_threshold = v;
+    }
     std::vector<uint8_t> warm(n);
     for (uint32_t i = 0; i < n; ++i) {
         const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
-        warm[i] = share * kInFlight > 0.02 ? 1 : 0;
+        warm[i] = share * kInFlight > warm_threshold ? 1 : 0;
     }
     std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
     below.reserve(n);

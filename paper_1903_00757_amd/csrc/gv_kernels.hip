@@ -92,9 +92,7 @@ __device__ __forceinline__ uint32_t lane_value(uint32_t x, uint32_t lane) {
 // 64 * W * 4 byte request per wave.
 template <int kV, int kCoherence>
 struct RowIo {
-    // atomic adds work on single floats: one float per lane and segment keeps every
-    // atomic instruction on 256 contiguous bytes
-    static constexpr int W = is_atomic(kCoherence) ? 1 : is_agent(kCoherence) ? (kV >= 2 ? 2 : 1) : (kV >= 4 ? 4 : kV);
+    static constexpr int W = is_agent(kCoherence) ? (kV >= 2 ? 2 : 1) : (kV >= 4 ? 4 : kV);
     static constexpr int S = kV / W;
 
     static __device__ __forceinline__ void load(const float *row, int lane, float (&x)[kV]) {
@@ -123,15 +121,27 @@ struct RowIo {
         }
     }
 
-    // row += delta without losing concurrent updates of other waves (fp32 atomic add per
-    // element; with W = 1 every instruction covers 256 contiguous bytes)
+    // row += delta without losing concurrent updates of other waves: one fp32 atomic add
+    // per element.  With two floats per lane the values are first exchanged between lanes
+    // (lane l takes elements l and l + 64 of the 128-float segment) so that every atomic
+    // instruction covers 256 contiguous bytes instead of every other word of 512.
     static __device__ __forceinline__ void add(float *row, int lane, const float (&delta)[kV]) {
+        static_assert(W <= 2, "atomic adds are used with the device-scope layouts only");
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-#pragma unroll
-            for (int e = 0; e < W; ++e) {
-                float *p = row + s * (kWave * W) + lane * W + e;
-                (void)__hip_atomic_fetch_add(p, delta[s * W + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (W == 2) {
+                const int lo = (lane >> 1) * 4, hi = (32 + (lane >> 1)) * 4;  // byte addresses of the source lanes
+                const int e0 = __float_as_int(delta[s * 2]), e1 = __float_as_int(delta[s * 2 + 1]);
+                const int lo0 = __builtin_amdgcn_ds_bpermute(lo, e0), lo1 = __builtin_amdgcn_ds_bpermute(lo, e1);
+                const int hi0 = __builtin_amdgcn_ds_bpermute(hi, e0), hi1 = __builtin_amdgcn_ds_bpermute(hi, e1);
+                const float first = __int_as_float((lane & 1) ? lo1 : lo0);
+                const float second = __int_as_float((lane & 1) ? hi1 : hi0);
+                float *p = row + s * (kWave * 2) + lane;
+                (void)__hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                (void)__hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                (void)__hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -327,12 +337,25 @@ __device__ __forceinline__ void sort_tile(uint32_t *key, uint32_t *pos) {
     }
 }
 
+// Wave-uniform description of one sample of a sorted tile.
+template <int kK>
+struct TileSample {
+    uint32_t u, v;
+    uint32_t nk[kK];     // negatives
+    uint32_t warm;       // bit 0: u, bit 1: v, bit 2+k: negative k
+    float lr;
+    bool context_side;   // stationary row is context[v] (else vertex[u])
+    float *stationary;   // address of the stationary row
+};
+
 template <int kV, int kK, int kCoherence, int kTile>
 __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint32_t *__restrict__ degree) {
     constexpr int D = kV * kWave;
     constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
+    // samples whose gathers are in flight together: bounded by the registers their rows take
+    constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
     using Io = RowIo<kV, kCoherence>;
     __shared__ uint32_t s_key[kTile];
     __shared__ uint32_t s_pos[kTile];
@@ -360,10 +383,22 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
         __syncthreads();
         sort_tile<kTile>(s_key, s_pos);
 
-        float *held = nullptr;  // address of the row kept in y[]
+        float *held = nullptr;   // address of the row kept in y[]
+        bool held_warm = true;   // its merge must not lose concurrent updates
         float y[kV], moved[kV];
 #pragma unroll
         for (int j = 0; j < kV; ++j) y[j] = moved[j] = 0.0f;
+
+        // Merge the held row back: add the run's total change atomically, or, for a row that
+        // concurrent samples are unlikely to share (mixed policy) or under the plain
+        // device-scope policy, store the register copy.
+        auto flush = [&]() {
+            if (!held) return;
+            if (kCoherence == kAtomicAgent || (kCoherence == kMixed && held_warm))
+                Io::add(held, lane, moved);
+            else
+                Io::store(held, lane, y);
+        };
 
         for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
             const uint32_t tag = s_key[base + lane];
@@ -375,8 +410,9 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
 #pragma unroll
             for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
             const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
-            uint32_t warm = 0;  // bit 0: u, bit 1: v, bit 2+k: negative k
+            uint32_t warm = 0xFFFFFFFFu;
             if constexpr (kCoherence == kMixed) {
+                warm = 0;
                 if (mine) {
                     warm = (uint32_t)a.warm[p.x] | ((uint32_t)a.warm[p.y] << 1);
 #pragma unroll
@@ -387,129 +423,157 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
             const uint64_t live = __ballot(mine);
             const uint32_t in_chunk = live == ~0ull ? (uint32_t)kWave : (uint32_t)__builtin_ctzll(~live);
 
-            for (uint32_t i = 0; i < in_chunk; ++i) {
-                const uint32_t u = lane_value(p.x, i);
-                const uint32_t v = lane_value(p.y, i);
-                const bool context_side = (lane_value(tag, i) >> 31) != 0;
-                const uint32_t warm_i = lane_value(warm, i);
-                uint32_t nk[kK];
+            auto decode = [&](uint32_t i) {
+                TileSample<kK> s;
+                s.u = lane_value(p.x, i);
+                s.v = lane_value(p.y, i);
 #pragma unroll
-                for (int k = 0; k < kK; ++k) nk[k] = lane_value(neg[k], i);
-                const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
-                const float lrw = lr_i * a.neg_weight;
-                float *want = context_side ? a.context + (size_t)v * D : a.vertex + (size_t)u * D;
-                if (want != held) {
-                    if (held) Io::add(held, lane, moved);
-                    Io::load(want, lane, y);
+                for (int k = 0; k < kK; ++k) s.nk[k] = lane_value(neg[k], i);
+                s.warm = lane_value(warm, i);
+                s.lr = __uint_as_float(lane_value(__float_as_uint(lr), i));
+                s.context_side = (lane_value(tag, i) >> 31) != 0;
+                s.stationary = s.context_side ? a.context + (size_t)s.v * D : a.vertex + (size_t)s.u * D;
+                return s;
+            };
+            // Issue the loads of a sample: its K+1 other rows, and its stationary row when that
+            // is not the row the wave will be holding at that point.  other[0] is context[v]
+            // (vertex side) or vertex[u] (context side); other[1+k] is the context row of negative k.
+            auto fetch = [&](const TileSample<kK> &s, const float *held_then, float (&other)[kK + 1][kV],
+                             float (&fresh)[kV]) {
+                Io::load(s.context_side ? a.vertex + (size_t)s.u * D : a.context + (size_t)s.v * D, lane, other[0]);
 #pragma unroll
-                    for (int j = 0; j < kV; ++j) moved[j] = 0.0f;
-                    held = want;
-                }
+                for (int k = 0; k < kK; ++k) Io::load(a.context + (size_t)s.nk[k] * D, lane, other[1 + k]);
+                if (s.stationary != held_then) Io::load(s.stationary, lane, fresh);
+            };
 
-            if (!context_side) {
-                // y is vertex[u]; context rows v, nk[] are remote
-                uint32_t rows[kK + 1];
-                rows[0] = v;
+            // One sample: switch the held row if needed, then the scores, coefficients and updates.
+            auto train_one = [&](const TileSample<kK> &cur, float (&other)[kK + 1][kV], const float (&fresh)[kV]) {
+                if (cur.stationary != held) {
+                    flush();
 #pragma unroll
-                for (int k = 0; k < kK; ++k) rows[k + 1] = nk[k];
-                float c[kK + 1][kV];
-#pragma unroll
-                for (int k = 0; k <= kK; ++k) Io::load(a.context + (size_t)rows[k] * D, lane, c[k]);
-                float coef[kK + 1];
-#pragma unroll
-                for (int k = 0; k <= kK; ++k) {
-                    float partial = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < kV; ++j) partial = fmaf(y[j], c[k][j], partial);
-                    const float score = wave_sum(partial);
-                    coef[k] = k == 0 ? lr_i * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                    for (int j = 0; j < kV; ++j) {
+                        y[j] = fresh[j];
+                        moved[j] = 0.0f;
+                    }
+                    held = cur.stationary;
+                    held_warm = ((cur.warm >> (cur.context_side ? 1 : 0)) & 1u) != 0;
                 }
+                const float lrw = cur.lr * a.neg_weight;
+
+                if (!cur.context_side) {
+                    // y is vertex[u]; other[] holds context[v] and the negatives' context rows
+                    uint32_t rows[kK + 1];
+                    rows[0] = cur.v;
 #pragma unroll
-                for (int k = 0; k <= kK; ++k) {
-                    bool repeated = false;
+                    for (int k = 0; k < kK; ++k) rows[k + 1] = cur.nk[k];
+                    float coef[kK + 1];
 #pragma unroll
-                    for (int k2 = 0; k2 < k; ++k2) repeated |= rows[k2] == rows[k];
-                    if (repeated) continue;
-                    float total = coef[k];
+                    for (int k = 0; k <= kK; ++k) {
+                        float partial = 0.0f;
 #pragma unroll
-                    for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
-                    remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, (warm_i >> (k + 1)) & 1u, total, y,
-                                                  c[k]);
-                }
+                        for (int j = 0; j < kV; ++j) partial = fmaf(y[j], other[k][j], partial);
+                        const float score = wave_sum(partial);
+                        coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                    }
 #pragma unroll
-                for (int j = 0; j < kV; ++j) {
-                    float acc = 0.0f;
+                    for (int k = 0; k <= kK; ++k) {
+                        bool repeated = false;
 #pragma unroll
-                    for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], c[k][j], acc);
-                    y[j] += acc;
-                    moved[j] += acc;
-                }
-            } else {
-                // y is context[v]; vertex[u] and the negatives' context rows are remote
-                float *xp = a.vertex + (size_t)u * D;
-                float x[kV];
-                Io::load(xp, lane, x);
-                float c[kK][kV];
+                        for (int k2 = 0; k2 < k; ++k2) repeated |= rows[k2] == rows[k];
+                        if (repeated) continue;
+                        float total = coef[k];
 #pragma unroll
-                for (int k = 0; k < kK; ++k) {
-                    if (nk[k] == v) {
+                        for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
+                        remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, (cur.warm >> (k + 1)) & 1u,
+                                                      total, y, other[k]);
+                    }
 #pragma unroll
-                        for (int j = 0; j < kV; ++j) c[k][j] = y[j];
-                    } else {
-                        Io::load(a.context + (size_t)nk[k] * D, lane, c[k]);
+                    for (int j = 0; j < kV; ++j) {
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], other[k][j], acc);
+                        y[j] += acc;
+                        moved[j] += acc;
+                    }
+                } else {
+                    // y is context[v]; other[0] is vertex[u], other[1+k] the negatives' context rows
+                    // (a negative equal to v is the held row itself: its register copy is the fresh one)
+#pragma unroll
+                    for (int k = 0; k < kK; ++k) {
+                        if (cur.nk[k] == cur.v) {
+#pragma unroll
+                            for (int j = 0; j < kV; ++j) other[1 + k][j] = y[j];
+                        }
+                    }
+                    float coef[kK + 1];
+#pragma unroll
+                    for (int k = 0; k <= kK; ++k) {
+                        float partial = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < kV; ++j) partial = fmaf(other[0][j], k == 0 ? y[j] : other[k][j], partial);
+                        const float score = wave_sum(partial);
+                        coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                    }
+                    float dx[kV];
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) {
+                        float acc = coef[0] * y[j];
+#pragma unroll
+                        for (int k = 1; k <= kK; ++k) acc = fmaf(coef[k], other[k][j], acc);
+                        dx[j] = acc;
+                    }
+                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.u * D, lane, cur.warm & 1u, 1.0f, dx, other[0]);
+                    float stay = coef[0];  // coefficient on the held row, negatives equal to v included
+#pragma unroll
+                    for (int k = 0; k < kK; ++k) {
+                        if (cur.nk[k] == cur.v) {
+                            stay += coef[k + 1];
+                            continue;
+                        }
+                        bool repeated = false;
+#pragma unroll
+                        for (int k2 = 0; k2 < k; ++k2) repeated |= cur.nk[k2] == cur.nk[k];
+                        if (repeated) continue;
+                        float total = coef[k + 1];
+#pragma unroll
+                        for (int k2 = k + 1; k2 < kK; ++k2) total += cur.nk[k2] == cur.nk[k] ? coef[k2 + 1] : 0.0f;
+                        remote_update<kV, kCoherence>(a.context + (size_t)cur.nk[k] * D, lane, (cur.warm >> (k + 2)) & 1u,
+                                                      total, other[0], other[1 + k]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kV; ++j) {
+                        const float d = stay * other[0][j];
+                        y[j] += d;
+                        moved[j] += d;
                     }
                 }
-                float coef[kK + 1];
-                {
-                    float partial = 0.0f;
+            };
+
+            // Samples go through in batches of kBatch: all gathers of a batch are issued first,
+            // then the samples are computed one after the other (a later sample of the batch sees
+            // the held row as the earlier ones left it), so one memory round trip serves kBatch
+            // samples instead of one.
+            for (uint32_t i0 = 0; i0 < in_chunk; i0 += kBatch) {
+                TileSample<kK> batch[kBatch];
+                float other[kBatch][kK + 1][kV], fresh[kBatch][kV];
+                const float *then = held;
 #pragma unroll
-                    for (int j = 0; j < kV; ++j) partial = fmaf(x[j], y[j], partial);
-                    coef[0] = lr_i * (1.0f - sigmoid(wave_sum(partial)));
-                }
+                for (int b = 0; b < kBatch; ++b) {
 #pragma unroll
-                for (int k = 0; k < kK; ++k) {
-                    float partial = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < kV; ++j) partial = fmaf(x[j], c[k][j], partial);
-                    coef[k + 1] = -lrw * sigmoid(wave_sum(partial));
-                }
-                float dx[kV];
-#pragma unroll
-                for (int j = 0; j < kV; ++j) {
-                    float acc = coef[0] * y[j];
-#pragma unroll
-                    for (int k = 0; k < kK; ++k) acc = fmaf(coef[k + 1], c[k][j], acc);
-                    dx[j] = acc;
-                }
-                remote_update<kV, kCoherence>(xp, lane, warm_i & 1u, 1.0f, dx, x);
-                float stay = coef[0];  // coefficient on the stationary row, negatives equal to v included
-#pragma unroll
-                for (int k = 0; k < kK; ++k) {
-                    if (nk[k] == v) {
-                        stay += coef[k + 1];
-                        continue;
+                    for (int j = 0; j < kV; ++j) fresh[b][j] = 0.0f;
+                    if (i0 + b < in_chunk) {
+                        batch[b] = decode(i0 + b);
+                        fetch(batch[b], then, other[b], fresh[b]);
+                        then = batch[b].stationary;
                     }
-                    bool repeated = false;
-#pragma unroll
-                    for (int k2 = 0; k2 < k; ++k2) repeated |= nk[k2] == nk[k];
-                    if (repeated) continue;
-                    float total = coef[k + 1];
-#pragma unroll
-                    for (int k2 = k + 1; k2 < kK; ++k2) total += nk[k2] == nk[k] ? coef[k2 + 1] : 0.0f;
-                    remote_update<kV, kCoherence>(a.context + (size_t)nk[k] * D, lane, (warm_i >> (k + 2)) & 1u, total, x,
-                                                  c[k]);
                 }
 #pragma unroll
-                for (int j = 0; j < kV; ++j) {
-                    const float d = stay * x[j];
-                    y[j] += d;
-                    moved[j] += d;
-                }
-            }
+                for (int b = 0; b < kBatch; ++b)
+                    if (i0 + b < in_chunk) train_one(batch[b], other[b], fresh[b]);
             }
             if (in_chunk < (uint32_t)kWave) break;
         }
-        if (held) Io::add(held, lane, moved);
+        flush();
         __syncthreads();  // the next tile overwrites the LDS arrays
     }
 }
