@@ -148,6 +148,24 @@ int gv_train_pool(gv_ctx *ctx);
  * count < 2^32.                                                                */
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
 
+/* Host producer of a pool (Sec. 3.1, Alg. 2, parallel online augmentation): walk number
+ * first_walk + w departs from a node drawn with probability proportional to its degree,
+ * takes walk_length uniform steps over the adjacency (host_offsets[n+1], host_adj[] = CSR
+ * with both directions of every edge), and yields every ordered pair (w_i, w_j),
+ * i < j <= i + window, in order of i then j; walks are concatenated until `count` pairs
+ * exist.  Random numbers: Philox stream 4 of `seed`, counter (walk number, step).
+ * shuffle = GV_SHUFFLE_NONE keeps generation order; GV_SHUFFLE_PSEUDO applies the pseudo
+ * shuffle of Sec. 3.1 (sample t goes to block t mod window of `window` consecutive blocks,
+ * appended in order).  `threads` workers split the walks; the result does not depend on
+ * their number.  host_pairs[count][2] may be any host memory, e.g. a slot returned by
+ * gv_acquire_pool_slot.  Uses no GPU and no context.  *walks_used (may be NULL) receives
+ * the number of walks consumed.  A node without neighbours must not be reachable
+ * (degree-proportional departure never starts at one).                                */
+enum { GV_SHUFFLE_NONE = 0, GV_SHUFFLE_PSEUDO = 1 };
+int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
+               uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
+               uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used);
+
 /* The K negatives of positive samples first_g .. first_g+count-1, exactly as
  * training draws them: host_out[count][K].                                     */
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out);

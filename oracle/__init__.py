@@ -38,6 +38,8 @@ def lib():
         L.orc_augment.restype = C.c_uint64
         L.orc_shuffle.argtypes = [C.c_uint64, C.c_uint64, u32p]
         L.orc_shuffle.restype = None
+        L.orc_pseudo_shuffle.argtypes = [C.c_uint64, C.c_uint32, u32p, u32p]
+        L.orc_pseudo_shuffle.restype = None
         L.orc_init_embeddings.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, f32p, f32p]
         L.orc_init_embeddings.restype = None
         L.orc_learning_rate.argtypes = [C.c_float, C.c_float, C.c_uint64, C.c_uint64]
@@ -113,6 +115,13 @@ def shuffle(seed, pairs):
     pairs = np.array(pairs, dtype=np.uint32, order="C")
     lib().orc_shuffle(seed, pairs.shape[0], _p(pairs, C.c_uint32))
     return pairs
+
+
+def pseudo_shuffle(pairs, s):
+    pairs = np.ascontiguousarray(pairs, dtype=np.uint32)
+    out = np.empty_like(pairs)
+    lib().orc_pseudo_shuffle(pairs.shape[0], s, _p(pairs, C.c_uint32), _p(out, C.c_uint32))
+    return out
 
 
 def init_embeddings(seed, n, d):

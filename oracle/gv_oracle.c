@@ -201,6 +201,26 @@ void orc_shuffle(uint64_t seed, uint64_t count, uint32_t *pairs)
     }
 }
 
+/* Pseudo shuffle (Sec. 3.1): the pool is divided into s consecutive blocks; going through
+ * the samples in generation order, each one is appended to the next block in turn (sample t
+ * to block t mod s), so that the s samples following each other in a walk, which share a
+ * node, are scattered over different blocks; the blocks are then read one after the other.
+ * (The paper gives the idea, not the scatter rule; round-robin is the reading taken.)       */
+void orc_pseudo_shuffle(uint64_t count, uint32_t s, const uint32_t *in, uint32_t *out)
+{
+    uint64_t *fill = (uint64_t *)calloc(s, sizeof(uint64_t));
+    uint64_t *start = (uint64_t *)calloc((size_t)s + 1, sizeof(uint64_t));
+    for (uint64_t t = 0; t < count; ++t) start[t % s + 1] += 1;      /* block sizes */
+    for (uint32_t b = 0; b < s; ++b) start[b + 1] += start[b];         /* block offsets */
+    for (uint64_t t = 0; t < count; ++t) {
+        uint32_t b = (uint32_t)(t % s);
+        uint64_t at = start[b] + fill[b]++;
+        out[2 * at] = in[2 * t];
+        out[2 * at + 1] = in[2 * t + 1];
+    }
+    free(fill); free(start);
+}
+
 /* ------------------------------------------------------------------------- */
 /* Initial embeddings (the paper defers to earlier work; the benchmark
  * configuration fixes it): vertex uniform in (-0.5/d, 0.5/d), context zero.

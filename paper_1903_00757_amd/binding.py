@@ -15,6 +15,7 @@ GV_MODE_HOGWILD, GV_MODE_DETERMINISTIC = 0, 1
 GV_VERTEX, GV_CONTEXT = 0, 1
 GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_MIXED = 0, 1, 2, 3
 GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED = 0, 1
+GV_SHUFFLE_NONE, GV_SHUFFLE_PSEUDO = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
 
@@ -22,7 +23,7 @@ EXPORTS = [
     "gv_create", "gv_destroy", "gv_last_error", "gv_set_graph", "gv_set_degrees", "gv_build_alias", "gv_get_alias",
     "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
-    "gv_sync", "gv_get_stats", "gv_set_position",
+    "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment",
 ]
 
 
@@ -90,6 +91,8 @@ def load():
     L.gv_sync.argtypes = [vp]
     L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
     L.gv_set_position.argtypes = [vp, C.c_uint64]
+    L.gv_augment.argtypes = [C.c_uint32, C.POINTER(C.c_uint64), u32p, C.c_uint64, C.c_uint32, C.c_uint32,
+                             C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, vp, C.POINTER(C.c_uint64)]
     for name in EXPORTS:
         if name not in ("gv_destroy", "gv_last_error"):
             getattr(L, name).restype = C.c_int
@@ -216,3 +219,22 @@ def gv_get_stats(ctx):
 
 def gv_set_position(ctx, next_g):
     _check(ctx, load().gv_set_position(ctx, next_g))
+
+
+def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, count, shuffle=GV_SHUFFLE_PSEUDO,
+               threads=1, out=None):
+    """Fill ``out`` (uint32[count][2], allocated if None; may be a pinned slot view) with walk samples.
+    Returns (pairs, walks_used)."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    adj = np.ascontiguousarray(adj, dtype=np.uint32)
+    if out is None:
+        out = np.empty((count, 2), dtype=np.uint32)
+    if out.dtype != np.uint32 or not out.flags.c_contiguous or out.size < 2 * count:
+        raise ValueError("out must be a C-contiguous uint32 array with room for count pairs")
+    walks = C.c_uint64()
+    rc = load().gv_augment(offsets.size - 1, offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                           adj.ctypes.data_as(C.POINTER(C.c_uint32)), seed, walk_length, window, first_walk, count,
+                           shuffle, threads, C.c_void_p(out.ctypes.data), C.byref(walks))
+    if rc != GV_OK:
+        raise GvError(rc, "gv_augment: bad argument")
+    return out[:count], walks.value

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgvhot.so")
-SOURCES = ["gv_kernels.hip", "gv_api.cpp"]
+SOURCES = ["gv_kernels.hip", "gv_api.cpp", "gv_augment.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Wall", "-Wextra", "-Wno-unused-parameter",
           # packed-fp32 instructions are kept out of the generated code on purpose
@@ -30,7 +30,7 @@ def build(verbose: bool = False) -> str:
     for src in SOURCES:
         obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
         cmd = [HIPCC, *COMMON, "-c", os.path.join(CSRC, src), "-o", obj]
-        if src.endswith(".cpp"):
+        if src == "gv_api.cpp":  # uses the HIP vector types in its interface to the kernels
             cmd.insert(1, "-x")
             cmd.insert(2, "hip")
         if verbose:
@@ -45,7 +45,7 @@ def build(verbose: bool = False) -> str:
         if verbose and out:
             print(out)
     tmp = LIB + f".{os.getpid()}.tmp"
-    subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objects])
+    subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objects, "-lpthread"])
     os.replace(tmp, LIB)
     return LIB
 

@@ -1,0 +1,101 @@
+// Host producer of sample pools: parallel online augmentation (Sec. 3.1, Alg. 2) with the
+// cache-friendly pseudo shuffle of the same section.  Pure host code: it writes into any
+// caller buffer, in particular into the pinned pool slots of a context.
+#include <stdint.h>
+
+#include <algorithm>
+#include <thread>
+#include <vector>
+
+#include "gvhot.h"
+
+namespace {
+
+struct Words {
+    uint32_t w[4];
+};
+
+// Philox4x32-10 (Salmon et al., SC'11), counter (index lo, index hi, sub-index, stream).
+inline Words philox(uint64_t seed, uint64_t index, uint32_t sub, uint32_t stream) {
+    uint32_t c0 = (uint32_t)index, c1 = (uint32_t)(index >> 32), c2 = sub, c3 = stream;
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t a = 0xD2511F53ull * c0, b = 0xCD9E8D57ull * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0, n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Words{{c0, c1, c2, c3}};
+}
+
+// uniform integer in [0, range) from the first two words
+inline uint64_t pick(const Words &r, uint64_t range) {
+    const unsigned __int128 wide = (unsigned __int128)(((uint64_t)r.w[0] << 32) | r.w[1]) * range;
+    return (uint64_t)(wide >> 64);
+}
+
+constexpr uint32_t kWalkStream = 4;
+
+}  // namespace
+
+extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
+                          uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
+                          uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
+    if (walks_used) *walks_used = 0;
+    if (count == 0) return GV_OK;
+    if (!host_offsets || !host_adj || !host_pairs || n == 0 || walk_length == 0 || window == 0 ||
+        shuffle > GV_SHUFFLE_PSEUDO)
+        return GV_EINVAL;
+    const uint64_t half_edges = host_offsets[n];
+    if (half_edges == 0) return GV_EINVAL;
+    const uint32_t L = walk_length, s = window;
+    uint64_t per_walk = 0;  // pairs (i, j), i < j <= min(i + s, L)
+    for (uint32_t d = 1; d <= s && d <= L; ++d) per_walk += L + 1 - d;
+    const uint64_t walks = (count + per_walk - 1) / per_walk;
+    if (walks_used) *walks_used = walks;
+
+    // Pseudo shuffle: the pool is cut into `s` consecutive blocks and sample number t (in
+    // generation order) is appended to block t mod s, so the s samples that follow each other
+    // inside a walk (and share a node) end up a block apart while every block is written
+    // sequentially.  Block b holds the samples t = b, b + s, b + 2s, ...
+    std::vector<uint64_t> block_start(s + 1, 0);
+    for (uint32_t b = 0; b < s; ++b) block_start[b + 1] = block_start[b] + (count > b ? (count - b + s - 1) / s : 0);
+
+    const uint32_t workers = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(threads ? threads : 1, walks));
+    auto work = [&](uint32_t worker) {
+        std::vector<uint32_t> path(L + 1);
+        const uint64_t lo = walks * worker / workers, hi = walks * (worker + 1) / workers;
+        for (uint64_t w = lo; w < hi; ++w) {
+            // departure: owner of a uniformly chosen half-edge = probability proportional to degree
+            const uint64_t e = pick(philox(seed, first_walk + w, 0, kWalkStream), half_edges);
+            const uint64_t *owner = std::upper_bound(host_offsets, host_offsets + n + 1, e) - 1;
+            path[0] = (uint32_t)(owner - host_offsets);
+            for (uint32_t t = 1; t <= L; ++t) {
+                const uint32_t x = path[t - 1];
+                const uint64_t begin = host_offsets[x], degree = host_offsets[x + 1] - begin;
+                path[t] = host_adj[begin + pick(philox(seed, first_walk + w, t, kWalkStream), degree)];
+            }
+            uint64_t t_global = w * per_walk;
+            for (uint32_t i = 0; i <= L; ++i)
+                for (uint32_t j = i + 1; j <= L && j <= i + s; ++j, ++t_global) {
+                    if (t_global >= count) return;
+                    const uint64_t at = shuffle == GV_SHUFFLE_PSEUDO ? block_start[t_global % s] + t_global / s : t_global;
+                    host_pairs[2 * at] = path[i];
+                    host_pairs[2 * at + 1] = path[j];
+                }
+        }
+    };
+    if (workers == 1) {
+        work(0);
+    } else {
+        std::vector<std::thread> pool;
+        pool.reserve(workers);
+        for (uint32_t i = 0; i < workers; ++i) pool.emplace_back(work, i);
+        for (std::thread &t : pool) t.join();
+    }
+    return GV_OK;
+}
