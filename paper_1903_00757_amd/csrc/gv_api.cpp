@@ -46,8 +46,7 @@ struct gv_ctx {
     float *context = nullptr;
     uint2 *alias = nullptr;
     bool alias_ready = false;
-    uint32_t *dev_degree = nullptr;       // device copy of the degrees (grouping key)
-    uint8_t *dev_warm = nullptr;          // device, per node: updates must not be lost
+    uint8_t *dev_heat = nullptr;          // device, per node: degree class (bits 0..6) and warm flag (bit 7)
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
@@ -139,14 +138,18 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->vertex) (void)hipFree(ctx->vertex);
     if (ctx->context) (void)hipFree(ctx->context);
     if (ctx->alias) (void)hipFree(ctx->alias);
-    if (ctx->dev_degree) (void)hipFree(ctx->dev_degree);
-    if (ctx->dev_warm) (void)hipFree(ctx->dev_warm);
+    if (ctx->dev_heat) (void)hipFree(ctx->dev_heat);
 
     ctx->vertex = ctx->context = nullptr;
     ctx->alias = nullptr;
-    ctx->dev_degree = nullptr;
-    ctx->dev_warm = nullptr;
+    ctx->dev_heat = nullptr;
     ctx->alias_ready = false;
+}
+
+// Logarithmic degree class in 7 bits: min(127, floor(4 log2(1 + degree))).
+uint32_t degree_class(uint32_t degree) {
+    const double c = floor(4.0 * log2(1.0 + (double)degree));
+    return c > 127.0 ? 127u : (uint32_t)c;
 }
 
 int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
@@ -158,10 +161,13 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     GV_HIP(ctx, hipMalloc((void **)&ctx->vertex, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->context, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint2)));
-    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_degree, (size_t)n * sizeof(uint32_t)));
-    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_warm, (size_t)n));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_degree, deg.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemset(ctx->dev_warm, 1, (size_t)n));
+    {
+        // until the alias table is built (it fixes the negative-sampling shares) every row counts as warm
+        std::vector<uint8_t> heat(n);
+        for (uint32_t i = 0; i < n; ++i) heat[i] = (uint8_t)(0x80u | degree_class(deg[i]));
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_heat, (size_t)n));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_heat, heat.data(), (size_t)n, hipMemcpyHostToDevice));
+    }
     GV_HIP(ctx, hipMemsetAsync(ctx->vertex, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
@@ -205,7 +211,7 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.alias = ctx->alias;
     a.pairs = dev_pairs;
     a.negatives = nullptr;
-    a.warm = ctx->dev_warm;
+    a.heat = ctx->dev_heat;
     a.error_flag = ctx->error_flag;
     a.first_g = first_g;
     a.total = ctx->cfg.total_samples;
@@ -249,8 +255,7 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
     if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u)
-        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->dev_degree, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence,
-                                           ctx->compute));
+        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
     else
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
     ctx->stats.train_launches += 1;
@@ -507,7 +512,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     std::vector<uint8_t> warm(n);
     for (uint32_t i = 0; i < n; ++i) {
         const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
-        warm[i] = share * kInFlight > warm_threshold ? 1 : 0;
+        warm[i] = (uint8_t)((share * kInFlight > warm_threshold ? 0x80u : 0u) | degree_class(ctx->degree[i]));
     }
     std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
     below.reserve(n);
@@ -536,7 +541,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     rc = sync_all(ctx);
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
     GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint2), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_warm, warm.data(), (size_t)n, hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_heat, warm.data(), (size_t)n, hipMemcpyHostToDevice));
     ctx->alias_ready = true;
     return GV_OK;
 }

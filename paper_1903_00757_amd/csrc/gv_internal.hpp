@@ -14,7 +14,8 @@ struct TrainArgs {
     const uint2 *alias;       // per node {threshold, alias}
     const uint32_t *pairs;    // count x (u, v)
     const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
-    const uint8_t *warm;      // per node: 1 = updates of this row must not be lost (see gv_build_alias)
+    const uint8_t *heat;      // per node: bits 0..6 degree class min(127, floor(4 log2(1 + degree))), bit 7 =
+                              // warm: updates of this row must not be lost (see gv_build_alias)
     uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
     uint64_t first_g;         // global position of pairs[0]
     uint64_t total;           // T of the learning-rate schedule
@@ -27,10 +28,9 @@ struct TrainArgs {
 // Launch shapes are chosen here; both return the HIP error of the launch.
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
                                 hipStream_t stream);
-// Tiled stationary-row training (see k_train_tiled); degree[] is the device copy of the
-// node degrees and decides which row of a sample is kept in registers.
-hipError_t launch_train_tiled(const TrainArgs &a, const uint32_t *degree, uint32_t dim, uint32_t num_neg,
-                              uint32_t coherence, hipStream_t stream);
+// Tiled stationary-row training (see k_train_tiled).
+hipError_t launch_train_tiled(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                              hipStream_t stream);
 // One wave per sample over samples [0, a.count): the caller guarantees that no
 // two of them share a vertex row or a context row (negatives included).
 hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);

@@ -303,7 +303,8 @@ __device__ __forceinline__ void remote_update(float *row, int lane, bool warm, f
 // ---------------------------------------------------------------------------
 // Tiled stationary-row training.  A workgroup takes a tile of kTile consecutive samples
 // of the pool, tags every sample with its hotter row (the higher-degree one of u, v:
-// vertex[u] = side 0, context[v] = side 1) and sorts the tile by that row in LDS, so
+// vertex[u] = side 0, context[v] = side 1; decided by a one-byte degree class per node)
+// and sorts the tile by that row in LDS, so
 // that samples sharing their hot row become adjacent.  Each of its four waves then walks
 // a quarter of the sorted tile and keeps the hot row in registers for as long as
 // consecutive samples name it: the row is read once per run, the run's updates are
@@ -349,11 +350,12 @@ struct TileSample {
 };
 
 template <int kV, int kK, int kCoherence, int kTile>
-__global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint32_t *__restrict__ degree) {
+__global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     constexpr int D = kV * kWave;
     constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
+    static_assert(kTile <= 65536, "the slot number of a sample shares its word with two flags");
     // samples whose gathers are in flight together: bounded by the registers their rows take
     constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
     using Io = RowIo<kV, kCoherence>;
@@ -367,18 +369,21 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint32_t tile_base = tile * kTile;
         for (uint32_t t = threadIdx.x; t < (uint32_t)kTile; t += kBlock) {
-            uint32_t key = kSkip;
+            uint32_t key = kSkip, slot = t;
             if (tile_base + t < a.count) {
                 const uint2 p = pairs[tile_base + t];
                 if (p.x < a.n && p.y < a.n) {
-                    const bool context_side = degree[p.x] < degree[p.y];
+                    // heat byte: bits 0..6 a logarithmic degree class, bit 7 the warm flag
+                    const uint32_t hu = a.heat[p.x], hv = a.heat[p.y];
+                    const bool context_side = (hu & 127u) < (hv & 127u);
                     key = context_side ? (0x80000000u | p.y) : p.x;
+                    slot |= (hu >> 7) << 30 | (hv >> 7) << 31;  // warm flags of u and v ride along
                 } else {
                     *a.error_flag = 1u;  // the sample is skipped and reported at the next synchronisation
                 }
             }
             s_key[t] = key;
-            s_pos[t] = t;
+            s_pos[t] = slot;
         }
         __syncthreads();
         sort_tile<kTile>(s_key, s_pos);
@@ -403,7 +408,8 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
         for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
             const uint32_t tag = s_key[base + lane];
             const bool mine = tag != kSkip;
-            const uint32_t pos = tile_base + s_pos[base + lane];
+            const uint32_t slot = s_pos[base + lane];
+            const uint32_t pos = tile_base + (slot & 0xFFFFu);
             const uint2 p = mine ? pairs[pos] : make_uint2(0u, 0u);
             const uint64_t g = a.first_g + pos;
             uint32_t neg[kK];
@@ -414,9 +420,9 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a, const uint3
             if constexpr (kCoherence == kMixed) {
                 warm = 0;
                 if (mine) {
-                    warm = (uint32_t)a.warm[p.x] | ((uint32_t)a.warm[p.y] << 1);
+                    warm = slot >> 30;
 #pragma unroll
-                    for (int k = 0; k < kK; ++k) warm |= (uint32_t)a.warm[neg[k]] << (2 + k);
+                    for (int k = 0; k < kK; ++k) warm |= ((uint32_t)a.heat[neg[k]] >> 7) << (2 + k);
                 }
             }
             // sorted order puts the skipped slots last: the first one ends this wave's work
@@ -675,29 +681,27 @@ hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t
 }
 
 template <int kV, int kK, int kTile>
-hipError_t launch_tiled_vkt(const TrainArgs &a, const uint32_t *degree, uint32_t coherence, uint32_t blocks,
-                            hipStream_t stream) {
+hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
     if (coherence == kAgent)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a, degree);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
     else if (coherence == kMixed)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a, degree);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
     else
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a,
-                           degree);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
 template <int kV, int kK>
-hipError_t launch_tiled_vk(const TrainArgs &a, const uint32_t *degree, uint32_t coherence, hipStream_t stream) {
+hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
-    if (degree == nullptr || a.n > 0x80000000u) return hipErrorInvalidValue;
+    if (a.heat == nullptr || a.n > 0x80000000u) return hipErrorInvalidValue;
     static const uint32_t tile = env_u32("GV_TILE", 1024u);  // tuning sweeps: 512, 1024 or 2048
     uint32_t blocks = hogwild_blocks(a.count, a.n);
     const uint32_t tiles = (a.count + tile - 1) / tile;
     if (blocks > tiles) blocks = tiles;
-    if (tile == 512) return launch_tiled_vkt<kV, kK, 512>(a, degree, coherence, blocks, stream);
-    if (tile == 2048) return launch_tiled_vkt<kV, kK, 2048>(a, degree, coherence, blocks, stream);
-    return launch_tiled_vkt<kV, kK, 1024>(a, degree, coherence, blocks, stream);
+    if (tile == 512) return launch_tiled_vkt<kV, kK, 512>(a, coherence, blocks, stream);
+    if (tile == 2048) return launch_tiled_vkt<kV, kK, 2048>(a, coherence, blocks, stream);
+    return launch_tiled_vkt<kV, kK, 1024>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -739,9 +743,9 @@ hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_n
 #undef GV_CALL
 }
 
-hipError_t launch_train_tiled(const TrainArgs &a, const uint32_t *degree, uint32_t dim, uint32_t num_neg,
-                              uint32_t coherence, hipStream_t stream) {
-#define GV_CALL(V, K) launch_tiled_vk<V, K>(a, degree, coherence, stream)
+hipError_t launch_train_tiled(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                              hipStream_t stream) {
+#define GV_CALL(V, K) launch_tiled_vk<V, K>(a, coherence, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }
