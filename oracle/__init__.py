@@ -42,6 +42,8 @@ def lib():
         L.orc_pseudo_shuffle.restype = None
         L.orc_init_embeddings.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, f32p, f32p]
         L.orc_init_embeddings.restype = None
+        L.orc_init_vertex_rows.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, f32p]
+        L.orc_init_vertex_rows.restype = None
         L.orc_learning_rate.argtypes = [C.c_float, C.c_float, C.c_uint64, C.c_uint64]
         L.orc_learning_rate.restype = C.c_float
         L.orc_train.argtypes = [f32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, u32p, C.c_uint64,
@@ -129,6 +131,13 @@ def init_embeddings(seed, n, d):
     context = np.empty((n, d), dtype=np.float32)
     lib().orc_init_embeddings(seed, n, d, _p(vertex, C.c_float), _p(context, C.c_float))
     return vertex, context
+
+
+def init_vertex_rows(seed, row0, rows, d):
+    """Initial vertex rows row0 .. row0+rows-1 (the initial value of a row depends on nothing else)."""
+    vertex = np.empty((rows, d), dtype=np.float32)
+    lib().orc_init_vertex_rows(seed, row0, rows, d, _p(vertex, C.c_float))
+    return vertex
 
 
 def learning_rate(lr0, lr_min_ratio, g, T):

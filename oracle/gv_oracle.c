@@ -225,15 +225,20 @@ void orc_pseudo_shuffle(uint64_t count, uint32_t s, const uint32_t *in, uint32_t
 /* Initial embeddings (the paper defers to earlier work; the benchmark
  * configuration fixes it): vertex uniform in (-0.5/d, 0.5/d), context zero.
  * Element (row, col) takes word col%4 of the block (row, col/4).             */
-void orc_init_embeddings(uint64_t seed, uint64_t n, uint32_t d, float *vertex, float *context)
+void orc_init_vertex_rows(uint64_t seed, uint64_t row0, uint64_t rows, uint32_t d, float *vertex)
 {
-    for (uint64_t row = 0; row < n; ++row)
+    for (uint64_t i = 0; i < rows; ++i)
         for (uint32_t col = 0; col < d; ++col) {
             uint32_t r[4];
-            words(seed, row, col / 4, STREAM_INIT, r);
+            words(seed, row0 + i, col / 4, STREAM_INIT, r);
             double unit = ((double)r[col % 4] + 0.5) * (1.0 / 4294967296.0);
-            vertex[row * d + col] = (float)((unit - 0.5) / (double)d);
+            vertex[i * d + col] = (float)((unit - 0.5) / (double)d);
         }
+}
+
+void orc_init_embeddings(uint64_t seed, uint64_t n, uint32_t d, float *vertex, float *context)
+{
+    orc_init_vertex_rows(seed, 0, n, d, vertex);
     memset(context, 0, (size_t)n * d * sizeof(float));
 }
 

@@ -605,3 +605,54 @@ def test_full_size_pool_tracks_the_sequential_oracle(gv, c2_workload, c2_oracle_
     assert loss_ref < 0.95 * loss_start  # the pool does train
     assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
     assert 0.8 < np.median(ratios[0]) < 1.25 and 0.8 < np.median(ratios[1]) < 1.25
+
+
+def test_rows_beyond_2_to_32_elements(gv):
+    """A table of 4*10^7 rows x 128 (5.1*10^9 elements per matrix, 41 GB for both): samples that name
+    rows at the far end must be read and written at the right 64-bit offsets.  With the initial
+    embeddings (vertex from the counter-based generator, context zero) every isolated sample has the
+    closed form of the oracle's single step."""
+    n, d, K, w, seed, count, T = 40_000_000, 128, 1, 5.0, 77, 4099, 10**9
+    deg = np.ones(n, dtype=np.uint32)
+    rng = np.random.default_rng(5)
+    far = n - 1 - rng.choice(5_000_000, size=2 * count, replace=False).astype(np.int64)  # last 5 M rows
+    pool = np.stack([far[:count], far[count:]], axis=1).astype(np.uint32)
+    pool[0] = (n - 1, n - 2)
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=count, lr0=LR0) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, 9)
+        negs = gv.gv_draw_negatives(ctx, 0, count, K)
+        gv.gv_push_pool(ctx, pool)
+        gv.gv_train_pool(ctx)
+        gv.gv_sync(ctx)
+        # uniform table: the oracle's draw is the bucket itself
+        thresh = np.full(1, 0xFFFFFFFF, dtype=np.uint32)
+        touched_c = np.concatenate([pool[:, 1], negs[:, 0]])
+        uniq, counts = np.unique(touched_c, return_counts=True)
+        once = set(uniq[counts == 1].tolist())
+        check = [i for i in range(count) if int(pool[i, 1]) in once and int(negs[i, 0]) in once][:400]
+        assert len(check) >= 300
+        worst = 0.0
+        for i in check:
+            u, v, z = int(pool[i, 0]), int(pool[i, 1]), int(negs[i, 0])
+            x0 = oracle.init_vertex_rows(9, u, 1, d)
+            sub_v, sub_c = x0.copy(), np.zeros((2, d), dtype=np.float32)
+            oracle.train(sub_v, sub_c, np.array([[0, 0]], dtype=np.uint32), K=1, first_g=i, T=T, lr0=LR0,
+                         lr_min_ratio=0.0, w=w, seed=seed, thresh=thresh, alias=thresh,
+                         negatives=np.array([1], dtype=np.uint32))
+            got_x = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=u)[0]
+            got_v = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=v)[0]
+            got_z = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=z)[0]
+            scale = np.abs(x0).max()
+            worst = max(worst, np.abs(got_x - sub_v[0]).max() / scale, np.abs(got_v - sub_c[0]).max() / scale,
+                        np.abs(got_z - sub_c[1]).max() / scale)
+            assert np.abs(got_v).max() > 0 and np.abs(got_z).max() > 0
+        assert worst <= 1e-5, worst
+        # rows nobody names keep their initial value, at both ends of the table
+        first = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 2, d, row0=0)
+        assert np.array_equal(first, oracle.init_vertex_rows(9, 0, 2, d))
+        last = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=n - 3)
+        if (n - 3) not in set(pool[:, 0].tolist()):
+            assert np.array_equal(last, oracle.init_vertex_rows(9, n - 3, 1, d))
