@@ -66,7 +66,7 @@ enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT
 enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1 };
 
 typedef struct gv_config {
-    uint32_t dim;            /* d: 64, 128, 256 or 512                                        */
+    uint32_t dim;            /* d: a multiple of 32 in 32..512 (128, or 96 in Sec. 4.3)       */
     uint32_t num_neg;        /* K negatives per positive sample, 1..5                         */
     float lr0;               /* initial learning rate (0.025 in Sec. 4.3)                      */
     float lr_min_ratio;      /* floor of the linear decay as a fraction of lr0 (0 = none)      */

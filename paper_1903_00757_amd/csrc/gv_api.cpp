@@ -218,6 +218,7 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.seed = ctx->cfg.seed;
     a.count = count;
     a.n = ctx->n;
+    a.dim = ctx->cfg.dim;
     a.lr0 = ctx->cfg.lr0;
     a.lr_min_ratio = ctx->cfg.lr_min_ratio;
     a.neg_weight = ctx->cfg.neg_weight;
@@ -378,7 +379,7 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
     if (out) *out = nullptr;
     if (!cfg || !out) return fail(nullptr, GV_EINVAL, "null argument");
     if (!gv::supported_shape(cfg->dim, cfg->num_neg))
-        return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (64/128/256/512), num_neg %u (1..5)", cfg->dim,
+        return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (a multiple of 32 in 32..512), num_neg %u (1..5)", cfg->dim,
                     cfg->num_neg);
     if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
     if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 32))

@@ -22,6 +22,7 @@ struct TrainArgs {
     uint64_t seed;            // Philox key of the negative stream
     uint32_t count;           // samples in this launch
     uint32_t n;               // |V|
+    uint32_t dim;             // d: row length in floats
     float lr0, lr_min_ratio, neg_weight;
 };
 

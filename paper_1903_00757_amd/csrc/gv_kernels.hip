@@ -95,9 +95,15 @@ struct RowIo {
     static constexpr int W = is_agent(kCoherence) ? (kV >= 2 ? 2 : 1) : (kV >= 4 ? 4 : kV);
     static constexpr int S = kV / W;
 
-    static __device__ __forceinline__ void load(const float *row, int lane, float (&x)[kV]) {
+    // dim (a multiple of 32, at most 64 * kV) is the row length: lanes past the end hold zeros
+    static __device__ __forceinline__ void load(const float *row, int lane, uint32_t dim, float (&x)[kV]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
+            if ((uint32_t)(s * (kWave * W) + lane * W) >= dim) {
+#pragma unroll
+                for (int e = 0; e < W; ++e) x[s * W + e] = 0.0f;
+                continue;
+            }
             const float *p = row + s * (kWave * W) + lane * W;
             if constexpr (is_agent(kCoherence)) {
                 if constexpr (W == 2) {
@@ -125,7 +131,7 @@ struct RowIo {
     // per element.  With two floats per lane the values are first exchanged between lanes
     // (lane l takes elements l and l + 64 of the 128-float segment) so that every atomic
     // instruction covers 256 contiguous bytes instead of every other word of 512.
-    static __device__ __forceinline__ void add(float *row, int lane, const float (&delta)[kV]) {
+    static __device__ __forceinline__ void add(float *row, int lane, uint32_t dim, const float (&delta)[kV]) {
         static_assert(W <= 2, "atomic adds are used with the device-scope layouts only");
 #pragma unroll
         for (int s = 0; s < S; ++s) {
@@ -137,18 +143,22 @@ struct RowIo {
                 const float first = __int_as_float((lane & 1) ? lo1 : lo0);
                 const float second = __int_as_float((lane & 1) ? hi1 : hi0);
                 float *p = row + s * (kWave * 2) + lane;
-                (void)__hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                (void)__hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(s * (kWave * 2) + lane) < dim)
+                    (void)__hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
+                    (void)__hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                (void)__hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(s * kWave + lane) < dim)
+                    (void)__hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
 
-    static __device__ __forceinline__ void store(float *row, int lane, const float (&x)[kV]) {
+    static __device__ __forceinline__ void store(float *row, int lane, uint32_t dim, const float (&x)[kV]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
+            if ((uint32_t)(s * (kWave * W) + lane * W) >= dim) continue;
             float *p = row + s * (kWave * W) + lane * W;
             if constexpr (is_agent(kCoherence)) {
                 if constexpr (W == 2) {
@@ -184,15 +194,14 @@ __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + __expf
 // coefficient.  u and rows[] are wave-uniform.
 template <int kV, int kK, int kCoherence>
 __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__restrict__ context, uint32_t u,
-                                          const uint32_t (&rows)[kK + 1], float lr, float w, int lane) {
-    constexpr int D = kV * kWave;
+                                          const uint32_t (&rows)[kK + 1], float lr, float w, int lane, uint32_t D) {
     using Io = RowIo<kV, kCoherence>;
     float *xp = vertex + (size_t)u * D;
     float x[kV];
     float c[kK + 1][kV];
-    Io::load(xp, lane, x);
+    Io::load(xp, lane, D, x);
 #pragma unroll
-    for (int k = 0; k <= kK; ++k) Io::load(context + (size_t)rows[k] * D, lane, c[k]);
+    for (int k = 0; k <= kK; ++k) Io::load(context + (size_t)rows[k] * D, lane, D, c[k]);
 
     float coef[kK + 1];
 #pragma unroll
@@ -226,19 +235,19 @@ __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__r
             float dc[kV];
 #pragma unroll
             for (int j = 0; j < kV; ++j) dc[j] = total * x[j];
-            Io::add(context + (size_t)rows[k] * D, lane, dc);
+            Io::add(context + (size_t)rows[k] * D, lane, D, dc);
         } else {
 #pragma unroll
             for (int j = 0; j < kV; ++j) c[k][j] = fmaf(total, x[j], c[k][j]);
-            Io::store(context + (size_t)rows[k] * D, lane, c[k]);
+            Io::store(context + (size_t)rows[k] * D, lane, D, c[k]);
         }
     }
     if constexpr (is_atomic(kCoherence)) {
-        Io::add(xp, lane, dx);
+        Io::add(xp, lane, D, dx);
     } else {
 #pragma unroll
         for (int j = 0; j < kV; ++j) dx[j] += x[j];
-        Io::store(xp, lane, dx);
+        Io::store(xp, lane, D, dx);
     }
 }
 
@@ -275,7 +284,7 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
 #pragma unroll
             for (int k = 0; k < kK; ++k) rows[k + 1] = lane_value(neg[k], i);
             const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
-            sgns_step<kV, kK, kCoherence>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane);
+            sgns_step<kV, kK, kCoherence>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane, a.dim);
         }
     }
 }
@@ -284,19 +293,19 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
 // every concurrent update; the plain variant writes back loaded + total * other and can
 // lose an update that another wave makes between this wave's load and store.
 template <int kV, int kCoherence>
-__device__ __forceinline__ void remote_update(float *row, int lane, bool warm, float total, const float (&other)[kV],
-                                              const float (&loaded)[kV]) {
+__device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, bool warm, float total,
+                                              const float (&other)[kV], const float (&loaded)[kV]) {
     using Io = RowIo<kV, kCoherence>;
     if (kCoherence == kAtomicAgent || (kCoherence == kMixed && warm)) {
         float d[kV];
 #pragma unroll
         for (int j = 0; j < kV; ++j) d[j] = total * other[j];
-        Io::add(row, lane, d);
+        Io::add(row, lane, D, d);
     } else {
         float r[kV];
 #pragma unroll
         for (int j = 0; j < kV; ++j) r[j] = fmaf(total, other[j], loaded[j]);
-        Io::store(row, lane, r);
+        Io::store(row, lane, D, r);
     }
 }
 
@@ -351,7 +360,7 @@ struct TileSample {
 
 template <int kV, int kK, int kCoherence, int kTile>
 __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
-    constexpr int D = kV * kWave;
+    const uint32_t D = a.dim;
     constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
@@ -400,9 +409,9 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
         auto flush = [&]() {
             if (!held) return;
             if (kCoherence == kAtomicAgent || (kCoherence == kMixed && held_warm))
-                Io::add(held, lane, moved);
+                Io::add(held, lane, D, moved);
             else
-                Io::store(held, lane, y);
+                Io::store(held, lane, D, y);
         };
 
         for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
@@ -446,10 +455,10 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             // (vertex side) or vertex[u] (context side); other[1+k] is the context row of negative k.
             auto fetch = [&](const TileSample<kK> &s, const float *held_then, float (&other)[kK + 1][kV],
                              float (&fresh)[kV]) {
-                Io::load(s.context_side ? a.vertex + (size_t)s.u * D : a.context + (size_t)s.v * D, lane, other[0]);
+                Io::load(s.context_side ? a.vertex + (size_t)s.u * D : a.context + (size_t)s.v * D, lane, D, other[0]);
 #pragma unroll
-                for (int k = 0; k < kK; ++k) Io::load(a.context + (size_t)s.nk[k] * D, lane, other[1 + k]);
-                if (s.stationary != held_then) Io::load(s.stationary, lane, fresh);
+                for (int k = 0; k < kK; ++k) Io::load(a.context + (size_t)s.nk[k] * D, lane, D, other[1 + k]);
+                if (s.stationary != held_then) Io::load(s.stationary, lane, D, fresh);
             };
 
             // One sample: switch the held row if needed, then the scores, coefficients and updates.
@@ -490,7 +499,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                         float total = coef[k];
 #pragma unroll
                         for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
-                        remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, (cur.warm >> (k + 1)) & 1u,
+                        remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, D, (cur.warm >> (k + 1)) & 1u,
                                                       total, y, other[k]);
                     }
 #pragma unroll
@@ -528,7 +537,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                         for (int k = 1; k <= kK; ++k) acc = fmaf(coef[k], other[k][j], acc);
                         dx[j] = acc;
                     }
-                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.u * D, lane, cur.warm & 1u, 1.0f, dx, other[0]);
+                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.u * D, lane, D, cur.warm & 1u, 1.0f, dx, other[0]);
                     float stay = coef[0];  // coefficient on the held row, negatives equal to v included
 #pragma unroll
                     for (int k = 0; k < kK; ++k) {
@@ -543,7 +552,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                         float total = coef[k + 1];
 #pragma unroll
                         for (int k2 = k + 1; k2 < kK; ++k2) total += cur.nk[k2] == cur.nk[k] ? coef[k2 + 1] : 0.0f;
-                        remote_update<kV, kCoherence>(a.context + (size_t)cur.nk[k] * D, lane, (cur.warm >> (k + 2)) & 1u,
+                        remote_update<kV, kCoherence>(a.context + (size_t)cur.nk[k] * D, lane, D, (cur.warm >> (k + 2)) & 1u,
                                                       total, other[0], other[1 + k]);
                     }
 #pragma unroll
@@ -602,7 +611,7 @@ __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
 #pragma unroll
     for (int k = 0; k < kK; ++k) rows[k + 1] = a.negatives[(size_t)i * kK + k];
     const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + i, a.total);
-    sgns_step<kV, kK, kPlain>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane);
+    sgns_step<kV, kK, kPlain>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim);
 }
 
 __global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
@@ -715,7 +724,7 @@ hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
 }  // namespace
 
 bool supported_shape(uint32_t dim, uint32_t num_neg) {
-    return (dim == 64 || dim == 128 || dim == 256 || dim == 512) && num_neg >= 1 && num_neg <= 5;
+    return dim >= 32 && dim <= 512 && dim % 32 == 0 && num_neg >= 1 && num_neg <= 5;
 }
 
 #define GV_DISPATCH_K(V, CALL)                 \
@@ -727,14 +736,13 @@ bool supported_shape(uint32_t dim, uint32_t num_neg) {
         case 5: return CALL(V, 5);             \
         default: return hipErrorInvalidValue;  \
     }
-#define GV_DISPATCH(CALL)                           \
-    switch (dim) {                                  \
-        case 64: GV_DISPATCH_K(1, CALL)             \
-        case 128: GV_DISPATCH_K(2, CALL)            \
-        case 256: GV_DISPATCH_K(4, CALL)            \
-        case 512: GV_DISPATCH_K(8, CALL)            \
-        default: return hipErrorInvalidValue;       \
-    }
+// a lane holds V floats of a row: the smallest V in {1, 2, 4, 8} with 64 V >= dim
+#define GV_DISPATCH(CALL)                                                   \
+    if (!supported_shape(dim, num_neg) || a.dim != dim) return hipErrorInvalidValue; \
+    if (dim <= 64) { GV_DISPATCH_K(1, CALL) }                               \
+    if (dim <= 128) { GV_DISPATCH_K(2, CALL) }                              \
+    if (dim <= 256) { GV_DISPATCH_K(4, CALL) }                              \
+    GV_DISPATCH_K(8, CALL)
 
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
                                 hipStream_t stream) {

@@ -68,7 +68,7 @@ def test_set_graph_counts_degrees(gv, tiny_graph, tiny_alias):
     assert np.array_equal(thresh, tiny_alias[0]) and np.array_equal(alias, tiny_alias[1])
 
 
-@pytest.mark.parametrize("d", [64, 128, 512])
+@pytest.mark.parametrize("d", [64, 96, 128, 512])
 def test_initial_embeddings_are_bit_identical(gv, d):
     n = 3001
     with context_for(gv, dim=d, num_neg=1, total_samples=1, pool_capacity=1) as ctx:
@@ -142,7 +142,9 @@ def run_oracle(deg, K, w, pools, vertex, context, T, seed, lr_min=0.0):
 
 
 @pytest.mark.parametrize("d,K,w,count", [(128, 1, 5.0, 100_003), (64, 2, 2.5, 40_001), (256, 3, 1.0, 30_000),
-                                         (512, 5, 1.0, 20_011), (128, 5, 1.0, 50_000), (128, 4, 1.25, 1)])
+                                         (512, 5, 1.0, 20_011), (128, 5, 1.0, 50_000), (128, 4, 1.25, 1),
+                                         (96, 1, 5.0, 60_007), (32, 2, 2.5, 20_000), (160, 1, 5.0, 20_000),
+                                         (480, 5, 1.0, 10_000)])
 def test_deterministic_mode_matches_sequential_oracle(gv, tiny_graph, d, K, w, count):
     g = tiny_graph
     pool, _ = oracle.augment(100 + d + K, g["offsets"], g["adj"], 40, 5, count, shuffle_seed=9)
@@ -275,7 +277,7 @@ def check_single_steps(pool, negs, idx, first_g, T, K, w, seed, vertex, context,
 
 
 @pytest.mark.parametrize("policy", ALL_POLICIES)
-@pytest.mark.parametrize("d,K", [(128, 1), (64, 1), (256, 2), (512, 5)])
+@pytest.mark.parametrize("d,K", [(128, 1), (64, 1), (256, 2), (512, 5), (96, 1), (352, 3)])
 def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, policy, d, K):
     """A sparse pool over many nodes: most samples share no row with any other sample, so whatever
     the interleaving their rows must equal one sequential step from the initial values; rows never
