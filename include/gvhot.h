@@ -170,6 +170,16 @@ int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_ad
  * training draws them: host_out[count][K].                                     */
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out);
 
+/* Evaluation on the device (after waiting for all training).
+ * gv_eval_loss: mean over host_pairs[count][2] of the loss one training step descends,
+ *   -log sigmoid(x_u . c_v) - w sum_k log sigmoid(-x_u . c_k), the K negatives of sample i
+ *   drawn from the alias table with Philox stream 2 of eval_seed, counter (i, k).
+ * gv_cosine: host_out[i] = cosine of vertex rows host_first[i], host_second[i] (0 for a
+ *   zero row): the score of a node pair in link prediction (Sec. 4.5).
+ * Ids >= n give GV_EINVAL.                                                          */
+int gv_eval_loss(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count, uint64_t eval_seed, double *mean_loss);
+int gv_cosine(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count, float *host_out);
+
 /* Wait for all queued device work of the context; folds event timings into the
  * statistics.                                                                   */
 int gv_sync(gv_ctx *ctx);

@@ -23,7 +23,7 @@ EXPORTS = [
     "gv_create", "gv_destroy", "gv_last_error", "gv_set_graph", "gv_set_degrees", "gv_build_alias", "gv_get_alias",
     "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
-    "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment",
+    "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
 ]
 
 
@@ -91,6 +91,8 @@ def load():
     L.gv_sync.argtypes = [vp]
     L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
     L.gv_set_position.argtypes = [vp, C.c_uint64]
+    L.gv_eval_loss.argtypes = [vp, vp, C.c_uint64, C.c_uint64, C.POINTER(C.c_double)]
+    L.gv_cosine.argtypes = [vp, u32p, u32p, C.c_uint64, f32p]
     L.gv_augment.argtypes = [C.c_uint32, C.POINTER(C.c_uint64), u32p, C.c_uint64, C.c_uint32, C.c_uint32,
                              C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, vp, C.POINTER(C.c_uint64)]
     for name in EXPORTS:
@@ -219,6 +221,23 @@ def gv_get_stats(ctx):
 
 def gv_set_position(ctx, next_g):
     _check(ctx, load().gv_set_position(ctx, next_g))
+
+
+def gv_eval_loss(ctx, pairs, eval_seed):
+    pairs = np.ascontiguousarray(pairs, dtype=np.uint32)
+    out = C.c_double()
+    _check(ctx, load().gv_eval_loss(ctx, C.c_void_p(pairs.ctypes.data), pairs.shape[0], eval_seed, C.byref(out)))
+    return out.value
+
+
+def gv_cosine(ctx, first, second):
+    first, pa = _u32(first)
+    second, pb = _u32(second)
+    if first.size != second.size:
+        raise ValueError("first and second differ in length")
+    out = np.empty(first.size, dtype=np.float32)
+    _check(ctx, load().gv_cosine(ctx, pa, pb, first.size, out.ctypes.data_as(C.POINTER(C.c_float))))
+    return out
 
 
 def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, count, shuffle=GV_SHUFFLE_PSEUDO,

@@ -709,6 +709,59 @@ int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *h
     return GV_OK;
 }
 
+int gv_eval_loss(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count, uint64_t eval_seed, double *mean_loss) {
+    int rc = need_trainable(ctx);
+    if (rc) return rc;
+    if (!mean_loss || (count > 0 && !host_pairs)) return fail(ctx, GV_EINVAL, "null argument");
+    if (count == 0 || count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "count must be in 1 .. 2^32-1");
+    rc = sync_all(ctx);
+    if (rc) return rc;
+    uint32_t *dev_pairs = nullptr;
+    double *dev_total = nullptr;
+    GV_HIP(ctx, hipMalloc((void **)&dev_pairs, count * 2 * sizeof(uint32_t)));
+    hipError_t e = hipMalloc((void **)&dev_total, sizeof(double));
+    if (e == hipSuccess) e = hipMemcpy(dev_pairs, host_pairs, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(dev_total, 0, sizeof(double));
+    if (e == hipSuccess) {
+        gv::TrainArgs a = train_args(ctx, dev_pairs, 0, (uint32_t)count);
+        a.seed = eval_seed;
+        e = gv::launch_eval_loss(a, ctx->cfg.dim, ctx->cfg.num_neg, dev_total, ctx->compute);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->compute);
+    double total = 0.0;
+    if (e == hipSuccess) e = hipMemcpy(&total, dev_total, sizeof(double), hipMemcpyDeviceToHost);
+    (void)hipFree(dev_pairs);
+    if (dev_total) (void)hipFree(dev_total);
+    GV_HIP(ctx, e);
+    *mean_loss = total / (double)count;
+    return sync_all(ctx);  // reports ids >= n
+}
+
+int gv_cosine(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count, float *host_out) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (count == 0) return GV_OK;
+    if (!host_first || !host_second || !host_out) return fail(ctx, GV_EINVAL, "null argument");
+    if (count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "at most 2^32-1 pairs per call");
+    rc = sync_all(ctx);
+    if (rc) return rc;
+    uint32_t *dev_ids = nullptr;
+    float *dev_out = nullptr;
+    GV_HIP(ctx, hipMalloc((void **)&dev_ids, count * 2 * sizeof(uint32_t)));
+    hipError_t e = hipMalloc((void **)&dev_out, count * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(dev_ids, host_first, count * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(dev_ids + count, host_second, count * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = gv::launch_cosine(ctx->vertex, ctx->n, ctx->cfg.dim, dev_ids, dev_ids + count, (uint32_t)count, dev_out,
+                              ctx->error_flag, ctx->compute);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->compute);
+    if (e == hipSuccess) e = hipMemcpy(host_out, dev_out, count * sizeof(float), hipMemcpyDeviceToHost);
+    (void)hipFree(dev_ids);
+    if (dev_out) (void)hipFree(dev_out);
+    GV_HIP(ctx, e);
+    return sync_all(ctx);
+}
+
 int gv_sync(gv_ctx *ctx) {
     if (!ctx) return GV_EINVAL;
     int rc = bind_device(ctx);

@@ -41,6 +41,11 @@ hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, 
 // vertex ~ U(-0.5/d, 0.5/d) from Philox stream 1 (context is cleared by the caller).
 hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64_t seed, hipStream_t stream);
 
+// *total += sum of the per-sample losses of a.pairs[0 .. a.count) (a.seed = evaluation seed).
+hipError_t launch_eval_loss(const TrainArgs &a, uint32_t dim, uint32_t num_neg, double *total, hipStream_t stream);
+hipError_t launch_cosine(const float *vertex, uint32_t n, uint32_t dim, const uint32_t *first, const uint32_t *second,
+                         uint32_t count, float *out, uint32_t *error_flag, hipStream_t stream);
+
 bool supported_shape(uint32_t dim, uint32_t num_neg);
 
 }  // namespace gv

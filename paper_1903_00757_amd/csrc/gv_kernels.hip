@@ -46,8 +46,9 @@ __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 // table): bucket = floor(R * n / 2^64) from the first two words, accepted when
 // the third word is below the bucket's threshold, else the bucket's alias.
 __device__ __forceinline__ uint32_t draw_negative(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
-                                                  uint64_t g, uint32_t k) {
-    const uint4 r = philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), k, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+                                                  uint64_t g, uint32_t k, uint32_t stream = 0u) {
+    const uint4 r =
+        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), k, stream, (uint32_t)seed, (uint32_t)(seed >> 32));
     const uint64_t R = ((uint64_t)r.x << 32) | r.y;
     const uint32_t j = (uint32_t)__umul64hi(R, (uint64_t)n);
     const uint2 e = alias[j];
@@ -614,6 +615,90 @@ __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
     sgns_step<kV, kK, kPlain>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim);
 }
 
+// ---------------------------------------------------------------------------
+// Evaluation (no training runs meanwhile, so plain cached loads are fine).
+//
+// Mean of the per-sample loss  -log sigmoid(x_u . c_v) - w sum_k log sigmoid(-x_u . c_k)
+// over an evaluation pool; the negatives of sample i come from Philox stream 2, counter
+// (i, k).  Dot products in fp32, the logarithms and the sum in fp64.
+__device__ __forceinline__ double log_sigmoid(double z) { return z >= 0.0 ? -log1p(exp(-z)) : z - log1p(exp(z)); }
+
+template <int kV, int kK>
+__global__ __launch_bounds__(kBlock) void k_eval_loss(TrainArgs a, double *__restrict__ total) {
+    using Io = RowIo<kV, kPlain>;
+    const uint32_t D = a.dim;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
+    const uint32_t waves = gridDim.x * (kBlock / kWave);
+    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
+    double sum = 0.0;
+    for (uint32_t chunk = wave; chunk < chunks; chunk += waves) {
+        const uint32_t base = chunk * kWave;
+        const uint32_t in_chunk = min((uint32_t)kWave, a.count - base);
+        const bool mine = (uint32_t)lane < in_chunk;
+        const uint2 p = mine ? pairs[base + lane] : make_uint2(0u, 0u);
+        uint32_t neg[kK];
+#pragma unroll
+        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, (uint64_t)base + lane, k, 2u);
+        if (mine && (p.x >= a.n || p.y >= a.n)) *a.error_flag = 1u;
+        for (uint32_t i = 0; i < in_chunk; ++i) {
+            const uint32_t u = lane_value(p.x, i), v = lane_value(p.y, i);
+            if (u >= a.n || v >= a.n) continue;
+            float x[kV], c[kV];
+            Io::load(a.vertex + (size_t)u * D, lane, D, x);
+            double loss = 0.0;
+#pragma unroll
+            for (int k = 0; k <= kK; ++k) {
+                const uint32_t row = k == 0 ? v : lane_value(neg[k > 0 ? k - 1 : 0], i);
+                Io::load(a.context + (size_t)row * D, lane, D, c);
+                float partial = 0.0f;
+#pragma unroll
+                for (int j = 0; j < kV; ++j) partial = fmaf(x[j], c[j], partial);
+                const double score = (double)wave_sum(partial);
+                loss -= k == 0 ? log_sigmoid(score) : (double)a.neg_weight * log_sigmoid(-score);
+            }
+            sum += loss;
+        }
+    }
+    if (lane == 0) atomicAdd(total, sum);
+}
+
+// out[i] = cosine of vertex rows first[i], second[i] (0 when a row is zero), the score of
+// an edge in link prediction (Sec. 4.5).
+template <int kV>
+__global__ __launch_bounds__(kBlock) void k_cosine(const float *__restrict__ vertex, uint32_t n, uint32_t dim,
+                                                   const uint32_t *__restrict__ first,
+                                                   const uint32_t *__restrict__ second, uint32_t count,
+                                                   float *__restrict__ out, uint32_t *error_flag) {
+    using Io = RowIo<kV, kPlain>;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t waves = gridDim.x * (kBlock / kWave);
+    for (uint32_t i = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave); i < count;
+         i += waves) {
+        const uint32_t ra = first[i], rb = second[i];
+        if (ra >= n || rb >= n) {
+            *error_flag = 1u;
+            if (lane == 0) out[i] = 0.0f;
+            continue;
+        }
+        float x[kV], y[kV];
+        Io::load(vertex + (size_t)ra * dim, lane, dim, x);
+        Io::load(vertex + (size_t)rb * dim, lane, dim, y);
+        float xy = 0.0f, xx = 0.0f, yy = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kV; ++j) {
+            xy = fmaf(x[j], y[j], xy);
+            xx = fmaf(x[j], x[j], xx);
+            yy = fmaf(y[j], y[j], yy);
+        }
+        xy = wave_sum(xy);
+        xx = wave_sum(xx);
+        yy = wave_sum(yy);
+        if (lane == 0) out[i] = (xx > 0.0f && yy > 0.0f) ? xy / (sqrtf(xx) * sqrtf(yy)) : 0.0f;
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
                                                            uint64_t first_g, uint64_t count, uint32_t num_neg,
                                                            uint32_t *__restrict__ out) {
@@ -762,6 +847,37 @@ hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg
 #define GV_CALL(V, K) launch_batch_vk<V, K>(a, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
+}
+
+template <int kV, int kK>
+hipError_t launch_eval_vk(const TrainArgs &a, double *total, hipStream_t stream) {
+    if (a.count == 0) return hipSuccess;
+    const uint32_t chunks = (a.count + kWave - 1) / kWave;
+    const uint32_t wanted = (chunks + (kBlock / kWave) - 1) / (kBlock / kWave);
+    hipLaunchKernelGGL((k_eval_loss<kV, kK>), dim3(wanted < 2048u ? wanted : 2048u), dim3(kBlock), 0, stream, a, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_loss(const TrainArgs &a, uint32_t dim, uint32_t num_neg, double *total, hipStream_t stream) {
+#define GV_CALL(V, K) launch_eval_vk<V, K>(a, total, stream)
+    GV_DISPATCH(GV_CALL)
+#undef GV_CALL
+}
+
+hipError_t launch_cosine(const float *vertex, uint32_t n, uint32_t dim, const uint32_t *first, const uint32_t *second,
+                         uint32_t count, float *out, uint32_t *error_flag, hipStream_t stream) {
+    if (count == 0) return hipSuccess;
+    const uint32_t wanted = (count + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const dim3 grid(wanted < 4096u ? wanted : 4096u), block(kBlock);
+    if (dim <= 64)
+        hipLaunchKernelGGL((k_cosine<1>), grid, block, 0, stream, vertex, n, dim, first, second, count, out, error_flag);
+    else if (dim <= 128)
+        hipLaunchKernelGGL((k_cosine<2>), grid, block, 0, stream, vertex, n, dim, first, second, count, out, error_flag);
+    else if (dim <= 256)
+        hipLaunchKernelGGL((k_cosine<4>), grid, block, 0, stream, vertex, n, dim, first, second, count, out, error_flag);
+    else
+        hipLaunchKernelGGL((k_cosine<8>), grid, block, 0, stream, vertex, n, dim, first, second, count, out, error_flag);
+    return hipGetLastError();
 }
 
 hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,

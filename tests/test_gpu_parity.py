@@ -658,3 +658,35 @@ def test_rows_beyond_2_to_32_elements(gv):
         last = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=n - 3)
         if (n - 3) not in set(pool[:, 0].tolist()):
             assert np.array_equal(last, oracle.init_vertex_rows(9, n - 3, 1, d))
+
+
+# --------------------------------------------------------------------------- evaluation on the device
+@pytest.mark.parametrize("d,K,w", [(128, 1, 5.0), (96, 1, 5.0), (512, 5, 1.0), (64, 3, 2.0)])
+def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w):
+    g = tiny_graph
+    n = g["n"]
+    rng = np.random.default_rng(d + K)
+    vertex = (rng.standard_normal((n, d)) * 0.4).astype(np.float32)
+    context = (rng.standard_normal((n, d)) * 0.4).astype(np.float32)  # scores up to |20|: both log branches
+    vertex[17] = 0.0
+    eval_pool, _ = oracle.augment(9, g["offsets"], g["adj"], 40, 5, 70_003, shuffle_seed=2)
+    a = rng.integers(n, size=5000).astype(np.uint32)
+    b = rng.integers(n, size=5000).astype(np.uint32)
+    a[:3], b[:3] = (17, 5, 17), (4, 17, 17)
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, total_samples=1, pool_capacity=1) as ctx:
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+        loss = gv.gv_eval_loss(ctx, eval_pool, 4242)
+        cos = gv.gv_cosine(ctx, a, b)
+        bad = eval_pool.copy()
+        bad[5, 0] = n
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_eval_loss(ctx, bad, 1)
+        assert e.value.code == gv.GV_EINVAL
+    ref = oracle.loss(vertex, context, eval_pool, K=K, w=w, seed=4242, thresh=tiny_alias[0], alias=tiny_alias[1])
+    assert abs(loss - ref) <= 1e-5 * abs(ref), (loss, ref)
+    ref_cos = oracle.cosine(vertex, a, b)
+    assert np.abs(cos - ref_cos).max() <= 1e-5
+    assert cos[0] == 0 and cos[1] == 0 and cos[2] == 0
