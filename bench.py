@@ -23,8 +23,8 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters
-# read for a 1 GiB device copy (profiles/k_train_tiled_c2_d128_k1_mixed.md); only for the profiled setup.
-PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 54.01e9}
+# read for a 1 GiB device copy (profiles/k_train_tiled_*.md); only for the profiled setups.
+PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 51.38e9, ("c3", 1, 3): 483.7e9}
 
 
 def log(*a):
@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "tiny"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "tiny", "c5-marginal"])
     ap.add_argument("--pools", type=int, default=8, help="distinct pre-generated pools cycled through")
     ap.add_argument("--coherence", type=int, default=int(os.environ.get("GV_BENCH_COHERENCE", "3")))
     ap.add_argument("--schedule", type=int, default=int(os.environ.get("GV_BENCH_SCHEDULE", "1")))
@@ -85,13 +85,24 @@ def main():
     total = cfg["total_samples"]
 
     t0 = time.perf_counter()
-    n, src, dst = W.make_graph(args.workload)
-    deg = W.degrees(n, src, dst)
-    offsets, adj = W.csr_from_edges(n, src, dst)
-    log(f"graph {args.workload}: n={n} edges={src.size} ({time.perf_counter() - t0:.1f} s)")
-    t0 = time.perf_counter()
-    pools = [W.walk_pool(offsets, adj, P, W.configs.WALK_LENGTH, W.configs.WINDOW, seed=100 * cfg["number"] + r)
-             for r in range(args.pools)]
+    if cfg["graph"] == "expected_degrees":
+        # too large to walk inside a benchmark run: degrees from the model, endpoints from their marginal
+        n, deg = W.expected_degrees(args.workload)
+        offsets = adj = None
+        edges = cfg["edges"]
+        args.no_streamed = True
+        log(f"degrees {args.workload}: n={n} ({time.perf_counter() - t0:.1f} s)")
+        t0 = time.perf_counter()
+        pools = [W.marginal_pool(deg, P, seed=100 * cfg["number"] + r) for r in range(args.pools)]
+    else:
+        n, src, dst = W.make_graph(args.workload)
+        deg = W.degrees(n, src, dst)
+        offsets, adj = W.csr_from_edges(n, src, dst)
+        edges = src.size
+        log(f"graph {args.workload}: n={n} edges={edges} ({time.perf_counter() - t0:.1f} s)")
+        t0 = time.perf_counter()
+        pools = [W.walk_pool(offsets, adj, P, W.configs.WALK_LENGTH, W.configs.WINDOW, seed=100 * cfg["number"] + r)
+                 for r in range(args.pools)]
     log(f"{args.pools} pools of {P} samples ({time.perf_counter() - t0:.1f} s)")
     dev_pools = [torch.from_numpy(p.view(np.int32)).cuda() for p in pools]
     torch.cuda.synchronize()
@@ -202,9 +213,11 @@ def main():
         "value": value, "unit": "positive samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {cfg['graph']} n={n} edges={src.size}, d={dim}, K={K}, "
+        "config": {"workload": f"{args.workload}: {cfg['graph']} n={n} edges={edges}, d={dim}, K={K}, "
                                f"neg_weight={w}, pool=2^{int(np.log2(P))} samples resident in HBM, "
-                               f"{args.pools} distinct walk pools (L=40, s=5) cycled, Hogwild",
+                               f"{args.pools} distinct pools cycled ("
+                               + ("endpoints from the degree marginal" if adj is None else "walks L=40, s=5")
+                               + "), asynchronous mode",
                    "coherence": ["plain", "agent", "atomic-agent", "mixed"][args.coherence],
                    "schedule": ["pool-order", "tiled"][args.schedule], "samples_per_step": P},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

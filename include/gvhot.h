@@ -74,7 +74,7 @@ typedef struct gv_config {
     uint32_t mode;           /* GV_MODE_*                                                      */
     uint64_t total_samples;  /* T: planned positive samples; lr(g) = lr0 * max(1 - g/T, floor) */
     uint64_t seed;           /* key of the negative-sampling stream                            */
-    uint64_t pool_capacity;  /* largest pool (in samples) that will be pushed; sizes the two
+    uint64_t pool_capacity;  /* largest pool (in samples, <= 2^31) that will be pushed; sizes the two
                                 pinned host slots and the two device buffers (8 B / sample)    */
     int32_t device;          /* HIP device ordinal                                             */
     uint32_t coherence;      /* GV_COHERENCE_*                                                 */
@@ -145,7 +145,7 @@ int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count);
 int gv_train_pool(gv_ctx *ctx);
 /* Train a pool that already lies in device memory (dev_pairs must stay valid
  * and unchanged until gv_sync).  Ids are checked as for pushed pools.
- * count < 2^32.                                                                */
+ * count <= 2^31.                                                               */
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
 
 /* Host producer of a pool (Sec. 3.1, Alg. 2, parallel online augmentation): walk number

@@ -382,8 +382,8 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
         return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (a multiple of 32 in 32..512), num_neg %u (1..5)", cfg->dim,
                     cfg->num_neg);
     if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
-    if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 32))
-        return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^32 samples");
+    if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 31))
+        return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^31 samples");
     if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
         cfg->schedule > GV_SCHEDULE_TILED)
         return fail(nullptr, GV_EINVAL, "bad mode / coherence / schedule field");
@@ -687,7 +687,7 @@ int gv_train_pool(gv_ctx *ctx) {
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     int rc = need_trainable(ctx);
     if (rc) return rc;
-    if (count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "at most 2^32-1 samples per call");
+    if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
     if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
     return train_any(ctx, dev_pairs, nullptr, count);
 }

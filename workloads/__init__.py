@@ -16,4 +16,4 @@ from .graphs import (  # noqa: F401
     uniform_negative_pairs,
 )
 from .pools import walk_pool, marginal_pool  # noqa: F401
-from .configs import CONFIGS, make_graph  # noqa: F401
+from .configs import CONFIGS, expected_degrees, make_graph  # noqa: F401

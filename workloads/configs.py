@@ -25,6 +25,9 @@ CONFIGS = {
     "c5": dict(number=5, graph="chung_lu", n=66_000_000, edges=1_800_000_000, gamma=2.2, dim=128, num_neg=1,
                neg_weight=5.0, total_samples=10_000_000_000, pool=1 << 24),
 }
+# configuration 5 without its adjacency: Chung-Lu expected degrees for 6.6*10^7 nodes / 1.8*10^9 edges and pools
+# whose endpoints are drawn independently from the degree-proportional marginal (same row-access distribution)
+CONFIGS["c5-marginal"] = dict(CONFIGS["c5"], graph="expected_degrees")
 WALK_LENGTH = 40
 WINDOW = 5
 LR0 = 0.025
@@ -53,3 +56,13 @@ def make_graph(name: str, cache: bool = True):
         np.savez(tmp, src=src, dst=dst)
         os.replace(tmp, path)
     return int(cfg["n"]), src, dst
+
+
+def expected_degrees(name: str):
+    """Degrees of a Chung-Lu configuration without generating its edges: round(2 m w_i / sum w), permuted."""
+    cfg = CONFIGS[name]
+    n, m, gamma = cfg["n"], cfg["edges"], cfg["gamma"]
+    rng = np.random.Generator(np.random.PCG64(cfg["number"]))
+    w = np.arange(1, n + 1, dtype=np.float64) ** (-1.0 / (gamma - 1.0))
+    deg = np.minimum(np.rint(2.0 * m * w / w.sum()), n - 1).astype(np.uint32)
+    return n, deg[rng.permutation(n)]
