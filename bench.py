@@ -93,7 +93,10 @@ def main():
         args.no_streamed = True
         log(f"degrees {args.workload}: n={n} ({time.perf_counter() - t0:.1f} s)")
         t0 = time.perf_counter()
-        pools = [W.marginal_pool(deg, P, seed=100 * cfg["number"] + r) for r in range(args.pools)]
+        pools = []
+        for r in range(args.pools):  # one progress line per pool: these take a while at 6.6*10^7 nodes
+            pools.append(W.marginal_pool(deg, P, seed=100 * cfg["number"] + r))
+            log(f"pool {r + 1}/{args.pools} ({time.perf_counter() - t0:.1f} s)")
     else:
         n, src, dst = W.make_graph(args.workload)
         deg = W.degrees(n, src, dst)

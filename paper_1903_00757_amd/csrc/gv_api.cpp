@@ -255,7 +255,7 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u)
+    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x40000000u)
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
     else
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));

@@ -156,6 +156,45 @@ struct RowIo {
         }
     }
 
+    // row += delta with returning atomic adds, x = the row right after this wave's addition
+    // (whatever other waves added before it is included), delta = 0.  Same lane exchange as
+    // add(), and the inverse exchange for the values that come back.
+    static __device__ __forceinline__ void exchange(float *row, int lane, uint32_t dim, float (&delta)[kV],
+                                                    float (&x)[kV]) {
+        static_assert(W <= 2, "atomic adds are used with the device-scope layouts only");
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if constexpr (W == 2) {
+                const int lo = (lane >> 1) * 4, hi = (32 + (lane >> 1)) * 4;
+                const int e0 = __float_as_int(delta[s * 2]), e1 = __float_as_int(delta[s * 2 + 1]);
+                const int lo0 = __builtin_amdgcn_ds_bpermute(lo, e0), lo1 = __builtin_amdgcn_ds_bpermute(lo, e1);
+                const int hi0 = __builtin_amdgcn_ds_bpermute(hi, e0), hi1 = __builtin_amdgcn_ds_bpermute(hi, e1);
+                float first = __int_as_float((lane & 1) ? lo1 : lo0);    // element lane of the segment
+                float second = __int_as_float((lane & 1) ? hi1 : hi0);   // element 64 + lane
+                float *p = row + s * (kWave * 2) + lane;
+                if ((uint32_t)(s * (kWave * 2) + lane) < dim)
+                    first += __hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
+                    second += __hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // lane l wants elements 2l and 2l + 1: lanes 2l, 2l + 1 hold them in `first` when
+                // l < 32, lanes 2l - 64, 2l - 63 in `second` otherwise
+                const int even = ((2 * lane) & 63) * 4, odd = ((2 * lane + 1) & 63) * 4;
+                const int f_even = __builtin_amdgcn_ds_bpermute(even, __float_as_int(first));
+                const int f_odd = __builtin_amdgcn_ds_bpermute(odd, __float_as_int(first));
+                const int s_even = __builtin_amdgcn_ds_bpermute(even, __float_as_int(second));
+                const int s_odd = __builtin_amdgcn_ds_bpermute(odd, __float_as_int(second));
+                x[s * 2] = __int_as_float(lane < 32 ? f_even : s_even);
+                x[s * 2 + 1] = __int_as_float(lane < 32 ? f_odd : s_odd);
+                delta[s * 2] = delta[s * 2 + 1] = 0.0f;
+            } else {
+                if ((uint32_t)(s * kWave + lane) < dim)
+                    x[s] = delta[s] + __hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                delta[s] = 0.0f;
+            }
+        }
+    }
+
     static __device__ __forceinline__ void store(float *row, int lane, uint32_t dim, const float (&x)[kV]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
@@ -378,6 +417,13 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint32_t tile_base = tile * kTile;
+        // Every tile sorts by its own scrambled view of (side, row id): equal rows still end up
+        // adjacent, but the order in which a tile reaches the rows differs from tile to tile.
+        // With one common order all workgroups, started together, would reach the same rows at
+        // the same moment, and a row would receive its updates of thousands of tiles in one
+        // burst, all computed from the same stale value.
+        const uint32_t id_bits = a.n > 1u ? 32u - (uint32_t)__builtin_clz(a.n - 1u) : 0u;  // <= 30 (checked at launch)
+        const uint32_t scramble = (id_bits ? (tile * 0x9E3779B1u) >> (32u - id_bits) : 0u) | (tile & 1u) << 31;
         for (uint32_t t = threadIdx.x; t < (uint32_t)kTile; t += kBlock) {
             uint32_t key = kSkip, slot = t;
             if (tile_base + t < a.count) {
@@ -386,7 +432,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                     // heat byte: bits 0..6 a logarithmic degree class, bit 7 the warm flag
                     const uint32_t hu = a.heat[p.x], hv = a.heat[p.y];
                     const bool context_side = (hu & 127u) < (hv & 127u);
-                    key = context_side ? (0x80000000u | p.y) : p.x;
+                    key = (context_side ? (0x80000000u | p.y) : p.x) ^ scramble;
                     slot |= (hu >> 7) << 30 | (hv >> 7) << 31;  // warm flags of u and v ride along
                 } else {
                     *a.error_flag = 1u;  // the sample is skipped and reported at the next synchronisation
@@ -447,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                 for (int k = 0; k < kK; ++k) s.nk[k] = lane_value(neg[k], i);
                 s.warm = lane_value(warm, i);
                 s.lr = __uint_as_float(lane_value(__float_as_uint(lr), i));
-                s.context_side = (lane_value(tag, i) >> 31) != 0;
+                s.context_side = ((lane_value(tag, i) ^ scramble) >> 31) != 0;
                 s.stationary = s.context_side ? a.context + (size_t)s.v * D : a.vertex + (size_t)s.u * D;
                 return s;
             };
@@ -572,6 +618,12 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             for (uint32_t i0 = 0; i0 < in_chunk; i0 += kBatch) {
                 TileSample<kK> batch[kBatch];
                 float other[kBatch][kK + 1][kV], fresh[kBatch][kV];
+                // A run that goes on past four samples first trades with memory: its change so far is
+                // added and the register copy takes in what other waves added meanwhile, so a held
+                // row is never more than four samples behind the other holders of that row.
+                if (held && (i0 & 3u) == 0 && held == decode(i0).stationary &&
+                    (kCoherence == kAtomicAgent || (kCoherence == kMixed && held_warm)))
+                    Io::exchange(held, lane, D, moved, y);
                 const float *then = held;
 #pragma unroll
                 for (int b = 0; b < kBatch; ++b) {
@@ -788,8 +840,8 @@ hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blo
 template <int kV, int kK>
 hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
-    if (a.heat == nullptr || a.n > 0x80000000u) return hipErrorInvalidValue;
-    static const uint32_t tile = env_u32("GV_TILE", 1024u);  // tuning sweeps: 512, 1024 or 2048
+    if (a.heat == nullptr || a.n > 0x40000000u) return hipErrorInvalidValue;  // row ids leave key bit 30 free
+    static const uint32_t tile = env_u32("GV_TILE", 2048u);  // tuning sweeps: 512, 1024 or 2048
     uint32_t blocks = hogwild_blocks(a.count, a.n);
     const uint32_t tiles = (a.count + tile - 1) / tile;
     if (blocks > tiles) blocks = tiles;

@@ -1,0 +1,68 @@
+"""Writes tests/golden/long_run_c2.txt: the sequential CPU oracle's trajectory over a long
+training run on the configuration-2 graph (Sec. 4.2 hyper-parameters: d = 128, one negative
+of weight 5, walks of length 40 augmented with window 5, learning rate decaying linearly to
+zero), against which the GPU test compares the library's asynchronous training.
+
+Everything here is computed by ``oracle/`` from seeded synthetic inputs; the library under test
+is not involved.  Takes about 20 minutes on one core:
+
+    python tests/golden/make_long_run_reference.py
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+
+import oracle  # noqa: E402
+import workloads as W  # noqa: E402
+
+# the test reads these from the file, so the two cannot drift apart
+SETUP = dict(graph="c2", holdout=0.01, holdout_seed=51, pool=1 << 24, pools=32, dim=128, num_neg=1,
+             neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=500, eval_walk_seed=777,
+             eval_count=1 << 18, eval_seed=99, negative_pair_seed=52, walk_length=40, window=5)
+CHECKPOINTS = (1, 2, 4, 8, 16, 24, 32)
+
+
+def pool_of(offsets, adj, seed, first_walk, count, s):
+    pairs, _ = oracle.augment(seed, offsets, adj, s["walk_length"], s["window"], count, first_walk=first_walk)
+    return oracle.pseudo_shuffle(pairs, s["window"])
+
+
+def main():
+    s = SETUP
+    n, src, dst = W.make_graph(s["graph"])
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    P, pools = s["pool"], s["pools"]
+    per_walk = sum(min(s["window"], s["walk_length"] - i) for i in range(s["walk_length"]))
+    walks_per_pool = -(-P // per_walk)
+    eval_pool = pool_of(offsets, adj, s["eval_walk_seed"], 0, s["eval_count"], s)
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    vertex, context = oracle.init_embeddings(s["init_seed"], n, s["dim"])
+    lines = ["# written by tests/golden/make_long_run_reference.py (CPU oracle only)"]
+    lines += [f"# {k} = {v}" for k, v in s.items()]
+    lines.append("# pools_trained eval_loss link_prediction_auc max_vertex_norm max_context_norm")
+    for k in range(pools):
+        t0 = time.time()
+        pool = pool_of(offsets, adj, s["walk_seed"], k * walks_per_pool, P, s)
+        oracle.train(vertex, context, pool, K=s["num_neg"], first_g=k * P, T=P * pools, lr0=s["lr0"],
+                     lr_min_ratio=0.0, w=s["neg_weight"], seed=s["train_seed"], thresh=thresh, alias=alias)
+        if k + 1 in CHECKPOINTS:
+            loss = oracle.loss(vertex, context, eval_pool, K=s["num_neg"], w=s["neg_weight"], seed=s["eval_seed"],
+                               thresh=thresh, alias=alias)
+            auc = oracle.link_prediction_auc(vertex, te_s, te_d, na, nb)
+            lines.append(f"{k + 1} {loss:.6f} {auc:.6f} {np.linalg.norm(vertex, axis=1).max():.3f} "
+                         f"{np.linalg.norm(context, axis=1).max():.3f}")
+            print(lines[-1], f"({time.time() - t0:.0f} s for this pool)", flush=True)
+    with open(os.path.join(HERE, "long_run_c2.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
+if __name__ == "__main__":
+    main()

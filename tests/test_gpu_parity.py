@@ -1,5 +1,6 @@
 """Parity of the HIP path against the CPU oracle, through the C boundary (needs a GPU)."""
 import contextlib
+import os
 
 import numpy as np
 import pytest
@@ -298,6 +299,45 @@ def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, policy, d, K):
     assert np.array_equal(got_v[cu == 0], vertex[cu == 0])
     assert np.array_equal(got_c[cc == 0], context[cc == 0])
     assert not np.array_equal(got_v[cu > 0], vertex[cu > 0])
+
+
+@pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, ATOMIC), (TILED, MIXED)])
+def test_tiled_run_on_one_hub_row_is_sequential(gv, policy):
+    """60 samples that all name one high-degree node u: the tiled schedule keeps vertex[u] in registers
+    through the whole run and trades it with memory between batches.  Every context row involved is a
+    multiple of its own unit vector, so the score of a sample does not depend on the other samples:
+    vertex[u] must then equal the oracle's whatever the order within the run, and every context row
+    must have moved by its coefficient times a value vertex[u] passed through."""
+    n, d, K, count, w, seed, hub = 200_000, 128, 1, 60, 5.0, 77, 4242
+    rng = np.random.default_rng(5)
+    deg = rng.integers(1, 50, size=n).astype(np.uint32)
+    deg[hub] = 10_000
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias)
+    partners = np.setdiff1d(np.arange(1000, 2000, dtype=np.uint32), negs.reshape(-1))[:count]
+    rows = np.concatenate([partners, negs.reshape(-1)])
+    assert np.unique(rows).size == 2 * count and hub not in rows
+    pool = np.stack([np.full(count, hub, dtype=np.uint32), partners], axis=1)
+    vertex, context = random_embeddings(n, d, seed=9)
+    vertex[hub] = rng.uniform(-1.0, 1.0, size=d).astype(np.float32)
+    for j, r in enumerate(rows):
+        context[r] = 0.0
+        context[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
+    T = 10 * count
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, T, seed, policy)
+    ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, T, seed)
+    assert np.abs(got_v[hub] - ref_v[hub]).max() <= 1e-5 * np.abs(ref_v[hub]).max()
+    assert not np.allclose(ref_v[hub], vertex[hub], rtol=1e-3)
+    lo, hi = np.minimum(vertex[hub], ref_v[hub]), np.maximum(vertex[hub], ref_v[hub])
+    for j, r in enumerate(rows):
+        moved = got_c[r].astype(np.float64) - context[r]
+        coef = (ref_v[hub, j].astype(np.float64) - vertex[hub, j]) / context[r, j]  # x_j moved by coef * c_j
+        seen = moved / coef  # the vertex[u] this sample multiplied its coefficient with
+        tol = 1e-3 * np.abs(vertex[hub]).max()  # fp32 rounding of the row over the smallest coefficient
+        assert np.all(seen >= lo - tol) and np.all(seen <= hi + tol), (j, r)
+    untouched = np.ones(n, dtype=bool)
+    untouched[rows] = False
+    assert np.array_equal(got_c[untouched], context[untouched])
 
 
 def evaluation_loss(deg, vertex, context, eval_pool, K, w):
@@ -690,3 +730,69 @@ def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w
     ref_cos = oracle.cosine(vertex, a, b)
     assert np.abs(cos - ref_cos).max() <= 1e-5
     assert cos[0] == 0 and cos[1] == 0 and cos[2] == 0
+
+
+def read_long_run_reference():
+    """tests/golden/long_run_c2.txt: the set-up and the oracle's checkpoints (written by the script beside it)."""
+    setup, rows = {}, []
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "long_run_c2.txt")) as f:
+        for line in f:
+            if line.startswith("#"):
+                if " = " in line:
+                    key, value = line[1:].strip().split(" = ")
+                    setup[key] = value if key == "graph" else float(value) if "." in value else int(value)
+                continue
+            k, loss, auc, nv, nc = line.split()
+            rows.append((int(k), float(loss), float(auc), float(nv), float(nc)))
+    return setup, rows
+
+
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (POOL_ORDER, ATOMIC)])
+def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, policy):
+    """32 pools of 2^24 samples (5.4*10^8 samples, learning rate decaying to zero) on the configuration-2
+    graph with 1 % of its edges held out, pools produced on the fly by the library's host producer
+    into the pinned slots.  At every checkpoint of the stored oracle trajectory the evaluation loss must
+    be within 2 % of the oracle's and no row may have grown beyond twice the oracle's longest row
+    (asynchronous updates that overshoot show up as a few very long rows well before the loss moves);
+    at the end the link-prediction AUC must match too.  This graph has no structure beyond its degrees,
+    so its AUC measures nothing but how far training has got and drops steeply over the run: it is held
+    to 0.01, the planted-partition test above holds the AUC of a graph that has structure to 0.005."""
+    s, reference = read_long_run_reference()
+    n, src, dst = W.make_graph(s["graph"])
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    P, pools, d = s["pool"], s["pools"], s["dim"]
+    walks_per_pool = -(-P // 190)
+    eval_pool, _ = gv.gv_augment(offsets, adj, seed=s["eval_walk_seed"], count=s["eval_count"], threads=16)
+    eval_pool = eval_pool.copy()
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
+    schedule, coherence = policy
+    checkpoints = {k: rest for k, *rest in reference}
+    assert pools in checkpoints
+    with context_for(gv, dim=d, num_neg=s["num_neg"], neg_weight=s["neg_weight"], mode=gv.GV_MODE_HOGWILD,
+                     total_samples=P * pools, seed=s["train_seed"], pool_capacity=P, lr0=s["lr0"],
+                     coherence=coherence, schedule=schedule) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, s["init_seed"])
+        for k in range(pools):
+            slot = gv.gv_acquire_pool_slot(ctx, P)
+            gv.gv_augment(offsets, adj, seed=s["walk_seed"], first_walk=k * walks_per_pool, count=P, threads=16,
+                          out=slot)
+            gv.gv_push_pool(ctx, slot, P)
+            gv.gv_train_pool(ctx)
+            if k + 1 in checkpoints:
+                ref_loss, ref_auc, ref_nv, ref_nc = checkpoints[k + 1]
+                gv.gv_sync(ctx)
+                loss = gv.gv_eval_loss(ctx, eval_pool, s["eval_seed"])
+                nv = np.linalg.norm(gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d), axis=1).max()
+                nc = np.linalg.norm(gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d), axis=1).max()
+                print(f"long run {policy} after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
+                      f"longest rows {nv:.2f}/{nc:.2f} vs {ref_nv:.2f}/{ref_nc:.2f}")
+                assert abs(loss - ref_loss) <= 0.02 * ref_loss
+                assert nv <= 2.0 * ref_nv and nc <= 2.0 * ref_nc
+        auc = oracle.auc(gv.gv_cosine(ctx, te_s, te_d), gv.gv_cosine(ctx, na, nb))
+        print(f"long run {policy}: auc {auc:.4f} vs {checkpoints[pools][1]:.4f}")
+        assert gv.gv_get_stats(ctx)["samples_trained"] == P * pools
+        assert abs(auc - checkpoints[pools][1]) <= 0.01
