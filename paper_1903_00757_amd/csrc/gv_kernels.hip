@@ -351,20 +351,20 @@ __device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, 
 
 // ---------------------------------------------------------------------------
 // Tiled stationary-row training.  A workgroup takes a tile of kTile consecutive samples
-// of the pool, tags every sample with its hotter row (the higher-degree one of u, v:
-// vertex[u] = side 0, context[v] = side 1; decided by a one-byte degree class per node)
-// and sorts the tile by that row in LDS, so
-// that samples sharing their hot row become adjacent.  Each of its four waves then walks
-// a quarter of the sorted tile and keeps the hot row in registers for as long as
-// consecutive samples name it: the row is read once per run, the run's updates are
-// applied to the register copy in order, and the run's total change is added to memory
-// once with fp32 atomic adds (nothing another wave adds meanwhile is lost).  The other
-// rows of a sample are fetched and updated per sample with the given policy.
+// of the pool, tags every sample with the hottest of its rows (vertex[u], context[v] or the
+// context row of a negative; decided by a one-byte degree class per node, ties going to the
+// earlier of the three) and sorts the tile by that row in LDS, so that samples sharing their
+// hot row become adjacent.  Each of its four waves then walks a quarter of the sorted tile
+// and keeps the hot row in registers for as long as consecutive samples name it: the row is
+// read once per run, the run's updates are applied to the register copy in order, and the
+// run's change is added to memory with fp32 atomic adds (nothing another wave adds meanwhile
+// is lost).  The other rows of a sample are fetched and updated per sample with the given
+// policy.  Accesses to one row are served one after the other by the memory system, so a
+// row that a percent of all samples name -- as an endpoint or, drawn in proportion to
+// degree^0.75, as a negative -- would otherwise set the pace of the whole launch.
 // Tiles are dealt round-robin to workgroups, so the launch still moves through the pool
-// front to back and a row's samples stay spread over time; only the memory traffic of
-// the few rows that a large share of all samples name shrinks (16 samples of one tile
-// sharing a row cost 2 row transfers instead of 32).  Every sample keeps the negatives
-// and the learning rate of its position in the pool.
+// front to back and a row's samples stay spread over time.  Every sample keeps the
+// negatives and the learning rate of its position in the pool.
 template <int kTile>
 __device__ __forceinline__ void sort_tile(uint32_t *key, uint32_t *pos) {
     for (uint32_t k = 2; k <= (uint32_t)kTile; k <<= 1) {
@@ -387,15 +387,15 @@ __device__ __forceinline__ void sort_tile(uint32_t *key, uint32_t *pos) {
     }
 }
 
-// Wave-uniform description of one sample of a sorted tile.
+// Wave-uniform description of one sample of a sorted tile.  Its rows are numbered
+// 0 = vertex[u], 1 = context[v], 2 + k = context[negative k].
 template <int kK>
 struct TileSample {
-    uint32_t u, v;
-    uint32_t nk[kK];     // negatives
-    uint32_t warm;       // bit 0: u, bit 1: v, bit 2+k: negative k
+    uint32_t id[kK + 2];  // u, v, negatives
+    uint32_t warm;        // bit j: row j is warm
+    uint32_t held;        // number of the stationary row
     float lr;
-    bool context_side;   // stationary row is context[v] (else vertex[u])
-    float *stationary;   // address of the stationary row
+    float *stationary;    // address of the stationary row
 };
 
 template <int kV, int kK, int kCoherence, int kTile>
@@ -404,12 +404,12 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
-    static_assert(kTile <= 65536, "the slot number of a sample shares its word with two flags");
+    static_assert(kTile <= 65536, "the slot number of a sample shares its word with the row number and two flags");
     // samples whose gathers are in flight together: bounded by the registers their rows take
     constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
     using Io = RowIo<kV, kCoherence>;
     __shared__ uint32_t s_key[kTile];
-    __shared__ uint32_t s_pos[kTile];
+    __shared__ uint32_t s_pos[kTile];  // bits 0..15 slot in the tile, 16..18 stationary row number, 30/31 warm u/v
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint32_t tile_base = tile * kTile;
-        // Every tile sorts by its own scrambled view of (side, row id): equal rows still end up
+        // Every tile sorts by its own scrambled view of (matrix, row id): equal rows still end up
         // adjacent, but the order in which a tile reaches the rows differs from tile to tile.
         // With one common order all workgroups, started together, would reach the same rows at
         // the same moment, and a row would receive its updates of thousands of tiles in one
@@ -431,9 +431,24 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                 if (p.x < a.n && p.y < a.n) {
                     // heat byte: bits 0..6 a logarithmic degree class, bit 7 the warm flag
                     const uint32_t hu = a.heat[p.x], hv = a.heat[p.y];
-                    const bool context_side = (hu & 127u) < (hv & 127u);
-                    key = (context_side ? (0x80000000u | p.y) : p.x) ^ scramble;
-                    slot |= (hu >> 7) << 30 | (hv >> 7) << 31;  // warm flags of u and v ride along
+                    uint32_t best = hu & 127u, held = 0u, row = p.x;
+                    if ((hv & 127u) > best) {
+                        best = hv & 127u;
+                        held = 1u;
+                        row = p.y;
+                    }
+#pragma unroll
+                    for (int k = 0; k < kK; ++k) {
+                        const uint32_t nk = draw_negative(a.alias, a.n, a.seed, a.first_g + tile_base + t, k);
+                        const uint32_t hn = a.heat[nk] & 127u;
+                        if (hn > best) {
+                            best = hn;
+                            held = 2u + k;
+                            row = nk;
+                        }
+                    }
+                    key = (held == 0u ? row : (0x80000000u | row)) ^ scramble;
+                    slot |= held << 16 | (hu >> 7) << 30 | (hv >> 7) << 31;
                 } else {
                     *a.error_flag = 1u;  // the sample is skipped and reported at the next synchronisation
                 }
@@ -485,30 +500,38 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             const uint64_t live = __ballot(mine);
             const uint32_t in_chunk = live == ~0ull ? (uint32_t)kWave : (uint32_t)__builtin_ctzll(~live);
 
+            auto row_address = [&](const TileSample<kK> &s, int j) {
+                return j == 0 ? a.vertex + (size_t)s.id[0] * D : a.context + (size_t)s.id[j] * D;
+            };
             auto decode = [&](uint32_t i) {
                 TileSample<kK> s;
-                s.u = lane_value(p.x, i);
-                s.v = lane_value(p.y, i);
+                s.id[0] = lane_value(p.x, i);
+                s.id[1] = lane_value(p.y, i);
 #pragma unroll
-                for (int k = 0; k < kK; ++k) s.nk[k] = lane_value(neg[k], i);
+                for (int k = 0; k < kK; ++k) s.id[2 + k] = lane_value(neg[k], i);
                 s.warm = lane_value(warm, i);
                 s.lr = __uint_as_float(lane_value(__float_as_uint(lr), i));
-                s.context_side = ((lane_value(tag, i) ^ scramble) >> 31) != 0;
-                s.stationary = s.context_side ? a.context + (size_t)s.v * D : a.vertex + (size_t)s.u * D;
+                s.held = (lane_value(slot, i) >> 16) & 7u;
+                s.stationary = row_address(s, 0);
+#pragma unroll
+                for (int j = 1; j <= kK + 1; ++j)
+                    if (s.held == (uint32_t)j) s.stationary = row_address(s, j);
                 return s;
             };
-            // Issue the loads of a sample: its K+1 other rows, and its stationary row when that
-            // is not the row the wave will be holding at that point.  other[0] is context[v]
-            // (vertex side) or vertex[u] (context side); other[1+k] is the context row of negative k.
+            // Issue the loads of a sample: its K+1 rows other than the stationary one, in row order
+            // (other[i] is row i if i comes before the stationary row, else row i + 1), and the
+            // stationary row when that is not the row the wave will be holding at that point.
             auto fetch = [&](const TileSample<kK> &s, const float *held_then, float (&other)[kK + 1][kV],
                              float (&fresh)[kV]) {
-                Io::load(s.context_side ? a.vertex + (size_t)s.u * D : a.context + (size_t)s.v * D, lane, D, other[0]);
 #pragma unroll
-                for (int k = 0; k < kK; ++k) Io::load(a.context + (size_t)s.nk[k] * D, lane, D, other[1 + k]);
+                for (int i = 0; i <= kK; ++i)
+                    Io::load((uint32_t)i < s.held ? row_address(s, i) : row_address(s, i + 1), lane, D, other[i]);
                 if (s.stationary != held_then) Io::load(s.stationary, lane, D, fresh);
             };
 
-            // One sample: switch the held row if needed, then the scores, coefficients and updates.
+            // One sample (same arithmetic as sgns_step): switch the held row if needed, then all
+            // scores and coefficients from the rows as they are before the sample, then the updates:
+            // into the register copy for the held row, to memory for the others.
             auto train_one = [&](const TileSample<kK> &cur, float (&other)[kK + 1][kV], const float (&fresh)[kV]) {
                 if (cur.stationary != held) {
                     flush();
@@ -518,96 +541,79 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                         moved[j] = 0.0f;
                     }
                     held = cur.stationary;
-                    held_warm = ((cur.warm >> (cur.context_side ? 1 : 0)) & 1u) != 0;
+                    held_warm = ((cur.warm >> cur.held) & 1u) != 0;
                 }
                 const float lrw = cur.lr * a.neg_weight;
+                const bool vertex_held = cur.held == 0u;
+                uint32_t held_id = cur.id[1];  // id of the held context row (unused when vertex[u] is held)
+#pragma unroll
+                for (int j = 2; j <= kK + 1; ++j)
+                    if (cur.held == (uint32_t)j) held_id = cur.id[j];
 
-                if (!cur.context_side) {
-                    // y is vertex[u]; other[] holds context[v] and the negatives' context rows
-                    uint32_t rows[kK + 1];
-                    rows[0] = cur.v;
+                // x = vertex[u]; c[j - 1] = context row j, taken from the register copy when it is the
+                // held row (a row can be named twice in a sample: positive and negative, or two negatives)
+                float x[kV], c[kK + 1][kV];
+                bool is_held[kK + 1];
 #pragma unroll
-                    for (int k = 0; k < kK; ++k) rows[k + 1] = cur.nk[k];
-                    float coef[kK + 1];
+                for (int e = 0; e < kV; ++e) x[e] = vertex_held ? y[e] : other[0][e];
 #pragma unroll
-                    for (int k = 0; k <= kK; ++k) {
-                        float partial = 0.0f;
+                for (int j = 1; j <= kK + 1; ++j) {
+                    is_held[j - 1] = !vertex_held && cur.id[j] == held_id;
+                    const bool before = (uint32_t)j < cur.held;  // its place in other[]: j before the held row, else j - 1
+                    const int at = j <= kK ? j : kK;             // (the last row is never before the held one)
 #pragma unroll
-                        for (int j = 0; j < kV; ++j) partial = fmaf(y[j], other[k][j], partial);
-                        const float score = wave_sum(partial);
-                        coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                    for (int e = 0; e < kV; ++e) {
+                        const float value = before ? other[at][e] : other[j - 1][e];
+                        c[j - 1][e] = is_held[j - 1] ? y[e] : value;
                     }
+                }
+                float coef[kK + 1];
 #pragma unroll
-                    for (int k = 0; k <= kK; ++k) {
-                        bool repeated = false;
+                for (int k = 0; k <= kK; ++k) {
+                    float partial = 0.0f;
 #pragma unroll
-                        for (int k2 = 0; k2 < k; ++k2) repeated |= rows[k2] == rows[k];
-                        if (repeated) continue;
-                        float total = coef[k];
+                    for (int e = 0; e < kV; ++e) partial = fmaf(x[e], c[k][e], partial);
+                    const float score = wave_sum(partial);
+                    coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                }
+                // context rows first (they take the vertex row as it was), each distinct row once
 #pragma unroll
-                        for (int k2 = k + 1; k2 <= kK; ++k2) total += rows[k2] == rows[k] ? coef[k2] : 0.0f;
-                        remote_update<kV, kCoherence>(a.context + (size_t)rows[k] * D, lane, D, (cur.warm >> (k + 1)) & 1u,
-                                                      total, y, other[k]);
+                for (int k = 0; k <= kK; ++k) {
+                    bool repeated = false;
+#pragma unroll
+                    for (int k2 = 0; k2 < k; ++k2) repeated |= cur.id[1 + k2] == cur.id[1 + k];
+                    if (repeated) continue;
+                    float total = coef[k];
+#pragma unroll
+                    for (int k2 = k + 1; k2 <= kK; ++k2) total += cur.id[1 + k2] == cur.id[1 + k] ? coef[k2] : 0.0f;
+                    if (is_held[k]) {
+#pragma unroll
+                        for (int e = 0; e < kV; ++e) {
+                            const float d = total * x[e];
+                            y[e] += d;
+                            moved[e] += d;
+                        }
+                    } else {
+                        remote_update<kV, kCoherence>(a.context + (size_t)cur.id[1 + k] * D, lane, D,
+                                                      (cur.warm >> (k + 1)) & 1u, total, x, c[k]);
                     }
+                }
+                float dx[kV];
 #pragma unroll
-                    for (int j = 0; j < kV; ++j) {
-                        float acc = 0.0f;
+                for (int e = 0; e < kV; ++e) {
+                    float acc = 0.0f;
 #pragma unroll
-                        for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], other[k][j], acc);
-                        y[j] += acc;
-                        moved[j] += acc;
+                    for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], c[k][e], acc);
+                    dx[e] = acc;
+                }
+                if (vertex_held) {
+#pragma unroll
+                    for (int e = 0; e < kV; ++e) {
+                        y[e] += dx[e];
+                        moved[e] += dx[e];
                     }
                 } else {
-                    // y is context[v]; other[0] is vertex[u], other[1+k] the negatives' context rows
-                    // (a negative equal to v is the held row itself: its register copy is the fresh one)
-#pragma unroll
-                    for (int k = 0; k < kK; ++k) {
-                        if (cur.nk[k] == cur.v) {
-#pragma unroll
-                            for (int j = 0; j < kV; ++j) other[1 + k][j] = y[j];
-                        }
-                    }
-                    float coef[kK + 1];
-#pragma unroll
-                    for (int k = 0; k <= kK; ++k) {
-                        float partial = 0.0f;
-#pragma unroll
-                        for (int j = 0; j < kV; ++j) partial = fmaf(other[0][j], k == 0 ? y[j] : other[k][j], partial);
-                        const float score = wave_sum(partial);
-                        coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
-                    }
-                    float dx[kV];
-#pragma unroll
-                    for (int j = 0; j < kV; ++j) {
-                        float acc = coef[0] * y[j];
-#pragma unroll
-                        for (int k = 1; k <= kK; ++k) acc = fmaf(coef[k], other[k][j], acc);
-                        dx[j] = acc;
-                    }
-                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.u * D, lane, D, cur.warm & 1u, 1.0f, dx, other[0]);
-                    float stay = coef[0];  // coefficient on the held row, negatives equal to v included
-#pragma unroll
-                    for (int k = 0; k < kK; ++k) {
-                        if (cur.nk[k] == cur.v) {
-                            stay += coef[k + 1];
-                            continue;
-                        }
-                        bool repeated = false;
-#pragma unroll
-                        for (int k2 = 0; k2 < k; ++k2) repeated |= cur.nk[k2] == cur.nk[k];
-                        if (repeated) continue;
-                        float total = coef[k + 1];
-#pragma unroll
-                        for (int k2 = k + 1; k2 < kK; ++k2) total += cur.nk[k2] == cur.nk[k] ? coef[k2 + 1] : 0.0f;
-                        remote_update<kV, kCoherence>(a.context + (size_t)cur.nk[k] * D, lane, D, (cur.warm >> (k + 2)) & 1u,
-                                                      total, other[0], other[1 + k]);
-                    }
-#pragma unroll
-                    for (int j = 0; j < kV; ++j) {
-                        const float d = stay * other[0][j];
-                        y[j] += d;
-                        moved[j] += d;
-                    }
+                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.id[0] * D, lane, D, cur.warm & 1u, 1.0f, dx, x);
                 }
             };
 
