@@ -9,6 +9,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <string>
 #include <utility>
@@ -44,9 +45,10 @@ struct gv_ctx {
     std::vector<uint32_t> degree;
     float *vertex = nullptr;
     float *context = nullptr;
-    uint2 *alias = nullptr;
+    uint4 *alias = nullptr;
     bool alias_ready = false;
-    uint8_t *dev_heat = nullptr;          // device, per node: degree class (bits 0..6) and warm flag (bit 7)
+    uint16_t *dev_rank = nullptr;         // device, per node: hot rank (see gv::TrainArgs)
+    uint32_t warm_ranks = 0;              // number of warm rows
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
@@ -138,20 +140,15 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->vertex) (void)hipFree(ctx->vertex);
     if (ctx->context) (void)hipFree(ctx->context);
     if (ctx->alias) (void)hipFree(ctx->alias);
-    if (ctx->dev_heat) (void)hipFree(ctx->dev_heat);
+    if (ctx->dev_rank) (void)hipFree(ctx->dev_rank);
 
     ctx->vertex = ctx->context = nullptr;
     ctx->alias = nullptr;
-    ctx->dev_heat = nullptr;
+    ctx->dev_rank = nullptr;
     ctx->alias_ready = false;
 }
 
 // Logarithmic degree class in 7 bits: min(127, floor(4 log2(1 + degree))).
-uint32_t degree_class(uint32_t degree) {
-    const double c = floor(4.0 * log2(1.0 + (double)degree));
-    return c > 127.0 ? 127u : (uint32_t)c;
-}
-
 int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     int rc = sync_all(ctx);
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
@@ -160,14 +157,8 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     const size_t bytes = (size_t)n * ctx->cfg.dim * sizeof(float);
     GV_HIP(ctx, hipMalloc((void **)&ctx->vertex, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->context, bytes));
-    GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint2)));
-    {
-        // until the alias table is built (it fixes the negative-sampling shares) every row counts as warm
-        std::vector<uint8_t> heat(n);
-        for (uint32_t i = 0; i < n; ++i) heat[i] = (uint8_t)(0x80u | degree_class(deg[i]));
-        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_heat, (size_t)n));
-        GV_HIP(ctx, hipMemcpy(ctx->dev_heat, heat.data(), (size_t)n, hipMemcpyHostToDevice));
-    }
+    GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint4)));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_rank, (size_t)n * sizeof(uint16_t)));  // filled by gv_build_alias
     GV_HIP(ctx, hipMemsetAsync(ctx->vertex, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
@@ -211,7 +202,8 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.alias = ctx->alias;
     a.pairs = dev_pairs;
     a.negatives = nullptr;
-    a.heat = ctx->dev_heat;
+    a.rank = ctx->dev_rank;
+    a.warm_ranks = ctx->warm_ranks;
     a.error_flag = ctx->error_flag;
     a.first_g = first_g;
     a.total = ctx->cfg.total_samples;
@@ -255,7 +247,7 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x40000000u)
+    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u)
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
     else
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
@@ -499,22 +491,38 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         sum += q;
     }
     if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+    // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
+    // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
     // A row is warm when, with kInFlight samples being processed at once, the expected number
     // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
     // or as a negative, share q/sum(q)) exceeds 0.1: the mixed policy then updates it with
     // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
-    // update only when two of the few samples naming such a row are in flight together.
+    // update only when two of the few samples naming such a row are in flight together.  The
+    // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
     const double kInFlight = 8192.0;
     double warm_threshold = 0.1;
     if (const char *e = getenv("GV_WARM_THRESHOLD")) {  // tuning sweeps
         const double v = atof(e);
         if (v > 0.0) warm_threshold = v;
     }
-    std::vector<uint8_t> warm(n);
-    for (uint32_t i = 0; i < n; ++i) {
+    const uint32_t kRanked = 0xFFFFu;
+    std::vector<uint32_t> order(n);
+    for (uint32_t i = 0; i < n; ++i) order[i] = i;
+    const uint32_t ranked = n < kRanked ? n : kRanked;
+    auto hotter = [&](uint32_t x, uint32_t y) {
+        return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;
+    };
+    std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
+    std::vector<uint16_t> rank(n, (uint16_t)kRanked);
+    uint32_t warm_ranks = 0;
+    for (uint32_t r = 0; r < ranked; ++r) {
+        const uint32_t i = order[r];
+        rank[i] = (uint16_t)r;
         const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
-        warm[i] = (uint8_t)((share * kInFlight > warm_threshold ? 0x80u : 0u) | degree_class(ctx->degree[i]));
+        if (share * kInFlight > warm_threshold) warm_ranks = r + 1;
     }
+    order.clear();
+    order.shrink_to_fit();
     std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
     below.reserve(n);
     above.reserve(n);
@@ -522,7 +530,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         p[i] = p[i] * (double)n / sum;
         (p[i] < 1.0 ? below : above).push_back(i);
     }
-    std::vector<uint2> table(n);
+    std::vector<uint4> table(n);
     std::vector<double> keep(n, 1.0);
     for (uint32_t i = 0; i < n; ++i) table[i].y = i;
     while (!below.empty() && !above.empty()) {
@@ -538,11 +546,14 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     for (uint32_t i = 0; i < n; ++i) {
         const double scaled = floor(keep[i] * 4294967296.0);
         table[i].x = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
+        table[i].z = (uint32_t)rank[i] | (uint32_t)rank[table[i].y] << 16;  // saves the kernel a second gather
+        table[i].w = 0u;
     }
     rc = sync_all(ctx);
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
-    GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint2), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_heat, warm.data(), (size_t)n, hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
+    ctx->warm_ranks = warm_ranks;
     ctx->alias_ready = true;
     return GV_OK;
 }
@@ -551,8 +562,8 @@ int gv_get_alias(gv_ctx *ctx, uint32_t *host_thresh, uint32_t *host_alias) {
     int rc = need_trainable(ctx);
     if (rc) return rc;
     if (!host_thresh || !host_alias) return fail(ctx, GV_EINVAL, "null output");
-    std::vector<uint2> table(ctx->n);
-    GV_HIP(ctx, hipMemcpy(table.data(), ctx->alias, (size_t)ctx->n * sizeof(uint2), hipMemcpyDeviceToHost));
+    std::vector<uint4> table(ctx->n);
+    GV_HIP(ctx, hipMemcpy(table.data(), ctx->alias, (size_t)ctx->n * sizeof(uint4), hipMemcpyDeviceToHost));
     for (uint32_t i = 0; i < ctx->n; ++i) {
         host_thresh[i] = table[i].x;
         host_alias[i] = table[i].y;

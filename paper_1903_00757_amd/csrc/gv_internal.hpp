@@ -11,11 +11,13 @@ namespace gv {
 struct TrainArgs {
     float *vertex;            // |V| x d, row-major
     float *context;           // |V| x d, row-major
-    const uint2 *alias;       // per node {threshold, alias}
+    const uint4 *alias;       // per node {threshold, alias, hot rank of the node | hot rank of the alias << 16, 0}
     const uint32_t *pairs;    // count x (u, v)
     const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
-    const uint8_t *heat;      // per node: bits 0..6 degree class min(127, floor(4 log2(1 + degree))), bit 7 =
-                              // warm: updates of this row must not be lost (see gv_build_alias)
+    const uint16_t *rank;     // per node: its place among the nodes by falling degree (ties by id), 0xFFFF
+                              // from place 65535 on ("hot rank")
+    uint32_t warm_ranks;      // rows of hot rank below this are warm: their updates must not be lost
+                              // (see gv_build_alias)
     uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
     uint64_t first_g;         // global position of pairs[0]
     uint64_t total;           // T of the learning-rate schedule
@@ -36,7 +38,7 @@ hipError_t launch_train_tiled(const TrainArgs &a, uint32_t dim, uint32_t num_neg
 // two of them share a vertex row or a context row (negatives included).
 hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);
 // out[i*K + k] = negative k of positive sample first_g + i.
-hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
+hipError_t launch_draw_negatives(const uint4 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
                                  uint32_t num_neg, uint32_t *out, hipStream_t stream);
 // vertex ~ U(-0.5/d, 0.5/d) from Philox stream 1 (context is cleared by the caller).
 hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64_t seed, hipStream_t stream);

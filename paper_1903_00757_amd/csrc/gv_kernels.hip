@@ -45,14 +45,24 @@ __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 // Negative k of positive sample g (Alg. 1, NegativeSampling; Sec. 4.3 alias
 // table): bucket = floor(R * n / 2^64) from the first two words, accepted when
 // the third word is below the bucket's threshold, else the bucket's alias.
-__device__ __forceinline__ uint32_t draw_negative(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
-                                                  uint64_t g, uint32_t k, uint32_t stream = 0u) {
+// The table entry also carries the hot ranks of both candidates.
+struct Drawn {
+    uint32_t id;
+    uint32_t rank;
+};
+__device__ __forceinline__ Drawn draw_ranked_negative(const uint4 *__restrict__ alias, uint32_t n, uint64_t seed,
+                                                      uint64_t g, uint32_t k, uint32_t stream = 0u) {
     const uint4 r =
         philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), k, stream, (uint32_t)seed, (uint32_t)(seed >> 32));
     const uint64_t R = ((uint64_t)r.x << 32) | r.y;
     const uint32_t j = (uint32_t)__umul64hi(R, (uint64_t)n);
-    const uint2 e = alias[j];
-    return r.z < e.x ? j : e.y;
+    const uint4 e = alias[j];
+    const bool keep = r.z < e.x;
+    return Drawn{keep ? j : e.y, keep ? (e.z & 0xFFFFu) : (e.z >> 16)};
+}
+__device__ __forceinline__ uint32_t draw_negative(const uint4 *__restrict__ alias, uint32_t n, uint64_t seed,
+                                                  uint64_t g, uint32_t k, uint32_t stream = 0u) {
+    return draw_ranked_negative(alias, n, seed, g, k, stream).id;
 }
 
 // Learning rate of positive sample g (Sec. 4.3: linear decay from lr0), fp64 then fp32.
@@ -352,9 +362,9 @@ __device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, 
 // ---------------------------------------------------------------------------
 // Tiled stationary-row training.  A workgroup takes a tile of kTile consecutive samples
 // of the pool, tags every sample with the hottest of its rows (vertex[u], context[v] or the
-// context row of a negative; decided by a one-byte degree class per node, ties going to the
-// earlier of the three) and sorts the tile by that row in LDS, so that samples sharing their
-// hot row become adjacent.  Each of its four waves then walks a quarter of the sorted tile
+// context row of a negative: the one of lowest hot rank, ties going to the earlier of the
+// three) and sorts the tile by that row in LDS, so that samples sharing their hot row become
+// adjacent.  Each of its four waves then walks a quarter of the sorted tile
 // and keeps the hot row in registers for as long as consecutive samples name it: the row is
 // read once per run, the run's updates are applied to the register copy in order, and the
 // run's change is added to memory with fp32 atomic adds (nothing another wave adds meanwhile
@@ -366,20 +376,17 @@ __device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, 
 // front to back and a row's samples stay spread over time.  Every sample keeps the
 // negatives and the learning rate of its position in the pool.
 template <int kTile>
-__device__ __forceinline__ void sort_tile(uint32_t *key, uint32_t *pos) {
+__device__ __forceinline__ void sort_tile(uint32_t *word) {
     for (uint32_t k = 2; k <= (uint32_t)kTile; k <<= 1) {
         for (uint32_t j = k >> 1; j > 0; j >>= 1) {
             for (uint32_t t = threadIdx.x; t < (uint32_t)kTile / 2; t += kBlock) {
                 const uint32_t lo = 2 * t - (t & (j - 1));  // partner pairs (lo, lo + j) of this bitonic step
                 const uint32_t hi = lo + j;
                 const bool ascending = (lo & k) == 0;
-                const uint32_t ka = key[lo], kb = key[hi];
-                if ((ka > kb) == ascending) {
-                    key[lo] = kb;
-                    key[hi] = ka;
-                    const uint32_t pa = pos[lo];
-                    pos[lo] = pos[hi];
-                    pos[hi] = pa;
+                const uint32_t wa = word[lo], wb = word[hi];
+                if ((wa > wb) == ascending) {
+                    word[lo] = wb;
+                    word[hi] = wa;
                 }
             }
             __syncthreads();
@@ -401,15 +408,22 @@ struct TileSample {
 template <int kV, int kK, int kCoherence, int kTile>
 __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     const uint32_t D = a.dim;
-    constexpr uint32_t kSkip = 0xFFFFFFFFu;  // key of a slot without a trainable sample
+    // One sort word per sample.  On top, 14 bits for its stationary row: the matrix, then either
+    // the hot rank (the kGroupedRanks hottest rows: their samples must end up adjacent) or a
+    // 12-bit hash of the row id (the others: they turn up less than once per tile, and the hash
+    // puts their samples in an order unrelated to the pool's, where neighbours come from one
+    // walk and often share a row).  Below, the number of that row within the sample (3 bits),
+    // the sample's slot in the tile (13 bits) and the warm flags of u and v (2 bits).
+    constexpr uint32_t kSkip = 0xFFFFFFFFu;  // word of a slot without a trainable sample (row number 7 is never used)
+    constexpr uint32_t kSlotBits = 13, kGroupedRanks = 4096;
+    static_assert(kTile <= (1 << kSlotBits) && kTile >= 2 * kBlock, "tile size");
+    static_assert(kK + 1 < 7, "row numbers take three bits and 7 is reserved");
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
-    static_assert(kTile <= 65536, "the slot number of a sample shares its word with the row number and two flags");
     // samples whose gathers are in flight together: bounded by the registers their rows take
     constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
     using Io = RowIo<kV, kCoherence>;
-    __shared__ uint32_t s_key[kTile];
-    __shared__ uint32_t s_pos[kTile];  // bits 0..15 slot in the tile, 16..18 stationary row number, 30/31 warm u/v
+    __shared__ uint32_t s_word[kTile];
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
@@ -417,47 +431,44 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint32_t tile_base = tile * kTile;
-        // Every tile sorts by its own scrambled view of (matrix, row id): equal rows still end up
-        // adjacent, but the order in which a tile reaches the rows differs from tile to tile.
-        // With one common order all workgroups, started together, would reach the same rows at
-        // the same moment, and a row would receive its updates of thousands of tiles in one
-        // burst, all computed from the same stale value.
-        const uint32_t id_bits = a.n > 1u ? 32u - (uint32_t)__builtin_clz(a.n - 1u) : 0u;  // <= 30 (checked at launch)
-        const uint32_t scramble = (id_bits ? (tile * 0x9E3779B1u) >> (32u - id_bits) : 0u) | (tile & 1u) << 31;
+        // Every tile orders the rows through its own mask, so the order in which a tile reaches
+        // the hot rows differs from tile to tile.  With one common order all workgroups, started
+        // together, would reach the same rows at the same moment, and a row would receive its
+        // updates of thousands of tiles in one burst, all computed from the same stale value.
+        const uint32_t scramble = (tile * 0x9E3779B1u) >> 18;  // 14 bits
         for (uint32_t t = threadIdx.x; t < (uint32_t)kTile; t += kBlock) {
-            uint32_t key = kSkip, slot = t;
+            uint32_t word = kSkip;
             if (tile_base + t < a.count) {
                 const uint2 p = pairs[tile_base + t];
                 if (p.x < a.n && p.y < a.n) {
-                    // heat byte: bits 0..6 a logarithmic degree class, bit 7 the warm flag
-                    const uint32_t hu = a.heat[p.x], hv = a.heat[p.y];
-                    uint32_t best = hu & 127u, held = 0u, row = p.x;
-                    if ((hv & 127u) > best) {
-                        best = hv & 127u;
+                    const uint32_t ru = a.rank[p.x], rv = a.rank[p.y];
+                    uint32_t best = ru, held = 0u, row = p.x;
+                    if (rv < best) {
+                        best = rv;
                         held = 1u;
                         row = p.y;
                     }
 #pragma unroll
                     for (int k = 0; k < kK; ++k) {
-                        const uint32_t nk = draw_negative(a.alias, a.n, a.seed, a.first_g + tile_base + t, k);
-                        const uint32_t hn = a.heat[nk] & 127u;
-                        if (hn > best) {
-                            best = hn;
+                        const Drawn nk = draw_ranked_negative(a.alias, a.n, a.seed, a.first_g + tile_base + t, k);
+                        if (nk.rank < best) {
+                            best = nk.rank;
                             held = 2u + k;
-                            row = nk;
+                            row = nk.id;
                         }
                     }
-                    key = (held == 0u ? row : (0x80000000u | row)) ^ scramble;
-                    slot |= held << 16 | (hu >> 7) << 30 | (hv >> 7) << 31;
+                    const uint32_t group = (held == 0u ? 0u : 1u << 13) |
+                                           (best < kGroupedRanks ? __brev(best) >> 20 : kGroupedRanks | (row * 0x9E3779B1u) >> 20);
+                    const uint32_t warm_uv = (ru < a.warm_ranks ? 1u : 0u) | (rv < a.warm_ranks ? 2u : 0u);
+                    word = (group ^ scramble) << 18 | held << 15 | t << 2 | warm_uv;
                 } else {
                     *a.error_flag = 1u;  // the sample is skipped and reported at the next synchronisation
                 }
             }
-            s_key[t] = key;
-            s_pos[t] = slot;
+            s_word[t] = word;
         }
         __syncthreads();
-        sort_tile<kTile>(s_key, s_pos);
+        sort_tile<kTile>(s_word);
 
         float *held = nullptr;   // address of the row kept in y[]
         bool held_warm = true;   // its merge must not lose concurrent updates
@@ -477,25 +488,20 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
         };
 
         for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
-            const uint32_t tag = s_key[base + lane];
-            const bool mine = tag != kSkip;
-            const uint32_t slot = s_pos[base + lane];
-            const uint32_t pos = tile_base + (slot & 0xFFFFu);
+            const uint32_t word = s_word[base + lane];
+            const bool mine = word != kSkip;
+            const uint32_t pos = tile_base + ((word >> 2) & ((1u << kSlotBits) - 1u));
             const uint2 p = mine ? pairs[pos] : make_uint2(0u, 0u);
             const uint64_t g = a.first_g + pos;
             uint32_t neg[kK];
+            uint32_t warm = word & 3u;  // bit j: row j of the sample is warm
 #pragma unroll
-            for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
-            const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
-            uint32_t warm = 0xFFFFFFFFu;
-            if constexpr (kCoherence == kMixed) {
-                warm = 0;
-                if (mine) {
-                    warm = slot >> 30;
-#pragma unroll
-                    for (int k = 0; k < kK; ++k) warm |= ((uint32_t)a.heat[neg[k]] >> 7) << (2 + k);
-                }
+            for (int k = 0; k < kK; ++k) {
+                const Drawn nk = draw_ranked_negative(a.alias, a.n, a.seed, g, k);
+                neg[k] = nk.id;
+                warm |= (nk.rank < a.warm_ranks ? 1u : 0u) << (2 + k);
             }
+            const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
             // sorted order puts the skipped slots last: the first one ends this wave's work
             const uint64_t live = __ballot(mine);
             const uint32_t in_chunk = live == ~0ull ? (uint32_t)kWave : (uint32_t)__builtin_ctzll(~live);
@@ -511,7 +517,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                 for (int k = 0; k < kK; ++k) s.id[2 + k] = lane_value(neg[k], i);
                 s.warm = lane_value(warm, i);
                 s.lr = __uint_as_float(lane_value(__float_as_uint(lr), i));
-                s.held = (lane_value(slot, i) >> 16) & 7u;
+                s.held = (lane_value(word, i) >> 15) & 7u;
                 s.stationary = row_address(s, 0);
 #pragma unroll
                 for (int j = 1; j <= kK + 1; ++j)
@@ -757,7 +763,7 @@ __global__ __launch_bounds__(kBlock) void k_cosine(const float *__restrict__ ver
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint2 *__restrict__ alias, uint32_t n, uint64_t seed,
+__global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint4 *__restrict__ alias, uint32_t n, uint64_t seed,
                                                            uint64_t first_g, uint64_t count, uint32_t num_neg,
                                                            uint32_t *__restrict__ out) {
     const uint64_t total = count * num_neg;
@@ -846,14 +852,18 @@ hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blo
 template <int kV, int kK>
 hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
-    if (a.heat == nullptr || a.n > 0x40000000u) return hipErrorInvalidValue;  // row ids leave key bit 30 free
-    static const uint32_t tile = env_u32("GV_TILE", 2048u);  // tuning sweeps: 512, 1024 or 2048
-    uint32_t blocks = hogwild_blocks(a.count, a.n);
+    if (a.rank == nullptr) return hipErrorInvalidValue;
+    static const uint32_t tile = env_u32("GV_TILE", 8192u);  // tuning sweeps: 2048, 4096 or 8192
+    // One workgroup per tile, started by the hardware in tile order as earlier ones end, unless the
+    // graph is so small that fewer samples must be in flight: then a fixed number of workgroups
+    // strides over the tiles.
+    const uint32_t limit = hogwild_blocks(a.count, a.n);
     const uint32_t tiles = (a.count + tile - 1) / tile;
-    if (blocks > tiles) blocks = tiles;
-    if (tile == 512) return launch_tiled_vkt<kV, kK, 512>(a, coherence, blocks, stream);
+    static const uint32_t fixed_grid = env_u32("GV_GRID_BLOCKS", 0u);
+    const uint32_t blocks = (limit >= 2048u && fixed_grid == 0u) || limit > tiles ? tiles : limit;
     if (tile == 2048) return launch_tiled_vkt<kV, kK, 2048>(a, coherence, blocks, stream);
-    return launch_tiled_vkt<kV, kK, 1024>(a, coherence, blocks, stream);
+    if (tile == 4096) return launch_tiled_vkt<kV, kK, 4096>(a, coherence, blocks, stream);
+    return launch_tiled_vkt<kV, kK, 8192>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -938,7 +948,7 @@ hipError_t launch_cosine(const float *vertex, uint32_t n, uint32_t dim, const ui
     return hipGetLastError();
 }
 
-hipError_t launch_draw_negatives(const uint2 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
+hipError_t launch_draw_negatives(const uint4 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
                                  uint32_t num_neg, uint32_t *out, hipStream_t stream) {
     const uint64_t total = count * num_neg;
     if (total == 0) return hipSuccess;
