@@ -371,6 +371,31 @@ def test_hogwild_quality_matches_oracle_on_tiny(gv, policy):
 
 
 @pytest.mark.parametrize("policy", LOSSLESS_POLICIES)
+def test_hogwild_quality_with_five_negatives(gv, policy):
+    """The shape of configuration 3 (K = 5, weight 1) on the small graph, d = 64: with several negatives the
+    tiled schedule may keep any of the K + 2 rows of a sample in registers.  Same gates as above."""
+    n, src, dst = W.make_graph("tiny", cache=False)
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, 0.05, seed=31)
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    total, d, K, w = 8_000_000, 64, 5, 1.0
+    pool, _ = oracle.augment(103, offsets, adj, 40, 5, total, shuffle_seed=7)
+    eval_pool, _ = oracle.augment(203, offsets, adj, 40, 5, 1 << 17, shuffle_seed=8)
+    vertex, context = oracle.init_embeddings(1, n, d)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, total, 1234, policy)
+    ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, total, 1234)
+    loss_gpu = evaluation_loss(deg, got_v, got_c, eval_pool, K, w)
+    loss_ref = evaluation_loss(deg, ref_v, ref_c, eval_pool, K, w)
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=32)
+    auc_gpu = oracle.link_prediction_auc(got_v, te_s, te_d, na, nb)
+    auc_ref = oracle.link_prediction_auc(ref_v, te_s, te_d, na, nb)
+    print(f"tiny K=5 policy={policy}: loss {loss_gpu:.5f} vs {loss_ref:.5f}; auc {auc_gpu:.4f} vs {auc_ref:.4f}")
+    assert loss_ref < 0.8 * evaluation_loss(deg, vertex, context, eval_pool, K, w)  # the run did learn
+    assert abs(loss_gpu - loss_ref) <= 0.02 * loss_ref
+    assert abs(auc_gpu - auc_ref) <= 0.005
+
+
+@pytest.mark.parametrize("policy", LOSSLESS_POLICIES)
 def test_hogwild_quality_on_planted_partition(gv, policy):
     """Scaled-down configuration 4 (5000 nodes, 10 communities, 5*10^4 edges, 5 % held out,
     8*10^6 samples in 2^20-sample pools, trained to the plateau): loss within 2 %, AUC within
