@@ -57,12 +57,13 @@ enum { GV_VERTEX = 0, GV_CONTEXT = 1 };
 enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT = 2, GV_COHERENCE_MIXED = 3 };
 /* Order in which an asynchronous launch walks a pool.
  *   POOL_ORDER   waves take chunks of 64 consecutive samples.
- *   TILED        workgroups take tiles of 1024 consecutive samples and sort each tile
- *                by the hotter row of every sample (the higher-degree one of u, v); a
- *                wave keeps that row in registers across the run of samples sharing it
- *                and adds the run's total change to memory once.  The launch still
- *                moves through the pool front to back, and each sample keeps the
- *                negatives and learning rate of its position in the pool.          */
+ *   TILED        workgroups take tiles of 8192 consecutive samples and sort each tile
+ *                by the hottest row of every sample (the highest-degree one of u, v and
+ *                the negatives); a wave keeps that row in registers across the run of
+ *                samples sharing it, trading its change with memory every four samples
+ *                and at the end of the run.  The launch still moves through the pool
+ *                front to back, and each sample keeps the negatives and learning rate
+ *                of its position in the pool.                                         */
 enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1 };
 
 typedef struct gv_config {

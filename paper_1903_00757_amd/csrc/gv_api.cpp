@@ -493,7 +493,8 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
     // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
     // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
-    // A row is warm when, with kInFlight samples being processed at once, the expected number
+    // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
+    // a full launch: several thousand waves, a few samples each), the expected number
     // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
     // or as a negative, share q/sum(q)) exceeds 0.1: the mixed policy then updates it with
     // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
