@@ -340,6 +340,47 @@ def test_tiled_run_on_one_hub_row_is_sequential(gv, policy):
     assert np.array_equal(got_c[untouched], context[untouched])
 
 
+@pytest.mark.parametrize("policy", [(POOL_ORDER, ATOMIC), (TILED, AGENT), (TILED, ATOMIC), (TILED, MIXED)])
+def test_single_samples_with_repeated_rows(gv, policy):
+    """Three nodes, K = 3: one-sample pools at positions whose negatives repeat v, repeat each other, or equal
+    the row the tiled schedule keeps in registers.  One sample alone is one sequential step whatever the
+    schedule, so every pattern of repeated rows must reproduce the oracle's step."""
+    n, d, K, w, seed, T = 3, 128, 3, 1.0, 3, 1000
+    deg = np.array([1, 2, 1], dtype=np.uint32)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    cases = {}
+    for g in range(300):
+        negs = oracle.draw_negatives(seed, g, 1, K, thresh, alias)[0]
+        for u in range(n):
+            for v in range(n):
+                rows = [v] + [int(x) for x in negs]
+                pattern = (u, tuple(rows.index(r) for r in rows))  # which rows coincide, and who is u
+                cases.setdefault(pattern, (g, u, v))
+    assert len(cases) >= 12
+    schedule, coherence = policy
+    vertex, context = random_embeddings(n, d, seed=11)
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=8, lr0=LR0, coherence=coherence, schedule=schedule) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        for pattern, (g, u, v) in sorted(cases.items()):
+            pool = np.array([[u, v]], dtype=np.uint32)
+            gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+            gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+            gv.gv_set_position(ctx, g)
+            gv.gv_push_pool(ctx, pool)
+            gv.gv_train_pool(ctx)
+            gv.gv_sync(ctx)
+            got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+            got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+            ref_v, ref_c = vertex.copy(), context.copy()
+            oracle.train(ref_v, ref_c, pool, K=K, first_g=g, T=T, lr0=LR0, lr_min_ratio=0.0, w=w, seed=seed,
+                         thresh=thresh, alias=alias)
+            for got, ref, start in ((got_v, ref_v, vertex), (got_c, ref_c, context)):
+                step = np.abs(ref - start).max()
+                assert np.abs(got - ref).max() <= 1e-4 * step + 1e-7, (pattern, g, u, v)
+
+
 def evaluation_loss(deg, vertex, context, eval_pool, K, w):
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     return oracle.loss(vertex, context, eval_pool, K=K, w=w, seed=99, thresh=thresh, alias=alias)
