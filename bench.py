@@ -193,6 +193,32 @@ def main():
                                           "host-bound"}
             log(f"online: {streamed['online']['value']:.4g} samples/s end to end, producer alone "
                 f"{P / produce_s:.4g} samples/s on {threads} threads")
+            # The same pipeline with the producer on the device (gv_augment_device): pool k+1 is written
+            # into the buffer that pool k-1 was trained from; producer and trainer share one stream.
+            gv.gv_set_adjacency(ctx, offsets, adj)
+            bufs = [torch.empty((P, 2), dtype=torch.int32, device="cuda") for _ in range(2)]
+            for i in range(2):
+                gv.gv_augment_device(ctx, bufs[i].data_ptr(), seed=901, first_walk=i * walks_per_pool, count=P)
+            gv.gv_sync(ctx)
+            t0 = time.perf_counter()
+            for i in range(8):
+                gv.gv_augment_device(ctx, bufs[i % 2].data_ptr(), seed=901, first_walk=i * walks_per_pool, count=P)
+            gv.gv_sync(ctx)
+            produce_d = (time.perf_counter() - t0) / 8
+            steps = args.steps
+            t0 = time.perf_counter()
+            for i in range(steps):
+                gv.gv_augment_device(ctx, bufs[i % 2].data_ptr(), seed=902, first_walk=i * walks_per_pool, count=P)
+                gv.gv_train_device_pool(ctx, bufs[i % 2].data_ptr(), P)
+            gv.gv_sync(ctx)
+            wall_d = time.perf_counter() - t0
+            streamed["online_device"] = {"value": steps * P / wall_d, "unit": "positive samples/s", "steps": steps,
+                                         "producer_alone": P / produce_d,
+                                         "note": "pools generated on the GPU by gv_augment_device, then trained; "
+                                                 "nothing crosses PCIe"}
+            log(f"online on the device: {streamed['online_device']['value']:.4g} samples/s end to end, producer "
+                f"alone {P / produce_d:.4g} samples/s")
+            del bufs
     finally:
         gv.gv_destroy(ctx)
 

@@ -167,6 +167,23 @@ int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_ad
                uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
                uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used);
 
+/* The same producer on the device (Sec. 3.1, Alg. 2; the paper runs it on the host CPUs: a
+ * host with few cores per GPU cannot feed this trainer, see gv_augment).
+ * gv_set_adjacency uploads the CSR adjacency of the graph given to gv_set_graph /
+ * gv_set_degrees: host_offsets[n + 1] (offsets[0] = 0, row i has degree(i) entries),
+ * host_adj[offsets[n]] with both directions of every edge; both are copied, the caller keeps
+ * its arrays.  Errors: GV_ESTATE without a graph, GV_EINVAL when a row length differs from
+ * the node's degree, an entry is >= n or the graph has no edge.
+ * gv_augment_device writes the pool that gv_augment would write for the same arguments
+ * (bit-identical: same walks, same random numbers, same order) into dev_pairs[count][2] in
+ * DEVICE memory, asynchronously on the context's compute stream, i.e. ordered with
+ * gv_train_device_pool calls before and after it: a buffer may be refilled right after the
+ * call that trains it, and trained right after the call that fills it.  walk_length <= 64.
+ * *walks_used (may be NULL) receives the number of walks consumed.                          */
+int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *host_adj);
+int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t window, uint64_t first_walk,
+                      uint64_t count, uint32_t shuffle, uint32_t *dev_pairs, uint64_t *walks_used);
+
 /* The K negatives of positive samples first_g .. first_g+count-1, exactly as
  * training draws them: host_out[count][K].                                     */
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out);

@@ -24,6 +24,7 @@ EXPORTS = [
     "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
     "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
+    "gv_set_adjacency", "gv_augment_device",
 ]
 
 
@@ -95,6 +96,9 @@ def load():
     L.gv_cosine.argtypes = [vp, u32p, u32p, C.c_uint64, f32p]
     L.gv_augment.argtypes = [C.c_uint32, C.POINTER(C.c_uint64), u32p, C.c_uint64, C.c_uint32, C.c_uint32,
                              C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, vp, C.POINTER(C.c_uint64)]
+    L.gv_set_adjacency.argtypes = [vp, C.POINTER(C.c_uint64), u32p]
+    L.gv_augment_device.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32, vp,
+                                    C.POINTER(C.c_uint64)]
     for name in EXPORTS:
         if name not in ("gv_destroy", "gv_last_error"):
             getattr(L, name).restype = C.c_int
@@ -257,3 +261,19 @@ def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, co
     if rc != GV_OK:
         raise GvError(rc, "gv_augment: bad argument")
     return out[:count], walks.value
+
+
+def gv_set_adjacency(ctx, offsets, adj):
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    adj = np.ascontiguousarray(adj, dtype=np.uint32)
+    _check(ctx, load().gv_set_adjacency(ctx, offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                        adj.ctypes.data_as(C.POINTER(C.c_uint32))))
+
+
+def gv_augment_device(ctx, device_ptr, *, seed, walk_length=40, window=5, first_walk=0, count,
+                      shuffle=GV_SHUFFLE_PSEUDO):
+    """Fill device memory at ``device_ptr`` (room for count x 2 uint32) with walk samples; returns walks used."""
+    walks = C.c_uint64()
+    _check(ctx, load().gv_augment_device(ctx, seed, walk_length, window, first_walk, count, shuffle,
+                                         C.c_void_p(device_ptr), C.byref(walks)))
+    return walks.value

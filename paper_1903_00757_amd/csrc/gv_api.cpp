@@ -49,6 +49,9 @@ struct gv_ctx {
     bool alias_ready = false;
     uint16_t *dev_rank = nullptr;         // device, per node: hot rank (see gv::TrainArgs)
     uint32_t warm_ranks = 0;              // number of warm rows
+    uint64_t *dev_offsets = nullptr;      // device CSR of the graph (gv_set_adjacency), for the device producer
+    uint32_t *dev_adj = nullptr;
+    uint64_t half_edges = 0;
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
@@ -141,7 +144,11 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->context) (void)hipFree(ctx->context);
     if (ctx->alias) (void)hipFree(ctx->alias);
     if (ctx->dev_rank) (void)hipFree(ctx->dev_rank);
-
+    if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
+    if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
+    ctx->dev_offsets = nullptr;
+    ctx->dev_adj = nullptr;
+    ctx->half_edges = 0;
     ctx->vertex = ctx->context = nullptr;
     ctx->alias = nullptr;
     ctx->dev_rank = nullptr;
@@ -702,6 +709,65 @@ int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count)
     if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
     if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
     return train_any(ctx, dev_pairs, nullptr, count);
+}
+
+int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *host_adj) {
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (!host_offsets || !host_adj) return fail(ctx, GV_EINVAL, "null adjacency");
+    const uint32_t n = ctx->n;
+    if (host_offsets[0] != 0) return fail(ctx, GV_EINVAL, "offsets[0] must be 0");
+    for (uint32_t i = 0; i < n; ++i)
+        if (host_offsets[i + 1] - host_offsets[i] != (uint64_t)ctx->degree[i])
+            return fail(ctx, GV_EINVAL, "row %u of the adjacency has %llu entries, the graph gives node %u degree %u", i,
+                        (unsigned long long)(host_offsets[i + 1] - host_offsets[i]), i, ctx->degree[i]);
+    const uint64_t half_edges = host_offsets[n];
+    if (half_edges == 0) return fail(ctx, GV_EINVAL, "graph without edges");
+    for (uint64_t e = 0; e < half_edges; ++e)
+        if (host_adj[e] >= n) return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
+    rc = sync_all(ctx);
+    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
+    if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
+    ctx->dev_offsets = nullptr;
+    ctx->dev_adj = nullptr;
+    ctx->half_edges = 0;
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_offsets, ((size_t)n + 1) * sizeof(uint64_t)));
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_adj, (size_t)half_edges * sizeof(uint32_t)));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_offsets, host_offsets, ((size_t)n + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_adj, host_adj, (size_t)half_edges * sizeof(uint32_t), hipMemcpyHostToDevice));
+    ctx->half_edges = half_edges;
+    return GV_OK;
+}
+
+int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t window, uint64_t first_walk,
+                      uint64_t count, uint32_t shuffle, uint32_t *dev_pairs, uint64_t *walks_used) {
+    if (walks_used) *walks_used = 0;
+    int rc = need_graph(ctx);
+    if (rc) return rc;
+    if (!ctx->dev_offsets) return fail(ctx, GV_ESTATE, "no adjacency: call gv_set_adjacency first");
+    if (walk_length == 0 || walk_length > 64 || window == 0 || shuffle > GV_SHUFFLE_PSEUDO)
+        return fail(ctx, GV_EINVAL, "walk_length must be in 1..64, window >= 1, shuffle GV_SHUFFLE_*");
+    if (count == 0) return GV_OK;
+    if (!dev_pairs) return fail(ctx, GV_EINVAL, "null output");
+    gv::AugmentArgs a{};
+    a.offsets = ctx->dev_offsets;
+    a.adj = ctx->dev_adj;
+    a.pairs = (uint2 *)dev_pairs;
+    a.half_edges = ctx->half_edges;
+    a.seed = seed;
+    a.first_walk = first_walk;
+    a.count = count;
+    a.per_walk = 0;  // pairs (i, j), i < j <= min(i + window, walk_length)
+    for (uint32_t d = 1; d <= window && d <= walk_length; ++d) a.per_walk += walk_length + 1 - d;
+    a.walks = (count + a.per_walk - 1) / a.per_walk;
+    a.n = ctx->n;
+    a.length = walk_length;
+    a.window = window;
+    a.pseudo_shuffle = shuffle == GV_SHUFFLE_PSEUDO ? 1u : 0u;
+    if (walks_used) *walks_used = a.walks;
+    GV_HIP(ctx, gv::launch_augment(a, ctx->compute));
+    return GV_OK;
 }
 
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out) {

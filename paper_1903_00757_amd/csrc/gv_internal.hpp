@@ -48,6 +48,18 @@ hipError_t launch_eval_loss(const TrainArgs &a, uint32_t dim, uint32_t num_neg, 
 hipError_t launch_cosine(const float *vertex, uint32_t n, uint32_t dim, const uint32_t *first, const uint32_t *second,
                          uint32_t count, float *out, uint32_t *error_flag, hipStream_t stream);
 
+// One pool of walk samples written on the device (see k_augment).
+struct AugmentArgs {
+    const uint64_t *offsets;  // CSR row starts, n + 1 entries
+    const uint32_t *adj;      // neighbours, both directions of every edge
+    uint2 *pairs;             // output, count x (u, v)
+    uint64_t half_edges;      // offsets[n]
+    uint64_t seed, first_walk, walks, count, per_walk;
+    uint32_t n, length, window, pseudo_shuffle;
+};
+// walk length at most 64
+hipError_t launch_augment(const AugmentArgs &a, hipStream_t stream);
+
 bool supported_shape(uint32_t dim, uint32_t num_neg);
 
 }  // namespace gv

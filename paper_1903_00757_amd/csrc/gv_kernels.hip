@@ -795,6 +795,60 @@ __global__ __launch_bounds__(kBlock) void k_init_vertex(float *__restrict__ vert
     }
 }
 
+// ---------------------------------------------------------------------------
+// Producer on the device: online augmentation (Sec. 3.1, Alg. 2) with the pseudo shuffle of
+// the same section, one thread per random walk.  Walk w departs at the owner of a uniformly
+// chosen half-edge (probability proportional to degree), takes `length` uniform steps over the
+// CSR adjacency and emits every ordered pair (w_i, w_j), i < j <= i + window, in order of i then
+// j; sample number t of the pool (walks concatenated) goes to position t, or, pseudo-shuffled,
+// to block t mod window at offset t / window.  Random numbers: Philox stream 4, counter
+// (walk number, step): the pool depends on nothing but the seed and the walk numbers.
+constexpr int kWalkBlock = 128;    // threads (= walks) per workgroup
+constexpr int kMaxWalkLength = 64;
+
+__device__ __forceinline__ uint64_t pick_below(uint4 r, uint64_t range) {
+    return __umul64hi(((uint64_t)r.x << 32) | r.y, range);
+}
+
+__global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
+    __shared__ uint32_t s_path[kMaxWalkLength + 1][kWalkBlock];  // a walk's nodes, one column per thread
+    const uint64_t w = (uint64_t)blockIdx.x * kWalkBlock + threadIdx.x;
+    if (w >= a.walks) return;
+    const uint32_t L = a.length, s = a.window;
+    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+    const uint64_t walk = a.first_walk + w;
+    // departure: last node whose first half-edge is at or before the chosen one
+    const uint64_t e = pick_below(philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), 0u, 4u, k0, k1), a.half_edges);
+    uint32_t lo = 0, hi = a.n;  // offsets[lo] <= e < offsets[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (a.offsets[mid] <= e) lo = mid; else hi = mid;
+    }
+    uint32_t x = lo;
+    s_path[0][threadIdx.x] = x;
+    for (uint32_t t = 1; t <= L; ++t) {
+        const uint64_t begin = a.offsets[x], degree = a.offsets[x + 1] - begin;
+        x = a.adj[begin + pick_below(philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), t, 4u, k0, k1), degree)];
+        s_path[t][threadIdx.x] = x;
+    }
+    uint64_t t_global = w * a.per_walk;
+    for (uint32_t i = 0; i <= L; ++i) {
+        const uint32_t from = s_path[i][threadIdx.x];
+        for (uint32_t j = i + 1; j <= L && j <= i + s; ++j, ++t_global) {
+            if (t_global >= a.count) return;
+            uint64_t at = t_global;
+            if (a.pseudo_shuffle) {
+                const uint64_t b = t_global % s, q = t_global / s;
+                // block b holds the samples b, b + s, b + 2s, ...: blocks before it hold
+                // ceil((count - b') / s) samples each
+                const uint64_t whole = a.count / s, extra = a.count % s;  // the first `extra` blocks hold one more
+                at = b * whole + (b < extra ? b : extra) + q;
+            }
+            a.pairs[at] = make_uint2(from, s_path[j][threadIdx.x]);
+        }
+    }
+}
+
 uint32_t env_u32(const char *name, uint32_t fallback) {
     const char *s = getenv(name);
     if (!s || !*s) return fallback;
@@ -965,6 +1019,15 @@ hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64
     const uint64_t wanted = (total + kBlock - 1) / kBlock;
     const uint32_t blocks = (uint32_t)(wanted < 65536 ? wanted : 65536);
     hipLaunchKernelGGL(k_init_vertex, dim3(blocks), dim3(kBlock), 0, stream, vertex, rows, dim, seed);
+    return hipGetLastError();
+}
+
+hipError_t launch_augment(const AugmentArgs &a, hipStream_t stream) {
+    if (a.walks == 0) return hipSuccess;
+    if (a.length == 0 || a.length > (uint32_t)kMaxWalkLength || a.window == 0) return hipErrorInvalidValue;
+    const uint64_t blocks = (a.walks + kWalkBlock - 1) / kWalkBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_augment, dim3((uint32_t)blocks), dim3(kWalkBlock), 0, stream, a);
     return hipGetLastError();
 }
 

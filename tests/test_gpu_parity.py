@@ -798,6 +798,99 @@ def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w
     assert cos[0] == 0 and cos[1] == 0 and cos[2] == 0
 
 
+# --------------------------------------------------------------------------- producer on the device
+@pytest.mark.parametrize("L,s,count,first_walk,shuffle", [
+    (40, 5, 190 * 300, 0, 0), (40, 5, 190 * 300, 0, 1), (40, 5, 57_123, 1000, 1), (40, 5, 7, 5, 1), (40, 5, 1, 0, 1),
+    (40, 2, 40_000, 17, 1), (7, 7, 10_000, 3, 1), (3, 5, 9_999, 0, 1), (64, 5, 30_000, 2**33, 1), (1, 1, 500, 0, 0),
+])
+def test_device_producer_writes_the_oracle_pool(gv, tiny_graph, L, s, count, first_walk, shuffle):
+    """gv_augment_device fills device memory with exactly the pool of the oracle's augmentation
+    (and pseudo shuffle): same walks, same pairs, same order, also for ragged counts, walks far
+    into the stream, and windows wider than the walk."""
+    import torch
+
+    g = tiny_graph
+    with context_for(gv, dim=32, num_neg=1, neg_weight=5.0, mode=gv.GV_MODE_HOGWILD, total_samples=10, seed=1,
+                     pool_capacity=8, lr0=LR0) as ctx:
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_set_adjacency(ctx, g["offsets"], g["adj"])
+        out = torch.full((count + 3, 2), -1, dtype=torch.int32, device="cuda")
+        walks = gv.gv_augment_device(ctx, out.data_ptr(), seed=91, walk_length=L, window=s, first_walk=first_walk,
+                                     count=count, shuffle=shuffle)
+        gv.gv_sync(ctx)
+        got = out.cpu().numpy().view(np.uint32)
+    ref, ref_walks = oracle.augment(91, g["offsets"], g["adj"], L, s, count, first_walk=first_walk)
+    if shuffle:
+        ref = oracle.pseudo_shuffle(ref, s)
+    assert walks == ref_walks
+    assert np.array_equal(got[:count], ref)
+    assert (got[count:] == 0xFFFFFFFF).all()  # nothing written past the pool
+
+
+def test_device_producer_feeds_training_like_the_host_producer(gv, tiny_graph):
+    """A pool produced on the device and trained from there gives the same embeddings as the same pool
+    produced by the host producer and pushed (deterministic mode: bit-identical)."""
+    import torch
+
+    g = tiny_graph
+    d, K, count = 64, 2, 50_000
+    vertex, context = random_embeddings(g["n"], d, seed=4)
+    results = []
+    for how in ("host", "device"):
+        with context_for(gv, dim=d, num_neg=K, neg_weight=2.5, mode=gv.GV_MODE_DETERMINISTIC, total_samples=2 * count,
+                         seed=6, pool_capacity=count, lr0=LR0) as ctx:
+            gv.gv_set_degrees(ctx, g["deg"])
+            gv.gv_build_alias(ctx, 0.75)
+            gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+            gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+            if how == "host":
+                for k in range(2):
+                    pool, walks = gv.gv_augment(g["offsets"], g["adj"], seed=8, first_walk=k * 264, count=count, threads=4)
+                    gv.gv_push_pool(ctx, pool)
+                    gv.gv_train_pool(ctx)
+            else:
+                gv.gv_set_adjacency(ctx, g["offsets"], g["adj"])
+                buf = torch.empty((count, 2), dtype=torch.int32, device="cuda")
+                for k in range(2):  # the buffer is refilled right behind the launch that trains it
+                    gv.gv_augment_device(ctx, buf.data_ptr(), seed=8, first_walk=k * 264, count=count)
+                    gv.gv_train_device_pool(ctx, buf.data_ptr(), count)
+            gv.gv_sync(ctx)
+            results.append((gv.gv_read_embeddings(ctx, gv.GV_VERTEX, g["n"], d),
+                            gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, g["n"], d)))
+    assert np.array_equal(results[0][0], results[1][0]) and np.array_equal(results[0][1], results[1][1])
+    assert not np.array_equal(results[0][0], vertex)
+
+
+def test_device_producer_argument_errors(gv, tiny_graph):
+    import torch
+
+    g = tiny_graph
+    with context_for(gv, dim=32, num_neg=1, neg_weight=5.0, mode=gv.GV_MODE_HOGWILD, total_samples=10, seed=1,
+                     pool_capacity=8, lr0=LR0) as ctx:
+        buf = torch.empty((100, 2), dtype=torch.int32, device="cuda")
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_set_adjacency(ctx, g["offsets"], g["adj"])
+        assert e.value.code == gv.GV_ESTATE  # no graph yet
+        gv.gv_set_degrees(ctx, g["deg"])
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_augment_device(ctx, buf.data_ptr(), seed=1, count=100)
+        assert e.value.code == gv.GV_ESTATE  # no adjacency yet
+        wrong = g["offsets"].copy()
+        wrong[1:] += 1
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_set_adjacency(ctx, wrong, np.concatenate([g["adj"], g["adj"][:1]]))
+        assert e.value.code == gv.GV_EINVAL  # row lengths differ from the degrees
+        gv.gv_set_adjacency(ctx, g["offsets"], g["adj"])
+        for bad in (dict(walk_length=65), dict(walk_length=0), dict(window=0), dict(shuffle=2)):
+            with pytest.raises(gv.GvError) as e:
+                gv.gv_augment_device(ctx, buf.data_ptr(), seed=1, count=100, **bad)
+            assert e.value.code == gv.GV_EINVAL
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_augment_device(ctx, 0, seed=1, count=100)
+        assert e.value.code == gv.GV_EINVAL
+        assert gv.gv_augment_device(ctx, 0, seed=1, count=0) == 0  # nothing to do
+
+
 def read_long_run_reference():
     """tests/golden/long_run_c2.txt: the set-up and the oracle's checkpoints (written by the script beside it)."""
     setup, rows = {}, []
