@@ -1,12 +1,15 @@
-"""Writes tests/golden/long_run_c2.txt: the sequential CPU oracle's trajectory over a long
-training run on the configuration-2 graph (Sec. 4.2 hyper-parameters: d = 128, one negative
-of weight 5, walks of length 40 augmented with window 5, learning rate decaying linearly to
-zero), against which the GPU test compares the library's asynchronous training.
+"""Writes tests/golden/long_run_<name>.txt: the sequential CPU oracle's trajectory over a long
+training run (Sec. 4.3 hyper-parameters: d = 128, one negative of weight 5, walks of length 40
+augmented with window 5, learning rate decaying linearly to zero), against which the GPU tests
+compare the library's asynchronous training.
 
 Everything here is computed by ``oracle/`` from seeded synthetic inputs; the library under test
-is not involved.  Takes about 20 minutes on one core:
+is not involved.  One core; about 20 minutes for c2 (32 pools on the 10^6-node power-law graph),
+about an hour and a half for c4 (the full 4*10^9 samples of the planted-partition configuration;
+checkpoints are written as they are reached, and the test uses those that exist):
 
-    python tests/golden/make_long_run_reference.py
+    python tests/golden/make_long_run_reference.py c2
+    python tests/golden/make_long_run_reference.py c4
 """
 import os
 import sys
@@ -20,11 +23,16 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
 import oracle  # noqa: E402
 import workloads as W  # noqa: E402
 
-# the test reads these from the file, so the two cannot drift apart
-SETUP = dict(graph="c2", holdout=0.01, holdout_seed=51, pool=1 << 24, pools=32, dim=128, num_neg=1,
-             neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=500, eval_walk_seed=777,
-             eval_count=1 << 18, eval_seed=99, negative_pair_seed=52, walk_length=40, window=5)
-CHECKPOINTS = (1, 2, 4, 8, 16, 24, 32)
+# the tests read these from the files, so the two cannot drift apart
+SETUPS = {
+    "c2": dict(graph="c2", holdout=0.01, holdout_seed=51, pool=1 << 24, pools=32, dim=128, num_neg=1,
+               neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=500, eval_walk_seed=777,
+               eval_count=1 << 18, eval_seed=99, negative_pair_seed=52, walk_length=40, window=5),
+    "c4": dict(graph="c4", holdout=0.01, holdout_seed=61, pool=1 << 24, pools=238, dim=128, num_neg=1,
+               neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=600, eval_walk_seed=778,
+               eval_count=1 << 18, eval_seed=99, negative_pair_seed=62, walk_length=40, window=5),
+}
+CHECKPOINTS = {"c2": (1, 2, 4, 8, 16, 24, 32), "c4": (4, 16, 32, 64, 96, 128, 160, 192, 238)}
 
 
 def pool_of(offsets, adj, seed, first_walk, count, s):
@@ -33,7 +41,9 @@ def pool_of(offsets, adj, seed, first_walk, count, s):
 
 
 def main():
-    s = SETUP
+    name = sys.argv[1] if len(sys.argv) > 1 else "c2"
+    s = SETUPS[name]
+    out_path = os.path.join(HERE, f"long_run_{name}.txt")
     n, src, dst = W.make_graph(s["graph"])
     tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
     deg = W.degrees(n, tr_s, tr_d)
@@ -45,23 +55,26 @@ def main():
     na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     vertex, context = oracle.init_embeddings(s["init_seed"], n, s["dim"])
-    lines = ["# written by tests/golden/make_long_run_reference.py (CPU oracle only)"]
+    lines = [f"# written by tests/golden/make_long_run_reference.py {name} (CPU oracle only)"]
     lines += [f"# {k} = {v}" for k, v in s.items()]
     lines.append("# pools_trained eval_loss link_prediction_auc max_vertex_norm max_context_norm")
+    with open(out_path, "w") as f:
+        f.write("\n".join(lines) + "\n")
     for k in range(pools):
         t0 = time.time()
         pool = pool_of(offsets, adj, s["walk_seed"], k * walks_per_pool, P, s)
         oracle.train(vertex, context, pool, K=s["num_neg"], first_g=k * P, T=P * pools, lr0=s["lr0"],
                      lr_min_ratio=0.0, w=s["neg_weight"], seed=s["train_seed"], thresh=thresh, alias=alias)
-        if k + 1 in CHECKPOINTS:
+        print(f"pool {k + 1}/{pools}: {time.time() - t0:.0f} s", flush=True)
+        if k + 1 in CHECKPOINTS[name]:
             loss = oracle.loss(vertex, context, eval_pool, K=s["num_neg"], w=s["neg_weight"], seed=s["eval_seed"],
                                thresh=thresh, alias=alias)
             auc = oracle.link_prediction_auc(vertex, te_s, te_d, na, nb)
             lines.append(f"{k + 1} {loss:.6f} {auc:.6f} {np.linalg.norm(vertex, axis=1).max():.3f} "
                          f"{np.linalg.norm(context, axis=1).max():.3f}")
             print(lines[-1], f"({time.time() - t0:.0f} s for this pool)", flush=True)
-    with open(os.path.join(HERE, "long_run_c2.txt"), "w") as f:
-        f.write("\n".join(lines) + "\n")
+            with open(out_path, "a") as f:
+                f.write(lines[-1] + "\n")
 
 
 if __name__ == "__main__":

@@ -891,10 +891,10 @@ def test_device_producer_argument_errors(gv, tiny_graph):
         assert gv.gv_augment_device(ctx, 0, seed=1, count=0) == 0  # nothing to do
 
 
-def read_long_run_reference():
-    """tests/golden/long_run_c2.txt: the set-up and the oracle's checkpoints (written by the script beside it)."""
+def read_long_run_reference(name="c2"):
+    """tests/golden/long_run_<name>.txt: the set-up and the oracle's checkpoints (written by the script beside it)."""
     setup, rows = {}, []
-    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "long_run_c2.txt")) as f:
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"long_run_{name}.txt")) as f:
         for line in f:
             if line.startswith("#"):
                 if " = " in line:
@@ -955,3 +955,50 @@ def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, policy):
         print(f"long run {policy}: auc {auc:.4f} vs {checkpoints[pools][1]:.4f}")
         assert gv.gv_get_stats(ctx)["samples_trained"] == P * pools
         assert abs(auc - checkpoints[pools][1]) <= 0.01
+
+
+def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
+    """Configuration 4 as BASELINE states it: planted partition, 4*10^6 nodes in 400 communities, 4*10^7
+    edges, 1 % held out, d = 128, K = 1, 4*10^9 samples (238 pools of 2^24, learning rate decaying to zero);
+    pools written in HBM by the device producer, default asynchronous policy.  The oracle's trajectory is
+    stored (`tests/golden/long_run_c4.txt`, one CPU core for two hours); at each stored checkpoint the
+    evaluation loss must be within 2 % and the link-prediction AUC of the held-out edges within 0.005."""
+    import torch
+
+    s, reference = read_long_run_reference("c4")
+    assert reference, "no checkpoint stored"
+    n, src, dst = W.make_graph(s["graph"])
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    print(f"configuration 4: graph ready ({n} nodes, {tr_s.size} training edges)", flush=True)
+    P, pools, d = s["pool"], s["pools"], s["dim"]
+    walks_per_pool = -(-P // 190)
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
+    checkpoints = {k: rest for k, *rest in reference}
+    last = max(checkpoints)
+    with context_for(gv, dim=d, num_neg=s["num_neg"], neg_weight=s["neg_weight"], mode=gv.GV_MODE_HOGWILD,
+                     total_samples=P * pools, seed=s["train_seed"], pool_capacity=8, lr0=s["lr0"]) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_set_adjacency(ctx, offsets, adj)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, s["init_seed"])
+        eval_buf = torch.empty((s["eval_count"], 2), dtype=torch.int32, device="cuda")
+        gv.gv_augment_device(ctx, eval_buf.data_ptr(), seed=s["eval_walk_seed"], count=s["eval_count"])
+        gv.gv_sync(ctx)
+        eval_pool = eval_buf.cpu().numpy().view(np.uint32)
+        bufs = [torch.empty((P, 2), dtype=torch.int32, device="cuda") for _ in range(2)]
+        for k in range(last):
+            buf = bufs[k % 2]
+            gv.gv_augment_device(ctx, buf.data_ptr(), seed=s["walk_seed"], first_walk=k * walks_per_pool, count=P)
+            gv.gv_train_device_pool(ctx, buf.data_ptr(), P)
+            if k + 1 in checkpoints:
+                ref_loss, ref_auc, ref_nv, ref_nc = checkpoints[k + 1]
+                gv.gv_sync(ctx)
+                loss = gv.gv_eval_loss(ctx, eval_pool, s["eval_seed"])
+                auc = oracle.auc(gv.gv_cosine(ctx, te_s, te_d), gv.gv_cosine(ctx, na, nb))
+                print(f"configuration 4 after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
+                      f"auc {auc:.4f} vs {ref_auc:.4f}", flush=True)
+                assert abs(loss - ref_loss) <= 0.02 * ref_loss
+                assert abs(auc - ref_auc) <= 0.005
+        assert gv.gv_get_stats(ctx)["samples_trained"] == P * last
