@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "tiny", "c5-marginal"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "tiny", "c5-marginal"])
     ap.add_argument("--pools", type=int, default=8, help="distinct pre-generated pools cycled through")
     ap.add_argument("--coherence", type=int, default=int(os.environ.get("GV_BENCH_COHERENCE", "3")))
     ap.add_argument("--schedule", type=int, default=int(os.environ.get("GV_BENCH_SCHEDULE", "1")))
