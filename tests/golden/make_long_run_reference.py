@@ -4,11 +4,13 @@ augmented with window 5, learning rate decaying linearly to zero), against which
 compare the library's asynchronous training.
 
 Everything here is computed by ``oracle/`` from seeded synthetic inputs; the library under test
-is not involved.  One core; about 20 minutes for c2 (32 pools on the 10^6-node power-law graph),
+is not involved.  One core; about 20 minutes for c2 (32 pools on the 10^6-node power-law graph), 10 minutes for
+c3 (4 pools of the same graph with d = 512 and 5 negatives of weight 1),
 about an hour and a half for c4 (the full 4*10^9 samples of the planted-partition configuration;
 checkpoints are written as they are reached, and the test uses those that exist):
 
     python tests/golden/make_long_run_reference.py c2
+    python tests/golden/make_long_run_reference.py c3
     python tests/golden/make_long_run_reference.py c4
 """
 import os
@@ -28,11 +30,14 @@ SETUPS = {
     "c2": dict(graph="c2", holdout=0.01, holdout_seed=51, pool=1 << 24, pools=32, dim=128, num_neg=1,
                neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=500, eval_walk_seed=777,
                eval_count=1 << 18, eval_seed=99, negative_pair_seed=52, walk_length=40, window=5),
+    "c3": dict(graph="c3", holdout=0.01, holdout_seed=51, pool=1 << 24, pools=4, dim=512, num_neg=5,
+               neg_weight=1.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=500, eval_walk_seed=777,
+               eval_count=1 << 18, eval_seed=99, negative_pair_seed=52, walk_length=40, window=5),
     "c4": dict(graph="c4", holdout=0.01, holdout_seed=61, pool=1 << 24, pools=238, dim=128, num_neg=1,
                neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=600, eval_walk_seed=778,
                eval_count=1 << 18, eval_seed=99, negative_pair_seed=62, walk_length=40, window=5),
 }
-CHECKPOINTS = {"c2": (1, 2, 4, 8, 16, 24, 32), "c4": (4, 16, 32, 64, 96, 128, 160, 192, 238)}
+CHECKPOINTS = {"c2": (1, 2, 4, 8, 16, 24, 32), "c3": (1, 2, 3, 4), "c4": (4, 16, 32, 64, 96, 128, 160, 192, 238)}
 
 
 def pool_of(offsets, adj, seed, first_walk, count, s):

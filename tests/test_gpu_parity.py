@@ -906,17 +906,18 @@ def read_long_run_reference(name="c2"):
     return setup, rows
 
 
-@pytest.mark.parametrize("policy", [(TILED, MIXED), (POOL_ORDER, ATOMIC)])
-def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, policy):
-    """32 pools of 2^24 samples (5.4*10^8 samples, learning rate decaying to zero) on the configuration-2
-    graph with 1 % of its edges held out, pools produced on the fly by the library's host producer
-    into the pinned slots.  At every checkpoint of the stored oracle trajectory the evaluation loss must
-    be within 2 % of the oracle's and no row may have grown beyond twice the oracle's longest row
-    (asynchronous updates that overshoot show up as a few very long rows well before the loss moves);
-    at the end the link-prediction AUC must match too.  This graph has no structure beyond its degrees,
-    so its AUC measures nothing but how far training has got and drops steeply over the run: it is held
-    to 0.01, the planted-partition test above holds the AUC of a graph that has structure to 0.005."""
-    s, reference = read_long_run_reference()
+@pytest.mark.parametrize("name,policy", [("c2", (TILED, MIXED)), ("c2", (POOL_ORDER, ATOMIC)), ("c3", (TILED, MIXED))])
+def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, name, policy):
+    """c2: 32 pools of 2^24 samples (5.4*10^8 samples, learning rate decaying to zero) on the configuration-2
+    graph with 1 % of its edges held out; c3: 4 such pools with d = 512 and 5 negatives of weight 1 (the oracle
+    needs two minutes per pool there).  Pools are produced on the fly by the library's host producer into the
+    pinned slots.  At every checkpoint of the stored oracle trajectory the evaluation loss must be within 2 %
+    of the oracle's and no row may have grown beyond twice the oracle's longest row (asynchronous updates
+    that overshoot show up as a few very long rows well before the loss moves); at the end the
+    link-prediction AUC must match too.  This graph has no structure beyond its degrees, so its AUC measures
+    nothing but how far training has got and drops steeply over the run: it is held to 0.01, the
+    planted-partition test above holds the AUC of a graph that has structure to 0.005."""
+    s, reference = read_long_run_reference(name)
     n, src, dst = W.make_graph(s["graph"])
     tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
     deg = W.degrees(n, tr_s, tr_d)
@@ -947,12 +948,12 @@ def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, policy):
                 loss = gv.gv_eval_loss(ctx, eval_pool, s["eval_seed"])
                 nv = np.linalg.norm(gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d), axis=1).max()
                 nc = np.linalg.norm(gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d), axis=1).max()
-                print(f"long run {policy} after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
+                print(f"long run {name} {policy} after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
                       f"longest rows {nv:.2f}/{nc:.2f} vs {ref_nv:.2f}/{ref_nc:.2f}")
                 assert abs(loss - ref_loss) <= 0.02 * ref_loss
                 assert nv <= 2.0 * ref_nv and nc <= 2.0 * ref_nc
         auc = oracle.auc(gv.gv_cosine(ctx, te_s, te_d), gv.gv_cosine(ctx, na, nb))
-        print(f"long run {policy}: auc {auc:.4f} vs {checkpoints[pools][1]:.4f}")
+        print(f"long run {name} {policy}: auc {auc:.4f} vs {checkpoints[pools][1]:.4f}")
         assert gv.gv_get_stats(ctx)["samples_trained"] == P * pools
         assert abs(auc - checkpoints[pools][1]) <= 0.01
 
