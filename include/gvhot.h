@@ -172,8 +172,9 @@ int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_ad
  * gv_set_adjacency uploads the CSR adjacency of the graph given to gv_set_graph /
  * gv_set_degrees: host_offsets[n + 1] (offsets[0] = 0, row i has degree(i) entries),
  * host_adj[offsets[n]] with both directions of every edge; both are copied, the caller keeps
- * its arrays.  Errors: GV_ESTATE without a graph, GV_EINVAL when a row length differs from
- * the node's degree, an entry is >= n or the graph has no edge.
+ * its arrays; a later gv_set_graph / gv_set_degrees discards the copy.  Errors: GV_ESTATE
+ * without a graph, GV_EINVAL when a row length differs from the node's degree, an entry is
+ * >= n or the graph has no edge.
  * gv_augment_device writes the pool that gv_augment would write for the same arguments
  * (bit-identical: same walks, same random numbers, same order) into dev_pairs[count][2] in
  * DEVICE memory, asynchronously on the context's compute stream, i.e. ordered with

@@ -155,7 +155,7 @@ void free_matrices(gv_ctx *ctx) {
     ctx->alias_ready = false;
 }
 
-// Logarithmic degree class in 7 bits: min(127, floor(4 log2(1 + degree))).
+// Takes over the degrees of a new graph: allocates the matrices (cleared) and the per-node tables.
 int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     int rc = sync_all(ctx);
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
