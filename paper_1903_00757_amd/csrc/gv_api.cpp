@@ -48,6 +48,7 @@ struct gv_ctx {
     uint4 *alias = nullptr;
     bool alias_ready = false;
     uint16_t *dev_rank = nullptr;         // device, per node: hot rank (see gv::TrainArgs)
+    uint32_t *dev_ranked = nullptr;       // device, bitmap of the nodes that have a hot rank
     uint32_t warm_ranks = 0;              // number of warm rows
     uint64_t *dev_offsets = nullptr;      // device CSR of the graph (gv_set_adjacency), for the device producer
     uint32_t *dev_adj = nullptr;
@@ -55,6 +56,8 @@ struct gv_ctx {
     uint32_t *error_flag = nullptr;       // device
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
+    uint32_t *records = nullptr;          // device scratch of the tiled kernel: K + 3 words per sample of a launch
+    uint64_t records_capacity = 0;        // in uint32 elements
     hipStream_t compute = nullptr;
     hipStream_t copy = nullptr;
     PoolSlot slot[2];
@@ -144,6 +147,8 @@ void free_matrices(gv_ctx *ctx) {
     if (ctx->context) (void)hipFree(ctx->context);
     if (ctx->alias) (void)hipFree(ctx->alias);
     if (ctx->dev_rank) (void)hipFree(ctx->dev_rank);
+    if (ctx->dev_ranked) (void)hipFree(ctx->dev_ranked);
+    ctx->dev_ranked = nullptr;
     if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
     if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
     ctx->dev_offsets = nullptr;
@@ -166,6 +171,7 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     GV_HIP(ctx, hipMalloc((void **)&ctx->context, bytes));
     GV_HIP(ctx, hipMalloc((void **)&ctx->alias, (size_t)n * sizeof(uint4)));
     GV_HIP(ctx, hipMalloc((void **)&ctx->dev_rank, (size_t)n * sizeof(uint16_t)));  // filled by gv_build_alias
+    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_ranked, ((size_t)n + 31) / 32 * sizeof(uint32_t)));
     GV_HIP(ctx, hipMemsetAsync(ctx->vertex, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
@@ -202,6 +208,19 @@ int ensure_negatives(gv_ctx *ctx, uint64_t elements) {
     return GV_OK;
 }
 
+int ensure_records(gv_ctx *ctx, uint64_t elements) {
+    if (elements <= ctx->records_capacity) return GV_OK;
+    if (ctx->records) {
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+        (void)hipFree(ctx->records);
+        ctx->records = nullptr;
+        ctx->records_capacity = 0;
+    }
+    GV_HIP(ctx, hipMalloc((void **)&ctx->records, elements * sizeof(uint32_t)));
+    ctx->records_capacity = elements;
+    return GV_OK;
+}
+
 gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_g, uint32_t count) {
     gv::TrainArgs a{};
     a.vertex = ctx->vertex;
@@ -210,6 +229,7 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.pairs = dev_pairs;
     a.negatives = nullptr;
     a.rank = ctx->dev_rank;
+    a.ranked = ctx->n > 20u * 0xFFFFu ? ctx->dev_ranked : nullptr;  // under 5 % of the nodes ranked
     a.warm_ranks = ctx->warm_ranks;
     a.error_flag = ctx->error_flag;
     a.first_g = first_g;
@@ -254,9 +274,12 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u)
+    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u) {
+        int rc = ensure_records(ctx, count * (ctx->cfg.num_neg + 3));
+        if (rc) return rc;
+        a.records = ctx->records;
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
-    else
+    } else
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
     ctx->stats.train_launches += 1;
     if (timed) return end_span(ctx, ctx->compute, span);
@@ -442,6 +465,7 @@ void gv_destroy(gv_ctx *ctx) {
     }
     free_matrices(ctx);
     if (ctx->negatives) (void)hipFree(ctx->negatives);
+    if (ctx->records) (void)hipFree(ctx->records);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
     if (ctx->compute) (void)hipStreamDestroy(ctx->compute);
@@ -522,10 +546,12 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     };
     std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
     std::vector<uint16_t> rank(n, (uint16_t)kRanked);
+    std::vector<uint32_t> ranked_bits(((size_t)n + 31) / 32, 0u);
     uint32_t warm_ranks = 0;
     for (uint32_t r = 0; r < ranked; ++r) {
         const uint32_t i = order[r];
         rank[i] = (uint16_t)r;
+        ranked_bits[i >> 5] |= 1u << (i & 31u);
         const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
         if (share * kInFlight > warm_threshold) warm_ranks = r + 1;
     }
@@ -561,6 +587,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
     if (rc != GV_OK && rc != GV_EINVAL) return rc;
     GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
     GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
+    GV_HIP(ctx, hipMemcpy(ctx->dev_ranked, ranked_bits.data(), ranked_bits.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     ctx->warm_ranks = warm_ranks;
     ctx->alias_ready = true;
     return GV_OK;

@@ -16,8 +16,13 @@ struct TrainArgs {
     const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
     const uint16_t *rank;     // per node: its place among the nodes by falling degree (ties by id), 0xFFFF
                               // from place 65535 on ("hot rank")
+    const uint32_t *ranked;   // bit i set: node i has a hot rank below 0xFFFF (small enough to stay in cache,
+                              // so the rank table is only read for the few nodes that are in it); null when
+                              // so many nodes are ranked that the detour does not pay
     uint32_t warm_ranks;      // rows of hot rank below this are warm: their updates must not be lost
                               // (see gv_build_alias)
+    uint32_t *records;        // tiled schedule: scratch of count x (K + 3) words, written and read by the launch
+                              // (u, v, the K negatives, warm flags of the negatives)
     uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
     uint64_t first_g;         // global position of pairs[0]
     uint64_t total;           // T of the learning-rate schedule

@@ -416,6 +416,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     // the sample's slot in the tile (13 bits) and the warm flags of u and v (2 bits).
     constexpr uint32_t kSkip = 0xFFFFFFFFu;  // word of a slot without a trainable sample (row number 7 is never used)
     constexpr uint32_t kSlotBits = 13, kGroupedRanks = 4096;
+    constexpr uint32_t kRecord = kK + 3;  // words of a sample's record: u, v, K negatives, warm flags of the negatives
     static_assert(kTile <= (1 << kSlotBits) && kTile >= 2 * kBlock, "tile size");
     static_assert(kK + 1 < 7, "row numbers take three bits and 7 is reserved");
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
@@ -441,22 +442,39 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             if (tile_base + t < a.count) {
                 const uint2 p = pairs[tile_base + t];
                 if (p.x < a.n && p.y < a.n) {
-                    const uint32_t ru = a.rank[p.x], rv = a.rank[p.y];
+                    // most nodes of a large graph have no hot rank: there a cache-resident bitmap says
+                    // which do, and the rank table is read for those only
+                    uint32_t ru, rv;
+                    if (a.ranked) {
+                        ru = (a.ranked[p.x >> 5] >> (p.x & 31u)) & 1u ? a.rank[p.x] : 0xFFFFu;
+                        rv = (a.ranked[p.y >> 5] >> (p.y & 31u)) & 1u ? a.rank[p.y] : 0xFFFFu;
+                    } else {
+                        ru = a.rank[p.x];
+                        rv = a.rank[p.y];
+                    }
                     uint32_t best = ru, held = 0u, row = p.x;
                     if (rv < best) {
                         best = rv;
                         held = 1u;
                         row = p.y;
                     }
+                    // the walk below takes the sample from this record instead of drawing it again
+                    uint32_t *record = a.records + (size_t)(tile_base + t) * kRecord;
+                    uint32_t warm_negatives = 0;
+                    record[0] = p.x;
+                    record[1] = p.y;
 #pragma unroll
                     for (int k = 0; k < kK; ++k) {
                         const Drawn nk = draw_ranked_negative(a.alias, a.n, a.seed, a.first_g + tile_base + t, k);
+                        record[2 + k] = nk.id;
+                        warm_negatives |= (nk.rank < a.warm_ranks ? 1u : 0u) << k;
                         if (nk.rank < best) {
                             best = nk.rank;
                             held = 2u + k;
                             row = nk.id;
                         }
                     }
+                    record[2 + kK] = warm_negatives;
                     const uint32_t group = (held == 0u ? 0u : 1u << 13) |
                                            (best < kGroupedRanks ? __brev(best) >> 20 : kGroupedRanks | (row * 0x9E3779B1u) >> 20);
                     const uint32_t warm_uv = (ru < a.warm_ranks ? 1u : 0u) | (rv < a.warm_ranks ? 2u : 0u);
@@ -491,16 +509,14 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             const uint32_t word = s_word[base + lane];
             const bool mine = word != kSkip;
             const uint32_t pos = tile_base + ((word >> 2) & ((1u << kSlotBits) - 1u));
-            const uint2 p = mine ? pairs[pos] : make_uint2(0u, 0u);
+            const uint32_t *record = a.records + (size_t)pos * kRecord;
+            const uint2 p = mine ? make_uint2(record[0], record[1]) : make_uint2(0u, 0u);
             const uint64_t g = a.first_g + pos;
             uint32_t neg[kK];
-            uint32_t warm = word & 3u;  // bit j: row j of the sample is warm
 #pragma unroll
-            for (int k = 0; k < kK; ++k) {
-                const Drawn nk = draw_ranked_negative(a.alias, a.n, a.seed, g, k);
-                neg[k] = nk.id;
-                warm |= (nk.rank < a.warm_ranks ? 1u : 0u) << (2 + k);
-            }
+            for (int k = 0; k < kK; ++k) neg[k] = mine ? record[2 + k] : 0u;
+            // bit j: row j of the sample is warm (u and v from the sort word, the negatives from the record)
+            const uint32_t warm = (word & 3u) | (mine ? record[2 + kK] << 2 : 0u);
             const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
             // sorted order puts the skipped slots last: the first one ends this wave's work
             const uint64_t live = __ballot(mine);
@@ -906,7 +922,7 @@ hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blo
 template <int kV, int kK>
 hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
-    if (a.rank == nullptr) return hipErrorInvalidValue;
+    if (a.rank == nullptr || a.records == nullptr) return hipErrorInvalidValue;
     constexpr uint32_t tile = 8192;  // samples per workgroup (2048 and 4096 were 10 % and 5 % slower on the power-law graph)
     // One workgroup per tile, started by the hardware in tile order as earlier ones end, unless the
     // graph is so small that fewer samples must be in flight: then a fixed number of workgroups
