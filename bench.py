@@ -24,7 +24,7 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters
 # read for a 1 GiB device copy (profiles/k_train_tiled_*.md); only for the profiled setups.
-PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 52.00e9, ("c3", 1, 3): 471.9e9}
+PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 50.45e9, ("c3", 1, 3): 463.4e9, ("c4", 1, 3): 56.11e9}
 
 
 def log(*a):
