@@ -142,7 +142,10 @@ int gv_acquire_pool_slot(gv_ctx *ctx, uint32_t **host_pairs);
 int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count);
 /* Train the oldest queued pool: positive samples g .. g+count-1 where g is the
  * number of samples trained so far.  Returns after launching (asynchronous);
- * GV_ESTATE if nothing is queued.                                              */
+ * GV_ESTATE if nothing is queued.  The training calls keep device scratch sized
+ * for the largest pool seen so far (a few words per sample): the first call, and
+ * a call with a larger pool than any before, allocate (GV_ENOMEM / GV_EHIP if
+ * that fails) and wait for the launches in flight.                              */
 int gv_train_pool(gv_ctx *ctx);
 /* Train a pool that already lies in device memory (dev_pairs must stay valid
  * and unchanged until gv_sync).  Ids are checked as for pushed pools.
