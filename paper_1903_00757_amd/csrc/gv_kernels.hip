@@ -368,12 +368,14 @@ __device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, 
 // and keeps the hot row in registers for as long as consecutive samples name it: the row is
 // read once per run, the run's updates are applied to the register copy in order, and the
 // run's change is added to memory with fp32 atomic adds (nothing another wave adds meanwhile
-// is lost).  The other rows of a sample are fetched and updated per sample with the given
+// is lost): every four samples, taking in what memory holds by then, and at the end of the
+// run.  The other rows of a sample are fetched and updated per sample with the given
 // policy.  Accesses to one row are served one after the other by the memory system, so a
 // row that a percent of all samples name -- as an endpoint or, drawn in proportion to
 // degree^0.75, as a negative -- would otherwise set the pace of the whole launch.
-// Tiles are dealt round-robin to workgroups, so the launch still moves through the pool
-// front to back and a row's samples stay spread over time.  Every sample keeps the
+// Tiles are taken in pool order (one workgroup per tile, started as earlier ones end, or a
+// fixed number of workgroups striding over the tiles), so the launch still moves through
+// the pool front to back and a row's samples stay spread over time.  Every sample keeps the
 // negatives and the learning rate of its position in the pool.
 template <int kTile>
 __device__ __forceinline__ void sort_tile(uint32_t *word) {
