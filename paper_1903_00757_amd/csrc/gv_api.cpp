@@ -267,6 +267,11 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
 // Asynchronous training of `count` samples at dev_pairs: one launch of the tiled
 // stationary-row kernel, or of the plain pool-order kernel.
 int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
+    const bool tiled = ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u;
+    if (tiled) {  // before the timed span: an allocation must not count as kernel time
+        int rc = ensure_records(ctx, count * (ctx->cfg.num_neg + 3));
+        if (rc) return rc;
+    }
     TimedSpan span{};
     const bool timed = ctx->cfg.profile != 0;
     if (timed) {
@@ -274,13 +279,12 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
-    if (ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u) {
-        int rc = ensure_records(ctx, count * (ctx->cfg.num_neg + 3));
-        if (rc) return rc;
+    if (tiled) {
         a.records = ctx->records;
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
-    } else
+    } else {
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+    }
     ctx->stats.train_launches += 1;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
