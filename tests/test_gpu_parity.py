@@ -301,6 +301,34 @@ def test_hogwild_rows_touched_once_equal_one_oracle_step(gv, policy, d, K):
     assert not np.array_equal(got_v[cu > 0], vertex[cu > 0])
 
 
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (TILED, ATOMIC)])
+def test_tiled_pools_of_changing_size(gv, policy):
+    """Pools of 300, 9000, 64 and 20001 samples in a row (the per-sample scratch of the tiled schedule grows
+    with the largest pool seen and is reused by the smaller ones): samples whose rows nobody else names in
+    any of the pools equal one oracle step at their global position."""
+    n, d, K, w, seed = 200_000, 128, 2, 2.5, 23
+    sizes = [300, 9000, 64, 20_001]
+    count = sum(sizes)
+    rng = np.random.default_rng(17)
+    deg = rng.integers(1, 50, size=n).astype(np.uint32)
+    pool = rng.integers(n, size=(count, 2)).astype(np.uint32)
+    cuts = np.cumsum([0] + sizes)
+    pools = [pool[a:b] for a, b in zip(cuts, cuts[1:])]
+    vertex, context = random_embeddings(n, d, seed=5)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, pools, vertex, context, 10 * count, seed, policy)
+    idx, cu, cc = singly_touched(pool, negs, n)
+    assert idx.size > 0.15 * count
+    picked = np.concatenate([idx[idx < cuts[1]], idx[(idx >= cuts[2]) & (idx < cuts[3])], idx[idx >= cuts[3]][:800],
+                             idx[(idx >= cuts[1]) & (idx < cuts[2])][:800]])
+    worst = check_single_steps(pool, negs, picked, 0, 10 * count, K, w, seed, vertex, context, got_v, got_c,
+                               thresh, alias)
+    assert worst <= 1e-5, worst
+    assert np.array_equal(got_v[cu == 0], vertex[cu == 0])
+    assert np.array_equal(got_c[cc == 0], context[cc == 0])
+
+
 @pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, ATOMIC), (TILED, MIXED)])
 def test_tiled_run_on_one_hub_row_is_sequential(gv, policy):
     """60 samples that all name one high-degree node u: the tiled schedule keeps vertex[u] in registers
