@@ -2,17 +2,24 @@
 """Benchmark of the training hot path on one MI355X.
 
 A step = one pool of 2^24 positive samples of configuration 2 (Chung-Lu graph,
-10^6 nodes / 5*10^6 edges, d = 128, K = 1) through the whole path: sample read,
-negative draw, row gathers, dot products, sigmoid-gradient, in-place updates.
-Pools are resident in HBM before the timed region; the streamed (PCIe-inclusive)
-rate is measured separately and reported beside it.  Prints ONE JSON line.
+10^6 nodes / 5*10^6 edges, d = 128, K = 1) through the whole path: pool copy
+host -> device from a pinned slot, sample read, negative draw, row gathers, dot
+products, sigmoid-gradient, in-place updates.  Eight pools are produced once
+(the library's own producer: walks of length 40, pairs within distance 5,
+pseudo shuffle) into the context's ring of pinned slots and then cycled with no
+host work in the loop; the copy of a pool overlaps the training of the pools
+before it.  The same steps are also timed with the pools already resident in
+HBM.  Every leg is timed three times (median and min are printed).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -22,9 +29,13 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters
-# read for a 1 GiB device copy (profiles/k_train_tiled_*.md); only for the profiled setups.
-PROFILED_TRAFFIC_BYTES = {("c2", 1, 3): 50.45e9, ("c3", 1, 3): 463.4e9, ("c4", 1, 3): 56.11e9}
+REPETITIONS = 3
+RING = 8
+# HBM bytes per launch measured with rocprofv3 counters in separate runs: the figures and the commands that
+# produced them are kept in this file (workload, schedule, coherence, bytes per launch, source summary)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+SCHEDULES = ["pool-order", "tiled", "auto"]
+COHERENCES = ["plain", "agent", "atomic-agent", "mixed"]
 
 
 def log(*a):
@@ -37,20 +48,92 @@ def algorithmic_bytes_per_sample(dim: int, num_neg: int) -> int:
     return 2 * (2 + num_neg) * 4 * dim + 8 + 8 * num_neg
 
 
-def cpu_baseline(n, deg, pool, dim, num_neg, w, total, seed, budget_samples):
-    """The sequential oracle, as it stands, on a bounded slice of the same workload."""
+def profiled_traffic(workload: str, schedule: str, coherence: str):
+    """(bytes per launch, name of the profile summary) from the tracked table, or (None, None)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                cols = line.split()
+                if len(cols) >= 5 and not line.startswith("#") and cols[:3] == [workload, schedule, coherence]:
+                    return float(cols[3]), cols[4]
+    except OSError:
+        pass
+    return None, None
+
+
+def cpu_baseline(offsets, adj, deg, cfg, seed, samples_one_core, samples_per_thread):
+    """The sequential oracle, as it stands, on a bounded slice of the same workload: once on one core, and
+    once as the same plain loop run lock-free on all host cores (every thread trains its own slice of the pool
+    on the shared matrices, as asynchronous SGD on a CPU does)."""
     import oracle
 
+    import workloads as W
+
+    n, dim, K, w, total = deg.size, cfg["dim"], cfg["num_neg"], cfg["neg_weight"], cfg["total_samples"]
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     vertex, context = oracle.init_embeddings(1, n, dim)
-    part = pool[:budget_samples]
+    cores = max(1, min(os.cpu_count() or 1, 16))
+    need = max(samples_one_core, samples_per_thread * cores)
+    if adj is not None:
+        pool, _ = oracle.augment(100 * cfg["number"], offsets, adj, W.configs.WALK_LENGTH, W.configs.WINDOW, need)
+        pool = oracle.pseudo_shuffle(pool, W.configs.WINDOW)
+        what = "walk pool of the same graph (the oracle's own augmentation and pseudo shuffle)"
+    else:
+        pool = W.marginal_pool(deg, need, seed=100 * cfg["number"])
+        what = "pool with endpoints from the degree marginal"
+    kw = dict(K=K, T=total, lr0=0.025, lr_min_ratio=0.0, w=w, seed=seed, thresh=thresh, alias=alias)
+    part = pool[:samples_one_core]
     t0 = time.perf_counter()
-    oracle.train(vertex, context, part, K=num_neg, first_g=0, T=total, lr0=0.025, lr_min_ratio=0.0, w=w,
-                 seed=seed, thresh=thresh, alias=alias)
+    oracle.train(vertex, context, part, first_g=0, **kw)
     dt = time.perf_counter() - t0
-    return {"value": part.shape[0] / dt, "unit": "positive samples/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {part.shape[0]} samples of one {pool.shape[0]}-sample pool of the same workload, "
-                      f"sequential C oracle (fp64 arithmetic), {dt:.1f} s"}
+    out = {"value": part.shape[0] / dt, "unit": "positive samples/s", "cores": 1, "kind": "oracle",
+           "sample": f"first {part.shape[0]} samples of a {what}, sequential C oracle (fp64 arithmetic), {dt:.1f} s"}
+
+    def work(t):
+        lo = t * samples_per_thread
+        oracle.train(vertex, context, pool[lo:lo + samples_per_thread], first_g=lo, **kw)
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(cores)]
+    t0 = time.perf_counter()
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    dt = time.perf_counter() - t0
+    out["all_cores"] = {"value": cores * samples_per_thread / dt, "unit": "positive samples/s", "cores": cores,
+                        "kind": "oracle", "sample": f"{cores} threads x {samples_per_thread} samples of the same pool, the "
+                        f"same loop run lock-free on shared matrices, {dt:.1f} s"}
+    return out
+
+
+def timed_legs(gv, ctx, run_steps, steps):
+    """REPETITIONS x `steps` steps, each repetition bracketed by a full synchronisation; per repetition the wall
+    time and the event-timed mean duration of its training launches."""
+    import torch
+
+    reps = []
+    for _ in range(REPETITIONS):
+        gv.gv_sync(ctx)
+        torch.cuda.synchronize()
+        before = gv.gv_get_stats(ctx)
+        t0 = time.perf_counter()
+        run_steps(steps)
+        gv.gv_sync(ctx)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        after = gv.gv_get_stats(ctx)
+        launches = max(after["timed_launches"] - before["timed_launches"], 1)
+        reps.append({"wall_s": wall, "kernel_ms": (after["train_kernel_ms"] - before["train_kernel_ms"]) / launches,
+                     "h2d_ms": after["h2d_ms"] - before["h2d_ms"], "h2d_bytes": after["h2d_bytes"] - before["h2d_bytes"]})
+    return reps
+
+
+def summarise(reps, steps, P):
+    walls = sorted(r["wall_s"] for r in reps)
+    median = next(r for r in reps if r["wall_s"] == walls[len(walls) // 2])
+    return median, {"samples_per_s_median": steps * P / median["wall_s"], "samples_per_s_best": steps * P / walls[0],
+                    "ms_per_step": [r["wall_s"] / steps * 1e3 for r in reps],
+                    "kernel_ms": [r["kernel_ms"] for r in reps]}
 
 
 def main():
@@ -59,11 +142,10 @@ def main():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "tiny", "c5-marginal"])
-    ap.add_argument("--pools", type=int, default=8, help="distinct pre-generated pools cycled through")
-    ap.add_argument("--coherence", type=int, default=int(os.environ.get("GV_BENCH_COHERENCE", "3")))
-    ap.add_argument("--schedule", type=int, default=int(os.environ.get("GV_BENCH_SCHEDULE", "1")))
+    ap.add_argument("--coherence", type=int, default=3, help="GV_COHERENCE_* of the asynchronous launches")
+    ap.add_argument("--schedule", type=int, default=2, help="GV_SCHEDULE_* of the asynchronous launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-streamed", action="store_true")
+    ap.add_argument("--no-online", action="store_true", help="skip the legs with pools produced on the fly")
     ap.add_argument("--cpu-samples", type=int, default=1 << 24)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
@@ -83,6 +165,9 @@ def main():
     dim, K, w = cfg["dim"], cfg["num_neg"], cfg["neg_weight"]
     P = cfg["pool"]
     total = cfg["total_samples"]
+    L, s = W.configs.WALK_LENGTH, W.configs.WINDOW
+    walks_per_pool = -(-P // sum(L + 1 - delta for delta in range(1, s + 1)))
+    threads = min(16, os.cpu_count() or 1)
 
     t0 = time.perf_counter()
     if cfg["graph"] == "expected_degrees":
@@ -90,116 +175,102 @@ def main():
         n, deg = W.expected_degrees(args.workload)
         offsets = adj = None
         edges = cfg["edges"]
-        args.no_streamed = True
+        args.no_online = True
         log(f"degrees {args.workload}: n={n} ({time.perf_counter() - t0:.1f} s)")
-        t0 = time.perf_counter()
-        pools = []
-        for r in range(args.pools):  # one progress line per pool: these take a while at 6.6*10^7 nodes
-            pools.append(W.marginal_pool(deg, P, seed=100 * cfg["number"] + r))
-            log(f"pool {r + 1}/{args.pools} ({time.perf_counter() - t0:.1f} s)")
     else:
         n, src, dst = W.make_graph(args.workload)
         deg = W.degrees(n, src, dst)
         offsets, adj = W.csr_from_edges(n, src, dst)
         edges = src.size
         log(f"graph {args.workload}: n={n} edges={edges} ({time.perf_counter() - t0:.1f} s)")
-        t0 = time.perf_counter()
-        pools = [W.walk_pool(offsets, adj, P, W.configs.WALK_LENGTH, W.configs.WINDOW, seed=100 * cfg["number"] + r)
-                 for r in range(args.pools)]
-    log(f"{args.pools} pools of {P} samples ({time.perf_counter() - t0:.1f} s)")
-    dev_pools = [torch.from_numpy(p.view(np.int32)).cuda() for p in pools]
-    torch.cuda.synchronize()
 
     ctx = gv.gv_create(dim=dim, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=total,
                        seed=W.configs.TRAIN_SEED, pool_capacity=P, coherence=args.coherence, schedule=args.schedule,
-                       profile=1)
+                       profile=1, pool_slots=RING)
+    online = {}
     try:
         gv.gv_set_degrees(ctx, deg)
         gv.gv_build_alias(ctx, 0.75)
         gv.gv_init_embeddings(ctx, 1)
 
-        def step(i):
-            t = dev_pools[i % len(dev_pools)]
-            gv.gv_train_device_pool(ctx, t.data_ptr(), P)
-
-        for i in range(args.warmup):
-            step(i)
-        gv.gv_sync(ctx)
-        before = gv.gv_get_stats(ctx)
-        torch.cuda.synchronize()
+        # Fill the ring once: RING distinct pools, written by the producer straight into the pinned slots.
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            step(args.warmup + i)
+        dev_pools = []
+        for r in range(RING):
+            slot = gv.gv_acquire_pool_slot(ctx, P)
+            if adj is None:
+                np.copyto(slot, W.marginal_pool(deg, P, seed=100 * cfg["number"] + r))
+            else:
+                gv.gv_augment(offsets, adj, seed=100 * cfg["number"], first_walk=r * walks_per_pool, count=P,
+                              threads=threads, out=slot)
+            dev_pools.append(torch.from_numpy(slot.view(np.int32)).cuda())
+            gv.gv_push_pool(ctx, slot, P)
+            gv.gv_train_pool(ctx)  # the first RING steps double as warm-up of the streamed path
+            log(f"pool {r + 1}/{RING} ({time.perf_counter() - t0:.1f} s)")
         gv.gv_sync(ctx)
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        after = gv.gv_get_stats(ctx)
-        launches = after["timed_launches"] - before["timed_launches"]
-        kernel_ms = (after["train_kernel_ms"] - before["train_kernel_ms"]) / max(launches, 1)
-        value = args.steps * P / wall
-        bytes_per_sample = algorithmic_bytes_per_sample(dim, K)
-        achieved = bytes_per_sample * P / (kernel_ms * 1e-3) / 1e9
-        log(f"resident: {value:.4g} samples/s, train kernel {kernel_ms:.3f} ms/launch, {achieved:.0f} GB/s algorithmic")
 
-        streamed = None
-        if not args.no_streamed:
-            # PCIe-inclusive path: the producer fills the library's pinned slot in place,
-            # the copy of pool k+1 overlaps training of pool k.
-            steps = max(4, args.steps // 2)
-            slot = gv.gv_acquire_pool_slot(ctx, P)
-            np.copyto(slot, pools[0])
-            gv.gv_push_pool(ctx, slot, P)
+        def streamed_steps(count):
+            for _ in range(count):
+                slot = gv.gv_acquire_pool_slot(ctx, P)  # next slot of the ring, still holding its pool
+                gv.gv_push_pool(ctx, slot, P)           # copy host -> device on the copy stream
+                gv.gv_train_pool(ctx)                   # launch; waits on the device for that copy only
+
+        position = [0]
+
+        def resident_steps(count):
+            for _ in range(count):
+                gv.gv_train_device_pool(ctx, dev_pools[position[0] % RING].data_ptr(), P)
+                position[0] += 1
+
+        streamed_steps(args.warmup)
+        streamed_reps = timed_legs(gv, ctx, streamed_steps, args.steps)
+        resident_steps(args.warmup)
+        resident_reps = timed_legs(gv, ctx, resident_steps, args.steps)
+        s_med, s_sum = summarise(streamed_reps, args.steps, P)
+        r_med, r_sum = summarise(resident_reps, args.steps, P)
+        h2d_GBps = s_med["h2d_bytes"] / max(s_med["h2d_ms"], 1e-9) / 1e6
+        s_sum.update({"h2d_GBps": h2d_GBps, "ring": RING, "exposed_copy_ms_per_step":
+                      s_med["wall_s"] / args.steps * 1e3 - s_med["kernel_ms"]})
+        stats = gv.gv_get_stats(ctx)
+        tiled = stats["tiled_launches"] > 0
+        gap = 1.0 - s_sum["samples_per_s_median"] / r_sum["samples_per_s_median"]
+        streamed_is_headline = gap <= 0.02
+        head, head_sum = (s_med, s_sum) if streamed_is_headline else (r_med, r_sum)
+        log(f"streamed: {s_sum['samples_per_s_median']:.4g} samples/s (kernel {s_med['kernel_ms']:.3f} ms/launch, "
+            f"H2D {h2d_GBps:.1f} GB/s); resident: {r_sum['samples_per_s_median']:.4g} samples/s "
+            f"(kernel {r_med['kernel_ms']:.3f} ms/launch); gap {gap * 100:.2f} %")
+
+        if not args.no_online:
+            # Online pipeline (Sec. 3.3): the host producer (parallel online augmentation with pseudo shuffle,
+            # Sec. 3.1) fills one pinned slot while the GPU trains the others.
+            steps = max(3, args.steps // 8)
+            first = RING * walks_per_pool
             gv.gv_sync(ctx)
-            s0 = gv.gv_get_stats(ctx)
             t0 = time.perf_counter()
-            for i in range(steps):
-                gv.gv_train_pool(ctx)
-                if i + 1 < steps:
-                    slot = gv.gv_acquire_pool_slot(ctx, P)
-                    np.copyto(slot, pools[(i + 1) % len(pools)])
-                    gv.gv_push_pool(ctx, slot, P)
-            gv.gv_sync(ctx)
-            wall_s = time.perf_counter() - t0
-            s1 = gv.gv_get_stats(ctx)
-            streamed = {"value": steps * P / wall_s, "unit": "positive samples/s", "steps": steps,
-                        "h2d_GBps": (s1["h2d_bytes"] - s0["h2d_bytes"]) / max(s1["h2d_ms"] - s0["h2d_ms"], 1e-9) / 1e6,
-                        "note": "pools filled into the pinned slot by one host thread (numpy copy) and copied "
-                                "host-to-device while the previous pool trains"}
-            log(f"streamed: {streamed['value']:.4g} samples/s")
-            # Online pipeline (Sec. 3.3): the host producer (parallel online augmentation with
-            # pseudo shuffle, Sec. 3.1) fills one pinned slot while the GPU trains the other.
-            threads = min(16, os.cpu_count() or 1)
-            walks_per_pool = -(-P // 190)
             slot = gv.gv_acquire_pool_slot(ctx, P)
-            t0 = time.perf_counter()
-            gv.gv_augment(offsets, adj, seed=900, first_walk=0, count=P, threads=threads, out=slot)
+            gv.gv_augment(offsets, adj, seed=900, first_walk=first, count=P, threads=threads, out=slot)
             produce_s = time.perf_counter() - t0
             gv.gv_push_pool(ctx, slot, P)
-            gv.gv_sync(ctx)
-            steps = max(3, args.steps // 8)
             t0 = time.perf_counter()
             for i in range(steps):
                 gv.gv_train_pool(ctx)
                 if i + 1 < steps:
                     slot = gv.gv_acquire_pool_slot(ctx, P)
-                    gv.gv_augment(offsets, adj, seed=900, first_walk=(i + 1) * walks_per_pool, count=P,
+                    gv.gv_augment(offsets, adj, seed=900, first_walk=first + (i + 1) * walks_per_pool, count=P,
                                   threads=threads, out=slot)
                     gv.gv_push_pool(ctx, slot, P)
             gv.gv_sync(ctx)
             wall_o = time.perf_counter() - t0
-            streamed["online"] = {"value": steps * P / wall_o, "unit": "positive samples/s", "steps": steps,
-                                  "host_threads": threads, "producer_alone": P / produce_s,
-                                  "note": "pools generated on the fly by gv_augment into the pinned slots; "
-                                          "host-bound"}
-            log(f"online: {streamed['online']['value']:.4g} samples/s end to end, producer alone "
+            online["host_producer"] = {"value": steps * P / wall_o, "unit": "positive samples/s", "steps": steps,
+                                       "host_threads": threads, "producer_alone": P / produce_s,
+                                       "note": "pools generated on the fly by gv_augment into the pinned slots; host-bound"}
+            log(f"online, host producer: {online['host_producer']['value']:.4g} samples/s end to end, producer alone "
                 f"{P / produce_s:.4g} samples/s on {threads} threads")
             # The same pipeline with the producer on the device (gv_augment_device): pool k+1 is written
             # into the buffer that pool k-1 was trained from; producer and trainer share one stream.
             gv.gv_set_adjacency(ctx, offsets, adj)
-            bufs = [torch.empty((P, 2), dtype=torch.int32, device="cuda") for _ in range(2)]
-            for i in range(2):
-                gv.gv_augment_device(ctx, bufs[i].data_ptr(), seed=901, first_walk=i * walks_per_pool, count=P)
-            gv.gv_sync(ctx)
+            bufs = dev_pools[:2]
             t0 = time.perf_counter()
             for i in range(8):
                 gv.gv_augment_device(ctx, bufs[i % 2].data_ptr(), seed=901, first_walk=i * walks_per_pool, count=P)
@@ -212,13 +283,12 @@ def main():
                 gv.gv_train_device_pool(ctx, bufs[i % 2].data_ptr(), P)
             gv.gv_sync(ctx)
             wall_d = time.perf_counter() - t0
-            streamed["online_device"] = {"value": steps * P / wall_d, "unit": "positive samples/s", "steps": steps,
+            online["device_producer"] = {"value": steps * P / wall_d, "unit": "positive samples/s", "steps": steps,
                                          "producer_alone": P / produce_d,
                                          "note": "pools generated on the GPU by gv_augment_device, then trained; "
                                                  "nothing crosses PCIe"}
-            log(f"online on the device: {streamed['online_device']['value']:.4g} samples/s end to end, producer "
+            log(f"online, device producer: {online['device_producer']['value']:.4g} samples/s end to end, producer "
                 f"alone {P / produce_d:.4g} samples/s")
-            del bufs
     finally:
         gv.gv_destroy(ctx)
 
@@ -233,29 +303,39 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(n, deg, pools[0], dim, K, w, total, W.configs.TRAIN_SEED, args.cpu_samples)
-        log(f"cpu oracle: {cpu['value']:.4g} samples/s")
+        cpu = cpu_baseline(offsets, adj, deg, cfg, W.configs.TRAIN_SEED, args.cpu_samples, args.cpu_samples // 4)
+        log(f"cpu oracle: {cpu['value']:.4g} samples/s on one core, {cpu['all_cores']['value']:.4g} on "
+            f"{cpu['all_cores']['cores']} cores")
 
+    bytes_per_sample = algorithmic_bytes_per_sample(dim, K)
+    achieved = bytes_per_sample * P / (head["kernel_ms"] * 1e-3) / 1e9
+    traffic, traffic_source = profiled_traffic(args.workload, SCHEDULES[args.schedule], COHERENCES[args.coherence])
+    pools_text = "endpoints from the degree marginal" if adj is None else \
+        f"walks L={L}, s={s}, pseudo-shuffled, written by the library's producer"
     out = {
         "metric": "positive edge samples/sec (d=128,K=1) + achieved HBM GB/s fraction, 1 MI355X"
                   if args.workload == "c2" else f"positive edge samples/sec (d={dim},K={K}), 1 MI355X",
-        "value": value, "unit": "positive samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "value": head_sum["samples_per_s_median"], "unit": "positive samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["wall_s"] / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {cfg['graph']} n={n} edges={edges}, d={dim}, K={K}, "
-                               f"neg_weight={w}, pool=2^{int(np.log2(P))} samples resident in HBM, "
-                               f"{args.pools} distinct pools cycled ("
-                               + ("endpoints from the degree marginal" if adj is None else "walks L=40, s=5")
-                               + "), asynchronous mode",
-                   "coherence": ["plain", "agent", "atomic-agent", "mixed"][args.coherence],
-                   "schedule": ["pool-order", "tiled"][args.schedule], "samples_per_step": P},
+                               f"neg_weight={w}, pools of 2^{int(np.log2(P))} samples "
+                               + (f"streamed from {RING} pinned pools (host -> device copy overlapped with training)"
+                                  if streamed_is_headline else
+                                  f"resident in HBM ({RING} distinct pools cycled; the streamed rate is {gap * 100:.1f} % lower, "
+                                  "see `streamed`)")
+                               + f", {pools_text}, asynchronous mode",
+                   "coherence": COHERENCES[args.coherence], "schedule": SCHEDULES[args.schedule],
+                   "kernel": "k_train_tiled" if tiled else "k_train_hogwild", "warm_rows": stats["warm_rows"],
+                   "samples_per_step": P, "repetitions": REPETITIONS, "value_is": "median of the repetitions"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC_BYTES.get((args.workload, args.schedule, args.coherence)),
-                     "kernel": "k_train_tiled" if args.schedule else "k_train_hogwild", "kernel_ms": kernel_ms,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": "k_train_tiled" if tiled else "k_train_hogwild", "kernel_ms": head["kernel_ms"],
                      "bytes_per_sample": bytes_per_sample},
         "cpu_baseline": cpu,
-        "streamed": streamed,
+        "streamed": s_sum,
+        "resident": r_sum,
+        "online": online or None,
     }
     print(json.dumps(out), flush=True)
 

@@ -63,24 +63,38 @@ enum { GV_COHERENCE_PLAIN = 0, GV_COHERENCE_AGENT = 1, GV_COHERENCE_ATOMIC_AGENT
  *                samples sharing it, trading its change with memory every four samples
  *                and at the end of the run.  The launch still moves through the pool
  *                front to back, and each sample keeps the negatives and learning rate
- *                of its position in the pool.                                         */
-enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1 };
+ *                of its position in the pool.
+ *   AUTO         TILED when the graph has rows that concurrent samples are likely to share
+ *                (decided by gv_build_alias from the degrees), POOL_ORDER otherwise: on a
+ *                graph without such rows the tile bookkeeping buys nothing.  With
+ *                GV_COHERENCE_MIXED the pool-order launch then uses AGENT stores (all rows
+ *                are cold).                                                            */
+enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1, GV_SCHEDULE_AUTO = 2 };
+
+/* gv_config.neg_weight value that asks for the paper's setting: 5 / K (Sec. 4.3: one
+ * negative whose gradient is scaled by 5, i.e. the gradient scale of five negatives).  */
+#define GV_NEG_WEIGHT_DEFAULT (-1.0f)
+/* Largest number of pinned pool slots of a context (gv_config.pool_slots).              */
+#define GV_MAX_POOL_SLOTS 16
 
 typedef struct gv_config {
     uint32_t dim;            /* d: a multiple of 32 in 32..512 (128, or 96 in Sec. 4.3)       */
     uint32_t num_neg;        /* K negatives per positive sample, 1..5                         */
     float lr0;               /* initial learning rate (0.025 in Sec. 4.3)                      */
     float lr_min_ratio;      /* floor of the linear decay as a fraction of lr0 (0 = none)      */
-    float neg_weight;        /* w: factor on every negative's gradient (5 at K = 1, Sec. 4.3)  */
+    float neg_weight;        /* w >= 0: factor on every negative's gradient, or
+                                GV_NEG_WEIGHT_DEFAULT for 5 / K (5 at K = 1, Sec. 4.3)         */
     uint32_t mode;           /* GV_MODE_*                                                      */
     uint64_t total_samples;  /* T: planned positive samples; lr(g) = lr0 * max(1 - g/T, floor) */
     uint64_t seed;           /* key of the negative-sampling stream                            */
-    uint64_t pool_capacity;  /* largest pool (in samples, <= 2^31) that will be pushed; sizes the two
-                                pinned host slots and the two device buffers (8 B / sample)    */
+    uint64_t pool_capacity;  /* largest pool (in samples, <= 2^31) that will be pushed; sizes the
+                                pinned host slots and their device twins (8 B / sample each)   */
     int32_t device;          /* HIP device ordinal                                             */
     uint32_t coherence;      /* GV_COHERENCE_*                                                 */
     uint32_t profile;        /* nonzero: time every training launch with HIP events            */
     uint32_t schedule;       /* GV_SCHEDULE_* (asynchronous mode)                              */
+    uint32_t pool_slots;     /* pinned pool slots in the ring: 0 (= 2, the two pools of Sec. 3.3)
+                                or 2..GV_MAX_POOL_SLOTS                                        */
 } gv_config;
 
 typedef struct gv_stats {
@@ -93,62 +107,80 @@ typedef struct gv_stats {
     uint64_t timed_launches;    /* launches contributing to train_kernel_ms                    */
     double h2d_ms;              /* event-timed pool copies host -> device (profile != 0)        */
     uint64_t h2d_bytes;
+    uint64_t tiled_launches;    /* asynchronous launches that took the tiled schedule            */
+    uint64_t warm_rows;         /* rows that gv_build_alias classed as warm (see GV_SCHEDULE_AUTO) */
 } gv_stats;
 
-/* Create a context on cfg->device.  Allocates the pool slots only; the graph
- * decides the matrix sizes later.  *out is NULL on failure.                    */
+/* Create a context on cfg->device (one GPU holds all rows: the single-GPU case of
+ * Sec. 3.4).  Allocates the pool slots only; the graph decides the matrix sizes later.
+ * *out is NULL on failure (GV_EINVAL for a bad field, GV_EHIP without a usable device,
+ * GV_ENOMEM).                                                                        */
 int gv_create(const gv_config *cfg, gv_ctx **out);
+/* Wait for the context's device work, free everything it owns.  (Housekeeping, no passage.) */
 void gv_destroy(gv_ctx *ctx);
-const char *gv_last_error(const gv_ctx *ctx); /* ctx may be NULL: error of a failed gv_create */
+/* Text of the context's last failure; ctx may be NULL: error of a failed gv_create or of a
+ * context-free call, per thread.  (Housekeeping, no passage.)                          */
+const char *gv_last_error(const gv_ctx *ctx);
 
 /* Graph G = (V, E), undirected (Sec. 2.1, Sec. 4.3): m edges (host_src[i],
  * host_dst[i]), ids < n; only the degrees are kept.  Allocates both n x d
  * matrices (zero) and the alias table.  GV_EINVAL on an id >= n.               */
 int gv_set_graph(gv_ctx *ctx, uint32_t n, uint64_t m, const uint32_t *host_src, const uint32_t *host_dst);
-/* Same, from degrees alone (for graphs whose edge list the caller streams).    */
+/* Same, from degrees alone (for graphs whose edge list the caller streams): the degrees
+ * are all that negative sampling (Sec. 4.3) needs of the graph.                        */
 int gv_set_degrees(gv_ctx *ctx, uint32_t n, const uint32_t *host_deg);
 
-/* Alias table over nodes with weights degree^power (Sec. 4.3: power 3/4).
+/* Alias table over nodes with weights degree^power (Sec. 4.3: alias table trick, power 3/4).
  * power must be 0.75 (exact, via square roots), 1.0 or 0.0.  Built on the host
  * with Vose's method in fp64 (index-ordered stacks), thresholds stored as
  * floor(p * 2^32) saturated; uploaded to the device.                           */
 int gv_build_alias(gv_ctx *ctx, double power);
-/* Copy the table out: host_thresh[n], host_alias[n].                           */
+/* Copy the table out: host_thresh[n], host_alias[n].  (Test hook, no passage.)          */
 int gv_get_alias(gv_ctx *ctx, uint32_t *host_thresh, uint32_t *host_alias);
 
-/* vertex ~ U(-0.5/d, 0.5/d) from stream 1 of `seed`, context = 0.              */
+/* Initial embeddings (Sec. 4.3 defers to earlier systems; benchmark configuration 1 fixes
+ * them): vertex ~ U(-0.5/d, 0.5/d) from stream 1 of `seed`, element (row, col) from word
+ * col % 4 of block (row, col / 4) as ((word + 0.5) / 2^32 - 0.5) / d; context = 0.      */
 int gv_init_embeddings(gv_ctx *ctx, uint64_t seed);
-/* Overwrite rows [row0, row0+rows) of one matrix from host_rows[rows][d].      */
+/* Overwrite rows [row0, row0+rows) of one matrix (Sec. 2.1: vertex and context) from
+ * host_rows[rows][d].  Waits for training first.  (Test and resume hook.)               */
 int gv_set_embeddings(gv_ctx *ctx, int which, const float *host_rows, uint64_t row0, uint64_t rows);
-/* Wait for all training, then copy rows [row0, row0+rows) to host_rows.        */
+/* Wait for all training, then copy rows [row0, row0+rows) to host_rows: the learned
+ * embeddings of Sec. 2.1 (the vertex matrix is the output embedding).                   */
 int gv_read_embeddings(gv_ctx *ctx, int which, float *host_rows, uint64_t row0, uint64_t rows);
-/* Device address of a matrix (library-owned; valid until gv_destroy).          */
+/* Device address of a matrix (library-owned; valid until the next gv_set_graph /
+ * gv_set_degrees / gv_destroy).  (Diagnostic hook, no passage.)                         */
 int gv_device_embeddings(gv_ctx *ctx, int which, float **dev_rows);
 
-/* Pool streaming (Sec. 3.3 two pools, Sec. 3.4 batched transfer).  The context
- * has two pinned host slots of pool_capacity samples, each paired with a device
- * buffer.  gv_acquire_pool_slot hands out the next free slot for the producer
- * to fill in place (blocks until the training launch that last used that slot
- * has finished).  gv_push_pool queues `count` samples for training: if
- * host_pairs is a pointer returned by gv_acquire_pool_slot the copy to the
- * device starts directly from it, otherwise the samples are first copied into
- * the next free slot (host_pairs may be reused on return).  The copy runs on
- * its own stream and overlaps training of the previously pushed pool.  At most
- * two pools can be queued and untrained: a third push returns GV_ESTATE.
+/* Pool streaming (Sec. 3.3 collaboration strategy: producers fill one pool while the GPU
+ * trains on another; Sec. 3.4 batched transfer).  The context has a ring of
+ * cfg.pool_slots pinned host slots of pool_capacity samples, each paired with a device
+ * buffer.  gv_acquire_pool_slot hands out the next slot of the ring that is neither being
+ * filled nor queued, for the producer to fill in place; it blocks until the training launch
+ * that last used that slot has finished.  A slot keeps what was last written into it: a
+ * caller that filled the ring once may acquire and push the slots again without rewriting
+ * them.  gv_push_pool queues `count` samples for training: if host_pairs is a pointer
+ * returned by gv_acquire_pool_slot the copy to the device starts directly from it,
+ * otherwise the samples are first copied into the next free slot (host_pairs may be reused
+ * on return).  The copy runs on its own stream and overlaps the training of the pools
+ * pushed before.  At most pool_slots pools can be acquired or queued and untrained: one
+ * more gv_acquire_pool_slot / gv_push_pool returns GV_ESTATE.  A push that fails releases
+ * the acquired slot it named.
  * Node ids are checked on the device while training: a sample naming an id >= n
  * is skipped, and the next gv_sync (or any call that synchronises) returns
  * GV_EINVAL once.                                                              */
 int gv_acquire_pool_slot(gv_ctx *ctx, uint32_t **host_pairs);
 int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count);
-/* Train the oldest queued pool: positive samples g .. g+count-1 where g is the
+/* Train the oldest queued pool (Alg. 1, the loop over positive samples; Sec. 4.3
+ * asynchronous SGD): positive samples g .. g+count-1 where g is the
  * number of samples trained so far.  Returns after launching (asynchronous);
  * GV_ESTATE if nothing is queued.  The training calls keep device scratch sized
  * for the largest pool seen so far (a few words per sample): the first call, and
  * a call with a larger pool than any before, allocate (GV_ENOMEM / GV_EHIP if
  * that fails) and wait for the launches in flight.                              */
 int gv_train_pool(gv_ctx *ctx);
-/* Train a pool that already lies in device memory (dev_pairs must stay valid
- * and unchanged until gv_sync).  Ids are checked as for pushed pools.
+/* The same training step for a pool that already lies in device memory (dev_pairs must stay
+ * valid and unchanged until gv_sync).  Ids are checked as for pushed pools.
  * count <= 2^31.                                                               */
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
 
@@ -164,8 +196,11 @@ int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count)
  * their number.  host_pairs[count][2] may be any host memory, e.g. a slot returned by
  * gv_acquire_pool_slot.  Uses no GPU and no context.  *walks_used (may be NULL) receives
  * the number of walks consumed.  A node without neighbours must not be reachable
- * (degree-proportional departure never starts at one).                                */
+ * (degree-proportional departure never starts at one).  The adjacency is checked where the
+ * walks touch it: an empty or ill-formed row, or an entry >= n, gives GV_EINVAL (the pool
+ * is then incomplete); GV_ENOMEM / GV_EHIP when workers cannot be set up.              */
 enum { GV_SHUFFLE_NONE = 0, GV_SHUFFLE_PSEUDO = 1 };
+#define GV_MAX_WINDOW (1u << 20) /* largest augmentation distance `window` the producers accept */
 int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
                uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
                uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used);
@@ -189,24 +224,43 @@ int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t
                       uint64_t count, uint32_t shuffle, uint32_t *dev_pairs, uint64_t *walks_used);
 
 /* The K negatives of positive samples first_g .. first_g+count-1, exactly as
- * training draws them: host_out[count][K].                                     */
+ * training draws them (Alg. 1, NegativeSampling; Sec. 4.3 alias table): host_out[count][K].
+ * (Parity hook.)                                                                        */
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out);
 
 /* Evaluation on the device (after waiting for all training).
- * gv_eval_loss: mean over host_pairs[count][2] of the loss one training step descends,
+ * gv_eval_loss: mean over host_pairs[count][2] of the loss one training step descends
+ *   (Alg. 1 with the logistic loss of negative sampling),
  *   -log sigmoid(x_u . c_v) - w sum_k log sigmoid(-x_u . c_k), the K negatives of sample i
  *   drawn from the alias table with Philox stream 2 of eval_seed, counter (i, k).
  * gv_cosine: host_out[i] = cosine of vertex rows host_first[i], host_second[i] (0 for a
  *   zero row): the score of a node pair in link prediction (Sec. 4.5).
- * Ids >= n give GV_EINVAL.                                                          */
+ * Ids >= n give GV_EINVAL.  Both keep one device scratch buffer that grows with the largest
+ * call.                                                                              */
 int gv_eval_loss(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count, uint64_t eval_seed, double *mean_loss);
 int gv_cosine(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count, float *host_out);
+/* Link prediction (Sec. 4.5): the held-out edges are ranked against other node pairs by the
+ * cosine of their vertex rows and the result is the area under the ROC curve.
+ * gv_auc: *auc = (sum of the ranks of host_pos among all scores - P (P + 1) / 2) / (P N),
+ *   equal scores sharing their mean rank; P = num_pos, N = num_neg, both > 0; pure host
+ *   code, no context.  GV_EINVAL for an empty set or a score that is not finite.
+ * gv_link_prediction_auc: the same statistic of the cosines of num_edges pairs
+ *   (host_edge_first[i], host_edge_second[i]) against num_others pairs
+ *   (host_other_first[i], host_other_second[i]); waits for training first.             */
+int gv_auc(const float *host_pos, uint64_t num_pos, const float *host_neg, uint64_t num_neg, double *auc);
+int gv_link_prediction_auc(gv_ctx *ctx, const uint32_t *host_edge_first, const uint32_t *host_edge_second,
+                           uint64_t num_edges, const uint32_t *host_other_first, const uint32_t *host_other_second,
+                           uint64_t num_others, double *auc);
 
 /* Wait for all queued device work of the context; folds event timings into the
- * statistics.                                                                   */
+ * statistics; reports samples that named an id >= n (GV_EINVAL, once).
+ * (Housekeeping, no passage.)                                                   */
 int gv_sync(gv_ctx *ctx);
+/* Counters of the context so far.  (Diagnostic hook, no passage.)               */
 int gv_get_stats(gv_ctx *ctx, gv_stats *out);
-/* Set the position g of the next positive sample (resume / tests).             */
+/* Set the position g of the next positive sample: g selects the negatives (stream 0,
+ * counter (g, k)) and the learning rate lr0 * max(1 - g / T, floor) of Sec. 4.3, so a run
+ * resumes exactly.  (Resume and test hook.)                                      */
 int gv_set_position(gv_ctx *ctx, uint64_t next_g);
 
 #ifdef __cplusplus

@@ -14,7 +14,9 @@ GV_OK, GV_EINVAL, GV_ENOMEM, GV_ESTATE, GV_EHIP = 0, -1, -2, -3, -4
 GV_MODE_HOGWILD, GV_MODE_DETERMINISTIC = 0, 1
 GV_VERTEX, GV_CONTEXT = 0, 1
 GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_MIXED = 0, 1, 2, 3
-GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED = 0, 1
+GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED, GV_SCHEDULE_AUTO = 0, 1, 2
+GV_NEG_WEIGHT_DEFAULT = -1.0
+GV_MAX_POOL_SLOTS = 16
 GV_SHUFFLE_NONE, GV_SHUFFLE_PSEUDO = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
@@ -24,7 +26,7 @@ EXPORTS = [
     "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
     "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
-    "gv_set_adjacency", "gv_augment_device",
+    "gv_set_adjacency", "gv_augment_device", "gv_auc", "gv_link_prediction_auc",
 ]
 
 
@@ -35,6 +37,7 @@ class gv_config(C.Structure):
         ("mode", C.c_uint32),
         ("total_samples", C.c_uint64), ("seed", C.c_uint64), ("pool_capacity", C.c_uint64),
         ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("schedule", C.c_uint32),
+        ("pool_slots", C.c_uint32),
     ]
 
 
@@ -42,7 +45,7 @@ class gv_stats(C.Structure):
     _fields_ = [
         ("samples_trained", C.c_uint64), ("pools_trained", C.c_uint64), ("train_launches", C.c_uint64),
         ("batches", C.c_uint64), ("train_kernel_ms", C.c_double), ("timed_launches", C.c_uint64),
-        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64),
+        ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("tiled_launches", C.c_uint64), ("warm_rows", C.c_uint64),
     ]
 
     def as_dict(self):
@@ -94,6 +97,8 @@ def load():
     L.gv_set_position.argtypes = [vp, C.c_uint64]
     L.gv_eval_loss.argtypes = [vp, vp, C.c_uint64, C.c_uint64, C.POINTER(C.c_double)]
     L.gv_cosine.argtypes = [vp, u32p, u32p, C.c_uint64, f32p]
+    L.gv_auc.argtypes = [f32p, C.c_uint64, f32p, C.c_uint64, C.POINTER(C.c_double)]
+    L.gv_link_prediction_auc.argtypes = [vp, u32p, u32p, C.c_uint64, u32p, u32p, C.c_uint64, C.POINTER(C.c_double)]
     L.gv_augment.argtypes = [C.c_uint32, C.POINTER(C.c_uint64), u32p, C.c_uint64, C.c_uint32, C.c_uint32,
                              C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, vp, C.POINTER(C.c_uint64)]
     L.gv_set_adjacency.argtypes = [vp, C.POINTER(C.c_uint64), u32p]
@@ -117,13 +122,12 @@ def _u32(a):
     return a, a.ctypes.data_as(C.POINTER(C.c_uint32))
 
 
-def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=None, mode=GV_MODE_HOGWILD,
+def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=GV_NEG_WEIGHT_DEFAULT, mode=GV_MODE_HOGWILD,
               total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_MIXED, profile=0,
-              schedule=GV_SCHEDULE_TILED):
-    cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio,
-                    neg_weight=(5.0 / max(num_neg, 1) if neg_weight is None else neg_weight), mode=mode,
+              schedule=GV_SCHEDULE_AUTO, pool_slots=0):
+    cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio, neg_weight=neg_weight, mode=mode,
                     total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,
-                    coherence=coherence, profile=profile, schedule=schedule)
+                    coherence=coherence, profile=profile, schedule=schedule, pool_slots=pool_slots)
     ctx = C.c_void_p()
     rc = load().gv_create(C.byref(cfg), C.byref(ctx))
     _check(None, rc)
@@ -244,6 +248,27 @@ def gv_cosine(ctx, first, second):
     return out
 
 
+def gv_auc(pos_scores, neg_scores):
+    pos = np.ascontiguousarray(pos_scores, dtype=np.float32)
+    neg = np.ascontiguousarray(neg_scores, dtype=np.float32)
+    out = C.c_double()
+    _check(None, load().gv_auc(pos.ctypes.data_as(C.POINTER(C.c_float)), pos.size,
+                               neg.ctypes.data_as(C.POINTER(C.c_float)), neg.size, C.byref(out)))
+    return out.value
+
+
+def gv_link_prediction_auc(ctx, edge_first, edge_second, other_first, other_second):
+    ef, pef = _u32(edge_first)
+    es, pes = _u32(edge_second)
+    of, pof = _u32(other_first)
+    os_, pos_ = _u32(other_second)
+    if ef.size != es.size or of.size != os_.size:
+        raise ValueError("pair arrays differ in length")
+    out = C.c_double()
+    _check(ctx, load().gv_link_prediction_auc(ctx, pef, pes, ef.size, pof, pos_, of.size, C.byref(out)))
+    return out.value
+
+
 def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, count, shuffle=GV_SHUFFLE_PSEUDO,
                threads=1, out=None):
     """Fill ``out`` (uint32[count][2], allocated if None; may be a pinned slot view) with walk samples.
@@ -259,7 +284,8 @@ def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, co
                            adj.ctypes.data_as(C.POINTER(C.c_uint32)), seed, walk_length, window, first_walk, count,
                            shuffle, threads, C.c_void_p(out.ctypes.data), C.byref(walks))
     if rc != GV_OK:
-        raise GvError(rc, "gv_augment: bad argument")
+        raise GvError(rc, "gv_augment: bad argument or ill-formed adjacency" if rc == GV_EINVAL
+                      else "gv_augment: workers could not be set up")
     return out[:count], walks.value
 
 

@@ -19,17 +19,19 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Wall", "-Wextra", "-Wno-unused-parameter",
           # packed-fp32 instructions are kept out of the generated code on purpose
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("GV_EXTRA_CFLAGS", "").split()
+          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose: bool = False) -> str:
-    out_dir = os.path.join(HERE, "_build")
+def build(verbose: bool = False, extra_flags=(), lib: str = LIB, out_dir: str = "", csrc: str = CSRC) -> str:
+    """Compile and link; ``extra_flags``, ``lib`` and ``out_dir`` let a caller build a variant
+    (other -D settings) beside the product library without touching it."""
+    out_dir = out_dir or os.path.join(HERE, "_build")
     os.makedirs(out_dir, exist_ok=True)
     objects = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
-        cmd = [HIPCC, *COMMON, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *COMMON, "-I", csrc, *extra_flags, "-c", os.path.join(csrc, src), "-o", obj]
         if src == "gv_api.cpp":  # uses the HIP vector types in its interface to the kernels
             cmd.insert(1, "-x")
             cmd.insert(2, "hip")
@@ -44,10 +46,10 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + out)
         if verbose and out:
             print(out)
-    tmp = LIB + f".{os.getpid()}.tmp"
+    tmp = lib + f".{os.getpid()}.tmp"
     subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objects, "-lpthread"])
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -10,6 +10,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <exception>
 #include <new>
 #include <string>
 #include <utility>
@@ -58,12 +59,13 @@ struct gv_ctx {
     uint64_t negatives_capacity = 0;      // in uint32 elements
     uint32_t *records = nullptr;          // device scratch of the tiled kernel: K + 3 words per sample of a launch
     uint64_t records_capacity = 0;        // in uint32 elements
+    void *eval_scratch = nullptr;         // device scratch of gv_eval_loss / gv_cosine / gv_auc, grown on demand
+    uint64_t eval_capacity = 0;           // in bytes
     hipStream_t compute = nullptr;
     hipStream_t copy = nullptr;
-    PoolSlot slot[2];
-    int queue[2] = {-1, -1};              // FIFO of queued slot indices
-    int queued = 0;
-    int next_slot = 0;                    // slots are handed out alternately
+    std::vector<PoolSlot> slot;           // ring of cfg.pool_slots pinned slots, each with a device twin
+    std::vector<int> queue;               // FIFO of queued slot indices (front = oldest)
+    int next_slot = 0;                    // slots are handed out in ring order
     uint64_t next_g = 0;
     gv_stats stats{};
     std::vector<TimedSpan> spans;         // recorded, not yet folded into stats
@@ -75,14 +77,32 @@ struct gv_ctx {
 
 namespace {
 
-int fail(gv_ctx *ctx, int code, const char *fmt, ...) {
+int fail(gv_ctx *ctx, int code, const char *fmt, ...) noexcept {
     char buf[512];
     va_list ap;
     va_start(ap, fmt);
     vsnprintf(buf, sizeof buf, fmt, ap);
     va_end(ap);
-    if (ctx) ctx->error = buf; else g_create_error = buf;
+    try {
+        if (ctx) ctx->error = buf; else g_create_error = buf;
+    } catch (...) {  // no memory even for the text: the code alone is returned
+    }
     return code;
+}
+
+// Every entry point runs its body through this: an exception of the C++ runtime (a container that
+// cannot grow, a thread that cannot start) becomes an error code instead of crossing the C boundary.
+template <class Body>
+int guarded(gv_ctx *ctx, Body &&body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, GV_ENOMEM, "out of host memory");
+    } catch (const std::exception &e) {
+        return fail(ctx, GV_EHIP, "host runtime error: %s", e.what());
+    } catch (...) {
+        return fail(ctx, GV_EHIP, "unknown host runtime error");
+    }
 }
 
 #define GV_HIP(ctx, expr)                                                                          \
@@ -256,9 +276,9 @@ int begin_span(gv_ctx *ctx, int kind, hipStream_t stream, TimedSpan *span) {
 int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
     GV_HIP(ctx, hipEventRecord(span.stop, stream));
     ctx->spans.push_back(span);
-    if (ctx->spans.size() >= 8192) {  // bound the number of live events
-        GV_HIP(ctx, hipEventSynchronize(span.stop));
+    if (ctx->spans.size() >= 8192) {  // bound the number of live events: all of them must have completed
         GV_HIP(ctx, hipStreamSynchronize(ctx->copy));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
         fold_spans(ctx);
     }
     return GV_OK;
@@ -267,7 +287,16 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
 // Asynchronous training of `count` samples at dev_pairs: one launch of the tiled
 // stationary-row kernel, or of the plain pool-order kernel.
 int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
-    const bool tiled = ctx->cfg.schedule == GV_SCHEDULE_TILED && ctx->n <= 0x80000000u;
+    // GV_SCHEDULE_AUTO: the tiled schedule exists for rows that many samples of a tile share.  A graph
+    // without a single warm row has none, and there the sort, the records and the rank reads are pure
+    // cost: such a graph is trained in pool order (with the mixed policy all of its rows are cold, i.e.
+    // updated with device-scope stores).
+    const bool wants_tiled = ctx->cfg.schedule == GV_SCHEDULE_TILED ||
+                             (ctx->cfg.schedule == GV_SCHEDULE_AUTO && ctx->warm_ranks > 0);
+    const bool tiled = wants_tiled && ctx->n <= 0x80000000u;
+    uint32_t coherence = ctx->cfg.coherence;
+    if (!tiled && ctx->cfg.schedule == GV_SCHEDULE_AUTO && coherence == GV_COHERENCE_MIXED && ctx->warm_ranks == 0)
+        coherence = GV_COHERENCE_AGENT;
     if (tiled) {  // before the timed span: an allocation must not count as kernel time
         int rc = ensure_records(ctx, count * (ctx->cfg.num_neg + 3));
         if (rc) return rc;
@@ -281,11 +310,12 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
     if (tiled) {
         a.records = ctx->records;
-        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
     } else {
-        GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, ctx->cfg.coherence, ctx->compute));
+        GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
     }
     ctx->stats.train_launches += 1;
+    ctx->stats.tiled_launches += tiled ? 1 : 0;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
 }
@@ -380,19 +410,55 @@ int release_slot(gv_ctx *ctx, PoolSlot &s) {
     return GV_OK;
 }
 
+// Next slot of the ring that is not being filled and not waiting to be trained (ring order =
+// oldest first, so a slot still feeding a launch is the one whose launch ends soonest).
 int pick_free_slot(gv_ctx *ctx, int *index) {
-    for (int t = 0; t < 2; ++t) {
-        const int i = (ctx->next_slot + t) & 1;
+    const int slots = (int)ctx->slot.size();
+    for (int t = 0; t < slots; ++t) {
+        const int i = (ctx->next_slot + t) % slots;
         PoolSlot &s = ctx->slot[i];
         if (s.state == kFree || s.state == kTraining) {
             int rc = release_slot(ctx, s);
             if (rc) return rc;
             *index = i;
-            ctx->next_slot = i ^ 1;
+            ctx->next_slot = (i + 1) % slots;
             return GV_OK;
         }
     }
-    return fail(ctx, GV_ESTATE, "both pool slots are filling or queued: train a pool first");
+    return fail(ctx, GV_ESTATE, "all %d pool slots are filling or queued: train a pool first", slots);
+}
+
+// Device scratch shared by the evaluation calls: grown when a call needs more, kept otherwise.
+int ensure_eval_scratch(gv_ctx *ctx, uint64_t bytes) {
+    if (bytes <= ctx->eval_capacity) return GV_OK;
+    if (ctx->eval_scratch) {
+        (void)hipFree(ctx->eval_scratch);
+        ctx->eval_scratch = nullptr;
+        ctx->eval_capacity = 0;
+    }
+    GV_HIP(ctx, hipMalloc(&ctx->eval_scratch, bytes));
+    ctx->eval_capacity = bytes;
+    return GV_OK;
+}
+
+// Area under the ROC curve of `pos` against `neg` as the rank statistic
+// (sum of the positives' ranks - P (P + 1) / 2) / (P N), equal scores sharing their mean rank.
+double rank_auc(const float *pos, uint64_t num_pos, const float *neg, uint64_t num_neg) {
+    std::vector<std::pair<float, uint8_t>> all;
+    all.reserve(num_pos + num_neg);
+    for (uint64_t i = 0; i < num_pos; ++i) all.emplace_back(pos[i], (uint8_t)1);
+    for (uint64_t i = 0; i < num_neg; ++i) all.emplace_back(neg[i], (uint8_t)0);
+    std::sort(all.begin(), all.end(), [](const auto &a, const auto &b) { return a.first < b.first; });
+    double positive_ranks = 0.0;
+    for (size_t lo = 0; lo < all.size();) {
+        size_t hi = lo;
+        uint64_t positives = 0;
+        while (hi < all.size() && all[hi].first == all[lo].first) positives += all[hi++].second;
+        positive_ranks += (double)positives * (0.5 * ((double)(lo + 1) + (double)hi));  // ranks lo+1 .. hi share their mean
+        lo = hi;
+    }
+    const double P = (double)num_pos, N = (double)num_neg;
+    return (positive_ranks - P * (P + 1.0) / 2.0) / (P * N);
 }
 
 }  // namespace
@@ -404,31 +470,39 @@ const char *gv_last_error(const gv_ctx *ctx) { return ctx ? ctx->error.c_str() :
 int gv_create(const gv_config *cfg, gv_ctx **out) {
     if (out) *out = nullptr;
     if (!cfg || !out) return fail(nullptr, GV_EINVAL, "null argument");
-    if (!gv::supported_shape(cfg->dim, cfg->num_neg))
-        return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (a multiple of 32 in 32..512), num_neg %u (1..5)", cfg->dim,
-                    cfg->num_neg);
-    if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
-    if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 31))
-        return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^31 samples");
-    if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
-        cfg->schedule > GV_SCHEDULE_TILED)
-        return fail(nullptr, GV_EINVAL, "bad mode / coherence / schedule field");
-    if (!(cfg->lr0 >= 0.0f) || !(cfg->lr_min_ratio >= 0.0f) || !(cfg->neg_weight >= 0.0f) || !isfinite(cfg->lr0) ||
-        !isfinite(cfg->neg_weight))
-        return fail(nullptr, GV_EINVAL, "lr0, lr_min_ratio and neg_weight must be finite and >= 0");
-    int devices = 0;
-    if (hipGetDeviceCount(&devices) != hipSuccess || devices <= 0)
-        return fail(nullptr, GV_EHIP, "no HIP device available");
-    if (cfg->device < 0 || cfg->device >= devices)
-        return fail(nullptr, GV_EINVAL, "device %d out of range (%d present)", cfg->device, devices);
-    gv_ctx *ctx = new (std::nothrow) gv_ctx;
-    if (!ctx) return fail(nullptr, GV_ENOMEM, "out of host memory");
-    ctx->cfg = *cfg;
-    auto bail = [&](int code) {
-        g_create_error = ctx->error;
-        gv_destroy(ctx);
-        return code;
-    };
+    return guarded(nullptr, [&]() -> int {
+        if (!gv::supported_shape(cfg->dim, cfg->num_neg))
+            return fail(nullptr, GV_EINVAL, "unsupported shape: dim %u (a multiple of 32 in 32..512), num_neg %u (1..5)",
+                        cfg->dim, cfg->num_neg);
+        if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
+        if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 31))
+            return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^31 samples");
+        if (cfg->pool_slots == 1 || cfg->pool_slots > GV_MAX_POOL_SLOTS)
+            return fail(nullptr, GV_EINVAL, "pool_slots must be 0 (= 2) or in 2..%d", GV_MAX_POOL_SLOTS);
+        if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
+            cfg->schedule > GV_SCHEDULE_AUTO)
+            return fail(nullptr, GV_EINVAL, "bad mode / coherence / schedule field");
+        const bool default_weight = cfg->neg_weight == GV_NEG_WEIGHT_DEFAULT;
+        if (!(cfg->lr0 >= 0.0f) || !(cfg->lr_min_ratio >= 0.0f) || !(default_weight || cfg->neg_weight >= 0.0f) ||
+            !isfinite(cfg->lr0) || !isfinite(cfg->neg_weight))
+            return fail(nullptr, GV_EINVAL,
+                        "lr0, lr_min_ratio and neg_weight must be finite and >= 0 (neg_weight may be GV_NEG_WEIGHT_DEFAULT)");
+        int devices = 0;
+        if (hipGetDeviceCount(&devices) != hipSuccess || devices <= 0)
+            return fail(nullptr, GV_EHIP, "no HIP device available");
+        if (cfg->device < 0 || cfg->device >= devices)
+            return fail(nullptr, GV_EINVAL, "device %d out of range (%d present)", cfg->device, devices);
+        gv_ctx *ctx = new (std::nothrow) gv_ctx;
+        if (!ctx) return fail(nullptr, GV_ENOMEM, "out of host memory");
+        ctx->cfg = *cfg;
+        // Sec. 4.3: one negative whose gradient is scaled by 5, to match the gradient scale of 5 negatives
+        if (default_weight) ctx->cfg.neg_weight = 5.0f / (float)cfg->num_neg;
+        if (ctx->cfg.pool_slots == 0) ctx->cfg.pool_slots = 2;
+        auto bail = [&](int code) {
+            g_create_error = ctx->error;
+            gv_destroy(ctx);
+            return code;
+        };
 #define GV_TRY(expr)                                                                                       \
     do {                                                                                                   \
         hipError_t e_ = (expr);                                                                            \
@@ -437,21 +511,29 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
             return bail(e_ == hipErrorOutOfMemory ? GV_ENOMEM : GV_EHIP);                                  \
         }                                                                                                  \
     } while (0)
-    GV_TRY(hipSetDevice(cfg->device));
-    GV_TRY(hipStreamCreateWithFlags(&ctx->compute, hipStreamNonBlocking));
-    GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
-    GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
-    GV_TRY(hipMemset(ctx->error_flag, 0, sizeof(uint32_t)));
-    const size_t pool_bytes = (size_t)cfg->pool_capacity * 2 * sizeof(uint32_t);
-    for (PoolSlot &s : ctx->slot) {
-        GV_TRY(hipHostMalloc((void **)&s.host, pool_bytes, hipHostMallocDefault));
-        GV_TRY(hipMalloc((void **)&s.dev, pool_bytes));
-        GV_TRY(hipEventCreateWithFlags(&s.copied, hipEventDisableTiming));
-        GV_TRY(hipEventCreateWithFlags(&s.trained, hipEventDisableTiming));
-    }
+        try {
+            ctx->slot.resize(ctx->cfg.pool_slots);
+            ctx->queue.reserve(ctx->cfg.pool_slots);
+        } catch (...) {
+            fail(ctx, GV_ENOMEM, "out of host memory");
+            return bail(GV_ENOMEM);
+        }
+        GV_TRY(hipSetDevice(cfg->device));
+        GV_TRY(hipStreamCreateWithFlags(&ctx->compute, hipStreamNonBlocking));
+        GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
+        GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
+        GV_TRY(hipMemset(ctx->error_flag, 0, sizeof(uint32_t)));
+        const size_t pool_bytes = (size_t)cfg->pool_capacity * 2 * sizeof(uint32_t);
+        for (PoolSlot &s : ctx->slot) {
+            GV_TRY(hipHostMalloc((void **)&s.host, pool_bytes, hipHostMallocDefault));
+            GV_TRY(hipMalloc((void **)&s.dev, pool_bytes));
+            GV_TRY(hipEventCreateWithFlags(&s.copied, hipEventDisableTiming));
+            GV_TRY(hipEventCreateWithFlags(&s.trained, hipEventDisableTiming));
+        }
 #undef GV_TRY
-    *out = ctx;
-    return GV_OK;
+        *out = ctx;
+        return GV_OK;
+    });
 }
 
 void gv_destroy(gv_ctx *ctx) {
@@ -459,7 +541,14 @@ void gv_destroy(gv_ctx *ctx) {
     (void)hipSetDevice(ctx->cfg.device);
     if (ctx->copy) (void)hipStreamSynchronize(ctx->copy);
     if (ctx->compute) (void)hipStreamSynchronize(ctx->compute);
-    fold_spans(ctx);
+    try {
+        fold_spans(ctx);
+    } catch (...) {
+    }
+    for (const TimedSpan &s : ctx->spans) {  // left over only if folding failed
+        (void)hipEventDestroy(s.start);
+        (void)hipEventDestroy(s.stop);
+    }
     for (hipEvent_t e : ctx->spare_events) (void)hipEventDestroy(e);
     for (PoolSlot &s : ctx->slot) {
         if (s.host) (void)hipHostFree(s.host);
@@ -470,6 +559,7 @@ void gv_destroy(gv_ctx *ctx) {
     free_matrices(ctx);
     if (ctx->negatives) (void)hipFree(ctx->negatives);
     if (ctx->records) (void)hipFree(ctx->records);
+    if (ctx->eval_scratch) (void)hipFree(ctx->eval_scratch);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
     if (ctx->compute) (void)hipStreamDestroy(ctx->compute);
@@ -478,147 +568,158 @@ void gv_destroy(gv_ctx *ctx) {
 
 int gv_set_graph(gv_ctx *ctx, uint32_t n, uint64_t m, const uint32_t *host_src, const uint32_t *host_dst) {
     if (!ctx) return GV_EINVAL;
-    if (n == 0 || (m > 0 && (!host_src || !host_dst))) return fail(ctx, GV_EINVAL, "empty graph or null edge arrays");
-    int rc = bind_device(ctx);
-    if (rc) return rc;
-    std::vector<uint32_t> deg(n, 0u);
-    for (uint64_t i = 0; i < m; ++i) {
-        const uint32_t a = host_src[i], b = host_dst[i];
-        if (a >= n || b >= n)
-            return fail(ctx, GV_EINVAL, "edge %llu names node id >= n (%u)", (unsigned long long)i, n);
-        if (deg[a] == UINT32_MAX || deg[b] == UINT32_MAX) return fail(ctx, GV_EINVAL, "degree overflow");
-        ++deg[a];
-        ++deg[b];
-    }
-    return adopt_degrees(ctx, n, std::move(deg));
+    return guarded(ctx, [&]() -> int {
+        if (n == 0 || (m > 0 && (!host_src || !host_dst)))
+            return fail(ctx, GV_EINVAL, "empty graph or null edge arrays");
+        int rc = bind_device(ctx);
+        if (rc) return rc;
+        std::vector<uint32_t> deg(n, 0u);
+        for (uint64_t i = 0; i < m; ++i) {
+            const uint32_t a = host_src[i], b = host_dst[i];
+            if (a >= n || b >= n)
+                return fail(ctx, GV_EINVAL, "edge %llu names node id >= n (%u)", (unsigned long long)i, n);
+            if (deg[a] == UINT32_MAX || deg[b] == UINT32_MAX) return fail(ctx, GV_EINVAL, "degree overflow");
+            ++deg[a];
+            ++deg[b];
+        }
+        return adopt_degrees(ctx, n, std::move(deg));
+    });
 }
 
 int gv_set_degrees(gv_ctx *ctx, uint32_t n, const uint32_t *host_deg) {
     if (!ctx) return GV_EINVAL;
-    if (n == 0 || !host_deg) return fail(ctx, GV_EINVAL, "empty graph or null degree array");
-    int rc = bind_device(ctx);
-    if (rc) return rc;
-    return adopt_degrees(ctx, n, std::vector<uint32_t>(host_deg, host_deg + n));
+    return guarded(ctx, [&]() -> int {
+        if (n == 0 || !host_deg) return fail(ctx, GV_EINVAL, "empty graph or null degree array");
+        int rc = bind_device(ctx);
+        if (rc) return rc;
+        return adopt_degrees(ctx, n, std::vector<uint32_t>(host_deg, host_deg + n));
+    });
 }
 
 int gv_build_alias(gv_ctx *ctx, double power) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    if (power != 0.75 && power != 1.0 && power != 0.0)
-        return fail(ctx, GV_EINVAL, "power must be 0.75, 1.0 or 0.0");
-    const uint32_t n = ctx->n;
-    // scaled weights p_i = q_i * n / S, S accumulated in index order
-    std::vector<double> p(n);
-    double sum = 0.0, degree_sum = 0.0;
-    for (uint32_t i = 0; i < n; ++i) degree_sum += (double)ctx->degree[i];
-    for (uint32_t i = 0; i < n; ++i) {
-        const double d = (double)ctx->degree[i];
-        double q;
-        if (power == 0.75) {
-            const double root = sqrt(d);
-            q = root * sqrt(root);
-        } else if (power == 1.0) {
-            q = d;
-        } else {
-            q = 1.0;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (power != 0.75 && power != 1.0 && power != 0.0)
+            return fail(ctx, GV_EINVAL, "power must be 0.75, 1.0 or 0.0");
+        const uint32_t n = ctx->n;
+        // scaled weights p_i = q_i * n / S, S accumulated in index order
+        std::vector<double> p(n);
+        double sum = 0.0, degree_sum = 0.0;
+        for (uint32_t i = 0; i < n; ++i) degree_sum += (double)ctx->degree[i];
+        for (uint32_t i = 0; i < n; ++i) {
+            const double d = (double)ctx->degree[i];
+            double q;
+            if (power == 0.75) {
+                const double root = sqrt(d);
+                q = root * sqrt(root);
+            } else if (power == 1.0) {
+                q = d;
+            } else {
+                q = 1.0;
+            }
+            p[i] = q;
+            sum += q;
         }
-        p[i] = q;
-        sum += q;
-    }
-    if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
-    // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
-    // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
-    // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
-    // a full launch: several thousand waves, a few samples each), the expected number
-    // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
-    // or as a negative, share q/sum(q)) exceeds 0.1: the mixed policy then updates it with
-    // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
-    // update only when two of the few samples naming such a row are in flight together.  The
-    // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
-    const double kInFlight = 8192.0;
-    double warm_threshold = 0.1;
-    if (const char *e = getenv("GV_WARM_THRESHOLD")) {  // tuning sweeps
-        const double v = atof(e);
-        if (v > 0.0) warm_threshold = v;
-    }
-    const uint32_t kRanked = 0xFFFFu;
-    std::vector<uint32_t> order(n);
-    for (uint32_t i = 0; i < n; ++i) order[i] = i;
-    const uint32_t ranked = n < kRanked ? n : kRanked;
-    auto hotter = [&](uint32_t x, uint32_t y) {
-        return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;
-    };
-    std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
-    std::vector<uint16_t> rank(n, (uint16_t)kRanked);
-    std::vector<uint32_t> ranked_bits(((size_t)n + 31) / 32, 0u);
-    uint32_t warm_ranks = 0;
-    for (uint32_t r = 0; r < ranked; ++r) {
-        const uint32_t i = order[r];
-        rank[i] = (uint16_t)r;
-        ranked_bits[i >> 5] |= 1u << (i & 31u);
-        const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
-        if (share * kInFlight > warm_threshold) warm_ranks = r + 1;
-    }
-    order.clear();
-    order.shrink_to_fit();
-    std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
-    below.reserve(n);
-    above.reserve(n);
-    for (uint32_t i = 0; i < n; ++i) {
-        p[i] = p[i] * (double)n / sum;
-        (p[i] < 1.0 ? below : above).push_back(i);
-    }
-    std::vector<uint4> table(n);
-    std::vector<double> keep(n, 1.0);
-    for (uint32_t i = 0; i < n; ++i) table[i].y = i;
-    while (!below.empty() && !above.empty()) {
-        const uint32_t poor = below.back();
-        below.pop_back();
-        const uint32_t rich = above.back();
-        above.pop_back();
-        keep[poor] = p[poor];
-        table[poor].y = rich;
-        p[rich] = (p[rich] + p[poor]) - 1.0;
-        (p[rich] < 1.0 ? below : above).push_back(rich);
-    }
-    for (uint32_t i = 0; i < n; ++i) {
-        const double scaled = floor(keep[i] * 4294967296.0);
-        table[i].x = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
-        table[i].z = (uint32_t)rank[i] | (uint32_t)rank[table[i].y] << 16;  // saves the kernel a second gather
-        table[i].w = 0u;
-    }
-    rc = sync_all(ctx);
-    if (rc != GV_OK && rc != GV_EINVAL) return rc;
-    GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_ranked, ranked_bits.data(), ranked_bits.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
-    ctx->warm_ranks = warm_ranks;
-    ctx->alias_ready = true;
-    return GV_OK;
+        if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+        // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
+        // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
+        // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
+        // a full launch: several thousand waves, a few samples each), the expected number
+        // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
+        // or as a negative, share q/sum(q)) exceeds kWarmThreshold: the mixed policy then updates it with
+        // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
+        // update only when two of the few samples naming such a row are in flight together.  The
+        // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
+#ifndef GV_TUNE_WARM
+#define GV_TUNE_WARM 0.1
+#endif
+        const double kInFlight = 8192.0, kWarmThreshold = GV_TUNE_WARM;
+        const uint32_t kRanked = 0xFFFFu;
+        std::vector<uint32_t> order(n);
+        for (uint32_t i = 0; i < n; ++i) order[i] = i;
+        const uint32_t ranked = n < kRanked ? n : kRanked;
+        auto hotter = [&](uint32_t x, uint32_t y) {
+            return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;
+        };
+        std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
+        std::vector<uint16_t> rank(n, (uint16_t)kRanked);
+        std::vector<uint32_t> ranked_bits(((size_t)n + 31) / 32, 0u);
+        uint32_t warm_ranks = 0;
+        for (uint32_t r = 0; r < ranked; ++r) {
+            const uint32_t i = order[r];
+            rank[i] = (uint16_t)r;
+            ranked_bits[i >> 5] |= 1u << (i & 31u);
+            const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
+            if (share * kInFlight > kWarmThreshold) warm_ranks = r + 1;
+        }
+        order.clear();
+        order.shrink_to_fit();
+        std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
+        below.reserve(n);
+        above.reserve(n);
+        for (uint32_t i = 0; i < n; ++i) {
+            p[i] = p[i] * (double)n / sum;
+            (p[i] < 1.0 ? below : above).push_back(i);
+        }
+        std::vector<uint4> table(n);
+        std::vector<double> keep(n, 1.0);
+        for (uint32_t i = 0; i < n; ++i) table[i].y = i;
+        while (!below.empty() && !above.empty()) {
+            const uint32_t poor = below.back();
+            below.pop_back();
+            const uint32_t rich = above.back();
+            above.pop_back();
+            keep[poor] = p[poor];
+            table[poor].y = rich;
+            p[rich] = (p[rich] + p[poor]) - 1.0;
+            (p[rich] < 1.0 ? below : above).push_back(rich);
+        }
+        for (uint32_t i = 0; i < n; ++i) {
+            const double scaled = floor(keep[i] * 4294967296.0);
+            table[i].x = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
+            table[i].z = (uint32_t)rank[i] | (uint32_t)rank[table[i].y] << 16;  // saves the kernel a second gather
+            table[i].w = 0u;
+        }
+        rc = sync_all(ctx);
+        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_ranked, ranked_bits.data(), ranked_bits.size() * sizeof(uint32_t),
+                              hipMemcpyHostToDevice));
+        ctx->warm_ranks = warm_ranks;
+        ctx->stats.warm_rows = warm_ranks;
+        ctx->alias_ready = true;
+        return GV_OK;
+    });
 }
 
 int gv_get_alias(gv_ctx *ctx, uint32_t *host_thresh, uint32_t *host_alias) {
-    int rc = need_trainable(ctx);
-    if (rc) return rc;
-    if (!host_thresh || !host_alias) return fail(ctx, GV_EINVAL, "null output");
-    std::vector<uint4> table(ctx->n);
-    GV_HIP(ctx, hipMemcpy(table.data(), ctx->alias, (size_t)ctx->n * sizeof(uint4), hipMemcpyDeviceToHost));
-    for (uint32_t i = 0; i < ctx->n; ++i) {
-        host_thresh[i] = table[i].x;
-        host_alias[i] = table[i].y;
-    }
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (!host_thresh || !host_alias) return fail(ctx, GV_EINVAL, "null output");
+        std::vector<uint4> table(ctx->n);
+        GV_HIP(ctx, hipMemcpy(table.data(), ctx->alias, (size_t)ctx->n * sizeof(uint4), hipMemcpyDeviceToHost));
+        for (uint32_t i = 0; i < ctx->n; ++i) {
+            host_thresh[i] = table[i].x;
+            host_alias[i] = table[i].y;
+        }
+        return GV_OK;
+    });
 }
 
 int gv_init_embeddings(gv_ctx *ctx, uint64_t seed) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    rc = sync_all(ctx);
-    if (rc != GV_OK && rc != GV_EINVAL) return rc;
-    GV_HIP(ctx, gv::launch_init_vertex(ctx->vertex, ctx->n, ctx->cfg.dim, seed, ctx->compute));
-    GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, (size_t)ctx->n * ctx->cfg.dim * sizeof(float), ctx->compute));
-    GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        rc = sync_all(ctx);
+        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        GV_HIP(ctx, gv::launch_init_vertex(ctx->vertex, ctx->n, ctx->cfg.dim, seed, ctx->compute));
+        GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, (size_t)ctx->n * ctx->cfg.dim * sizeof(float), ctx->compute));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+        return GV_OK;
+    });
 }
 
 static int matrix_window(gv_ctx *ctx, int which, uint64_t row0, uint64_t rows, float **base) {
@@ -631,251 +732,337 @@ static int matrix_window(gv_ctx *ctx, int which, uint64_t row0, uint64_t rows, f
 }
 
 int gv_set_embeddings(gv_ctx *ctx, int which, const float *host_rows, uint64_t row0, uint64_t rows) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    float *base = nullptr;
-    rc = matrix_window(ctx, which, row0, rows, &base);
-    if (rc) return rc;
-    if (rows == 0) return GV_OK;
-    if (!host_rows) return fail(ctx, GV_EINVAL, "null input");
-    rc = sync_all(ctx);
-    if (rc != GV_OK && rc != GV_EINVAL) return rc;
-    GV_HIP(ctx, hipMemcpy(base, host_rows, rows * ctx->cfg.dim * sizeof(float), hipMemcpyHostToDevice));
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        float *base = nullptr;
+        rc = matrix_window(ctx, which, row0, rows, &base);
+        if (rc) return rc;
+        if (rows == 0) return GV_OK;
+        if (!host_rows) return fail(ctx, GV_EINVAL, "null input");
+        rc = sync_all(ctx);
+        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        GV_HIP(ctx, hipMemcpy(base, host_rows, rows * ctx->cfg.dim * sizeof(float), hipMemcpyHostToDevice));
+        return GV_OK;
+    });
 }
 
 int gv_read_embeddings(gv_ctx *ctx, int which, float *host_rows, uint64_t row0, uint64_t rows) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    float *base = nullptr;
-    rc = matrix_window(ctx, which, row0, rows, &base);
-    if (rc) return rc;
-    if (rows == 0) return GV_OK;
-    if (!host_rows) return fail(ctx, GV_EINVAL, "null output");
-    rc = sync_all(ctx);
-    if (rc) return rc;
-    GV_HIP(ctx, hipMemcpy(host_rows, base, rows * ctx->cfg.dim * sizeof(float), hipMemcpyDeviceToHost));
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        float *base = nullptr;
+        rc = matrix_window(ctx, which, row0, rows, &base);
+        if (rc) return rc;
+        if (rows == 0) return GV_OK;
+        if (!host_rows) return fail(ctx, GV_EINVAL, "null output");
+        rc = sync_all(ctx);
+        if (rc) return rc;
+        GV_HIP(ctx, hipMemcpy(host_rows, base, rows * ctx->cfg.dim * sizeof(float), hipMemcpyDeviceToHost));
+        return GV_OK;
+    });
 }
 
 int gv_device_embeddings(gv_ctx *ctx, int which, float **dev_rows) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    if (!dev_rows) return fail(ctx, GV_EINVAL, "null output");
-    return matrix_window(ctx, which, 0, 0, dev_rows);
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (!dev_rows) return fail(ctx, GV_EINVAL, "null output");
+        return matrix_window(ctx, which, 0, 0, dev_rows);
+    });
 }
 
 int gv_acquire_pool_slot(gv_ctx *ctx, uint32_t **host_pairs) {
     if (!ctx || !host_pairs) return ctx ? fail(ctx, GV_EINVAL, "null output") : GV_EINVAL;
-    int rc = bind_device(ctx);
-    if (rc) return rc;
-    int i = -1;
-    rc = pick_free_slot(ctx, &i);
-    if (rc) return rc;
-    ctx->slot[i].state = kFilling;
-    *host_pairs = ctx->slot[i].host;
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = bind_device(ctx);
+        if (rc) return rc;
+        int i = -1;
+        rc = pick_free_slot(ctx, &i);
+        if (rc) return rc;
+        ctx->slot[i].state = kFilling;
+        *host_pairs = ctx->slot[i].host;
+        return GV_OK;
+    });
 }
 
 int gv_push_pool(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count) {
-    int rc = need_trainable(ctx);
-    if (rc) return rc;
-    if (count > ctx->cfg.pool_capacity)
-        return fail(ctx, GV_EINVAL, "pool of %llu samples exceeds pool_capacity %llu", (unsigned long long)count,
-                    (unsigned long long)ctx->cfg.pool_capacity);
-    if (count > 0 && !host_pairs) return fail(ctx, GV_EINVAL, "null pool");
-    int i = -1;
-    for (int t = 0; t < 2; ++t)
-        if (ctx->slot[t].state == kFilling && ctx->slot[t].host == host_pairs) i = t;
-    if (i < 0) {
-        if (ctx->queued == 2) return fail(ctx, GV_ESTATE, "two pools already queued: train one first");
-        rc = pick_free_slot(ctx, &i);
+    return guarded(ctx, [&]() -> int {
+        if (!ctx) return GV_EINVAL;
+        int i = -1;  // the acquired slot this push refers to, if any
+        for (size_t t = 0; t < ctx->slot.size(); ++t)
+            if (ctx->slot[t].state == kFilling && ctx->slot[t].host == host_pairs) i = (int)t;
+        // a push that fails gives an acquired slot back: it would otherwise stay out of the ring for good
+        auto give_back = [&](int rc) -> int {
+            if (i >= 0) ctx->slot[i].state = kFree;
+            return rc;
+        };
+        int rc = need_trainable(ctx);
+        if (rc) return give_back(rc);
+        if (count > ctx->cfg.pool_capacity)
+            return give_back(fail(ctx, GV_EINVAL, "pool of %llu samples exceeds pool_capacity %llu",
+                                  (unsigned long long)count, (unsigned long long)ctx->cfg.pool_capacity));
+        if (count > 0 && !host_pairs) return fail(ctx, GV_EINVAL, "null pool");
+        if (i < 0) {
+            rc = pick_free_slot(ctx, &i);
+            if (rc) return rc;
+            memcpy(ctx->slot[i].host, host_pairs, count * 2 * sizeof(uint32_t));
+            ctx->slot[i].state = kFilling;
+        }
+        PoolSlot &s = ctx->slot[i];
+        s.count = count;
+        auto hip_step = [&](hipError_t e, const char *what) -> int {
+            if (e == hipSuccess) return GV_OK;
+            return give_back(fail(ctx, e == hipErrorOutOfMemory ? GV_ENOMEM : GV_EHIP, "%s: %s", what, hipGetErrorString(e)));
+        };
+        TimedSpan span{};
+        const bool timed = ctx->cfg.profile != 0 && count > 0;
+        if (timed) {
+            rc = begin_span(ctx, 1, ctx->copy, &span);
+            if (rc) return give_back(rc);
+        }
+        if (count > 0) {
+            rc = hip_step(hipMemcpyAsync(s.dev, s.host, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->copy),
+                          "hipMemcpyAsync of the pool");
+            if (rc) return rc;
+        }
+        if (timed) {
+            rc = end_span(ctx, ctx->copy, span);
+            if (rc) return give_back(rc);
+        }
+        rc = hip_step(hipEventRecord(s.copied, ctx->copy), "hipEventRecord");
         if (rc) return rc;
-        memcpy(ctx->slot[i].host, host_pairs, count * 2 * sizeof(uint32_t));
-    }
-    PoolSlot &s = ctx->slot[i];
-    s.count = count;
-    TimedSpan span{};
-    const bool timed = ctx->cfg.profile != 0 && count > 0;
-    if (timed) {
-        rc = begin_span(ctx, 1, ctx->copy, &span);
-        if (rc) return rc;
-    }
-    if (count > 0)
-        GV_HIP(ctx, hipMemcpyAsync(s.dev, s.host, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->copy));
-    if (timed) {
-        rc = end_span(ctx, ctx->copy, span);
-        if (rc) return rc;
-    }
-    GV_HIP(ctx, hipEventRecord(s.copied, ctx->copy));
-    ctx->stats.h2d_bytes += count * 2 * sizeof(uint32_t);
-    s.state = kQueued;
-    ctx->queue[ctx->queued++] = i;
-    return GV_OK;
+        ctx->stats.h2d_bytes += count * 2 * sizeof(uint32_t);
+        s.state = kQueued;
+        ctx->queue.push_back(i);
+        return GV_OK;
+    });
 }
 
 int gv_train_pool(gv_ctx *ctx) {
-    int rc = need_trainable(ctx);
-    if (rc) return rc;
-    if (ctx->queued == 0) return fail(ctx, GV_ESTATE, "no pool queued: call gv_push_pool first");
-    const int i = ctx->queue[0];
-    ctx->queue[0] = ctx->queue[1];
-    ctx->queue[1] = -1;
-    --ctx->queued;
-    PoolSlot &s = ctx->slot[i];
-    GV_HIP(ctx, hipStreamWaitEvent(ctx->compute, s.copied, 0));
-    rc = train_any(ctx, s.dev, s.host, s.count);
-    if (rc) {
-        s.state = kFree;
-        return rc;
-    }
-    GV_HIP(ctx, hipEventRecord(s.trained, ctx->compute));
-    s.state = kTraining;
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (ctx->queue.empty()) return fail(ctx, GV_ESTATE, "no pool queued: call gv_push_pool first");
+        const int i = ctx->queue.front();
+        ctx->queue.erase(ctx->queue.begin());
+        PoolSlot &s = ctx->slot[i];
+        // Whatever goes wrong from here on, the slot returns to the ring only after the copy into its
+        // device twin and every launch that may read it have ended.
+        auto drop_slot = [&](int rc) -> int {
+            (void)hipStreamSynchronize(ctx->copy);
+            (void)hipStreamSynchronize(ctx->compute);
+            s.state = kFree;
+            return rc;
+        };
+        hipError_t e = hipStreamWaitEvent(ctx->compute, s.copied, 0);
+        if (e != hipSuccess) return drop_slot(fail(ctx, GV_EHIP, "hipStreamWaitEvent: %s", hipGetErrorString(e)));
+        rc = train_any(ctx, s.dev, s.host, s.count);
+        if (rc) return drop_slot(rc);
+        e = hipEventRecord(s.trained, ctx->compute);
+        if (e != hipSuccess) return drop_slot(fail(ctx, GV_EHIP, "hipEventRecord: %s", hipGetErrorString(e)));
+        s.state = kTraining;
+        return GV_OK;
+    });
 }
 
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
-    int rc = need_trainable(ctx);
-    if (rc) return rc;
-    if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
-    if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
-    return train_any(ctx, dev_pairs, nullptr, count);
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
+        if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
+        return train_any(ctx, dev_pairs, nullptr, count);
+    });
 }
 
 int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *host_adj) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    if (!host_offsets || !host_adj) return fail(ctx, GV_EINVAL, "null adjacency");
-    const uint32_t n = ctx->n;
-    if (host_offsets[0] != 0) return fail(ctx, GV_EINVAL, "offsets[0] must be 0");
-    for (uint32_t i = 0; i < n; ++i)
-        if (host_offsets[i + 1] - host_offsets[i] != (uint64_t)ctx->degree[i])
-            return fail(ctx, GV_EINVAL, "row %u of the adjacency has %llu entries, the graph gives node %u degree %u", i,
-                        (unsigned long long)(host_offsets[i + 1] - host_offsets[i]), i, ctx->degree[i]);
-    const uint64_t half_edges = host_offsets[n];
-    if (half_edges == 0) return fail(ctx, GV_EINVAL, "graph without edges");
-    for (uint64_t e = 0; e < half_edges; ++e)
-        if (host_adj[e] >= n) return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
-    rc = sync_all(ctx);
-    if (rc != GV_OK && rc != GV_EINVAL) return rc;
-    if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
-    if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
-    ctx->dev_offsets = nullptr;
-    ctx->dev_adj = nullptr;
-    ctx->half_edges = 0;
-    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_offsets, ((size_t)n + 1) * sizeof(uint64_t)));
-    GV_HIP(ctx, hipMalloc((void **)&ctx->dev_adj, (size_t)half_edges * sizeof(uint32_t)));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_offsets, host_offsets, ((size_t)n + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
-    GV_HIP(ctx, hipMemcpy(ctx->dev_adj, host_adj, (size_t)half_edges * sizeof(uint32_t), hipMemcpyHostToDevice));
-    ctx->half_edges = half_edges;
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (!host_offsets || !host_adj) return fail(ctx, GV_EINVAL, "null adjacency");
+        const uint32_t n = ctx->n;
+        if (host_offsets[0] != 0) return fail(ctx, GV_EINVAL, "offsets[0] must be 0");
+        for (uint32_t i = 0; i < n; ++i)
+            if (host_offsets[i + 1] - host_offsets[i] != (uint64_t)ctx->degree[i])
+                return fail(ctx, GV_EINVAL, "row %u of the adjacency has %llu entries, the graph gives node %u degree %u",
+                            i, (unsigned long long)(host_offsets[i + 1] - host_offsets[i]), i, ctx->degree[i]);
+        const uint64_t half_edges = host_offsets[n];
+        if (half_edges == 0) return fail(ctx, GV_EINVAL, "graph without edges");
+        for (uint64_t e = 0; e < half_edges; ++e)
+            if (host_adj[e] >= n)
+                return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
+        rc = sync_all(ctx);
+        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
+        if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
+        ctx->dev_offsets = nullptr;
+        ctx->dev_adj = nullptr;
+        ctx->half_edges = 0;
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_offsets, ((size_t)n + 1) * sizeof(uint64_t)));
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_adj, (size_t)half_edges * sizeof(uint32_t)));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_offsets, host_offsets, ((size_t)n + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_adj, host_adj, (size_t)half_edges * sizeof(uint32_t), hipMemcpyHostToDevice));
+        ctx->half_edges = half_edges;
+        return GV_OK;
+    });
 }
 
 int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t window, uint64_t first_walk,
                       uint64_t count, uint32_t shuffle, uint32_t *dev_pairs, uint64_t *walks_used) {
     if (walks_used) *walks_used = 0;
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    if (!ctx->dev_offsets) return fail(ctx, GV_ESTATE, "no adjacency: call gv_set_adjacency first");
-    if (walk_length == 0 || walk_length > 64 || window == 0 || shuffle > GV_SHUFFLE_PSEUDO)
-        return fail(ctx, GV_EINVAL, "walk_length must be in 1..64, window >= 1, shuffle GV_SHUFFLE_*");
-    if (count == 0) return GV_OK;
-    if (!dev_pairs) return fail(ctx, GV_EINVAL, "null output");
-    gv::AugmentArgs a{};
-    a.offsets = ctx->dev_offsets;
-    a.adj = ctx->dev_adj;
-    a.pairs = (uint2 *)dev_pairs;
-    a.half_edges = ctx->half_edges;
-    a.seed = seed;
-    a.first_walk = first_walk;
-    a.count = count;
-    a.per_walk = 0;  // pairs (i, j), i < j <= min(i + window, walk_length)
-    for (uint32_t d = 1; d <= window && d <= walk_length; ++d) a.per_walk += walk_length + 1 - d;
-    a.walks = (count + a.per_walk - 1) / a.per_walk;
-    a.n = ctx->n;
-    a.length = walk_length;
-    a.window = window;
-    a.pseudo_shuffle = shuffle == GV_SHUFFLE_PSEUDO ? 1u : 0u;
-    if (walks_used) *walks_used = a.walks;
-    GV_HIP(ctx, gv::launch_augment(a, ctx->compute));
-    return GV_OK;
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (!ctx->dev_offsets) return fail(ctx, GV_ESTATE, "no adjacency: call gv_set_adjacency first");
+        if (walk_length == 0 || walk_length > 64 || window == 0 || window > GV_MAX_WINDOW || shuffle > GV_SHUFFLE_PSEUDO)
+            return fail(ctx, GV_EINVAL, "walk_length must be in 1..64, window in 1..GV_MAX_WINDOW, shuffle GV_SHUFFLE_*");
+        if (count == 0) return GV_OK;
+        if (!dev_pairs) return fail(ctx, GV_EINVAL, "null output");
+        gv::AugmentArgs a{};
+        a.offsets = ctx->dev_offsets;
+        a.adj = ctx->dev_adj;
+        a.pairs = (uint2 *)dev_pairs;
+        a.half_edges = ctx->half_edges;
+        a.seed = seed;
+        a.first_walk = first_walk;
+        a.count = count;
+        a.per_walk = 0;  // pairs (i, j), i < j <= min(i + window, walk_length)
+        for (uint32_t d = 1; d <= window && d <= walk_length; ++d) a.per_walk += walk_length + 1 - d;
+        a.walks = (count + a.per_walk - 1) / a.per_walk;
+        a.n = ctx->n;
+        a.length = walk_length;
+        a.window = window;
+        a.pseudo_shuffle = shuffle == GV_SHUFFLE_PSEUDO ? 1u : 0u;
+        if (walks_used) *walks_used = a.walks;
+        GV_HIP(ctx, gv::launch_augment(a, ctx->compute));
+        return GV_OK;
+    });
 }
 
 int gv_draw_negatives(gv_ctx *ctx, uint64_t first_g, uint64_t count, uint32_t *host_out) {
-    int rc = need_trainable(ctx);
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (count == 0) return GV_OK;
+        if (!host_out) return fail(ctx, GV_EINVAL, "null output");
+        if (count > (1ull << 32)) return fail(ctx, GV_EINVAL, "at most 2^32 samples per call");
+        const uint32_t K = ctx->cfg.num_neg;
+        rc = ensure_negatives(ctx, count * K);
+        if (rc) return rc;
+        GV_HIP(ctx, gv::launch_draw_negatives(ctx->alias, ctx->n, ctx->cfg.seed, first_g, count, K, ctx->negatives,
+                                              ctx->compute));
+        GV_HIP(ctx, hipMemcpyAsync(host_out, ctx->negatives, count * K * sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                   ctx->compute));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+        return GV_OK;
+    });
+}
+
+int gv_eval_loss(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count, uint64_t eval_seed, double *mean_loss) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (!mean_loss || (count > 0 && !host_pairs)) return fail(ctx, GV_EINVAL, "null argument");
+        if (count == 0 || count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "count must be in 1 .. 2^32-1");
+        rc = sync_all(ctx);
+        if (rc) return rc;
+        // scratch layout: the running total (a double, 256 bytes reserved), then the pairs
+        rc = ensure_eval_scratch(ctx, 256 + count * 2 * sizeof(uint32_t));
+        if (rc) return rc;
+        double *dev_total = (double *)ctx->eval_scratch;
+        uint32_t *dev_pairs = (uint32_t *)((char *)ctx->eval_scratch + 256);
+        GV_HIP(ctx, hipMemcpyAsync(dev_pairs, host_pairs, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->compute));
+        GV_HIP(ctx, hipMemsetAsync(dev_total, 0, sizeof(double), ctx->compute));
+        gv::TrainArgs a = train_args(ctx, dev_pairs, 0, (uint32_t)count);
+        a.seed = eval_seed;
+        GV_HIP(ctx, gv::launch_eval_loss(a, ctx->cfg.dim, ctx->cfg.num_neg, dev_total, ctx->compute));
+        double total = 0.0;
+        GV_HIP(ctx, hipMemcpyAsync(&total, dev_total, sizeof(double), hipMemcpyDeviceToHost, ctx->compute));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+        *mean_loss = total / (double)count;
+        return sync_all(ctx);  // reports ids >= n
+    });
+}
+
+// cosines of `count` node pairs into host_out, through the evaluation scratch
+static int cosine_scores(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count,
+                         float *host_out) {
+    int rc = ensure_eval_scratch(ctx, count * (2 * sizeof(uint32_t) + sizeof(float)));
     if (rc) return rc;
-    if (count == 0) return GV_OK;
-    if (!host_out) return fail(ctx, GV_EINVAL, "null output");
-    if (count > (1ull << 32)) return fail(ctx, GV_EINVAL, "at most 2^32 samples per call");
-    const uint32_t K = ctx->cfg.num_neg;
-    rc = ensure_negatives(ctx, count * K);
-    if (rc) return rc;
-    GV_HIP(ctx, gv::launch_draw_negatives(ctx->alias, ctx->n, ctx->cfg.seed, first_g, count, K, ctx->negatives,
-                                          ctx->compute));
-    GV_HIP(ctx, hipMemcpyAsync(host_out, ctx->negatives, count * K * sizeof(uint32_t), hipMemcpyDeviceToHost,
-                               ctx->compute));
+    uint32_t *dev_ids = (uint32_t *)ctx->eval_scratch;
+    float *dev_out = (float *)(dev_ids + 2 * count);
+    GV_HIP(ctx, hipMemcpyAsync(dev_ids, host_first, count * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->compute));
+    GV_HIP(ctx, hipMemcpyAsync(dev_ids + count, host_second, count * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->compute));
+    GV_HIP(ctx, gv::launch_cosine(ctx->vertex, ctx->n, ctx->cfg.dim, dev_ids, dev_ids + count, (uint32_t)count, dev_out,
+                                  ctx->error_flag, ctx->compute));
+    GV_HIP(ctx, hipMemcpyAsync(host_out, dev_out, count * sizeof(float), hipMemcpyDeviceToHost, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
     return GV_OK;
 }
 
-int gv_eval_loss(gv_ctx *ctx, const uint32_t *host_pairs, uint64_t count, uint64_t eval_seed, double *mean_loss) {
-    int rc = need_trainable(ctx);
-    if (rc) return rc;
-    if (!mean_loss || (count > 0 && !host_pairs)) return fail(ctx, GV_EINVAL, "null argument");
-    if (count == 0 || count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "count must be in 1 .. 2^32-1");
-    rc = sync_all(ctx);
-    if (rc) return rc;
-    uint32_t *dev_pairs = nullptr;
-    double *dev_total = nullptr;
-    GV_HIP(ctx, hipMalloc((void **)&dev_pairs, count * 2 * sizeof(uint32_t)));
-    hipError_t e = hipMalloc((void **)&dev_total, sizeof(double));
-    if (e == hipSuccess) e = hipMemcpy(dev_pairs, host_pairs, count * 2 * sizeof(uint32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemset(dev_total, 0, sizeof(double));
-    if (e == hipSuccess) {
-        gv::TrainArgs a = train_args(ctx, dev_pairs, 0, (uint32_t)count);
-        a.seed = eval_seed;
-        e = gv::launch_eval_loss(a, ctx->cfg.dim, ctx->cfg.num_neg, dev_total, ctx->compute);
-    }
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->compute);
-    double total = 0.0;
-    if (e == hipSuccess) e = hipMemcpy(&total, dev_total, sizeof(double), hipMemcpyDeviceToHost);
-    (void)hipFree(dev_pairs);
-    if (dev_total) (void)hipFree(dev_total);
-    GV_HIP(ctx, e);
-    *mean_loss = total / (double)count;
-    return sync_all(ctx);  // reports ids >= n
+int gv_cosine(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count, float *host_out) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (count == 0) return GV_OK;
+        if (!host_first || !host_second || !host_out) return fail(ctx, GV_EINVAL, "null argument");
+        if (count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "at most 2^32-1 pairs per call");
+        rc = sync_all(ctx);
+        if (rc) return rc;
+        rc = cosine_scores(ctx, host_first, host_second, count, host_out);
+        if (rc) return rc;
+        return sync_all(ctx);
+    });
 }
 
-int gv_cosine(gv_ctx *ctx, const uint32_t *host_first, const uint32_t *host_second, uint64_t count, float *host_out) {
-    int rc = need_graph(ctx);
-    if (rc) return rc;
-    if (count == 0) return GV_OK;
-    if (!host_first || !host_second || !host_out) return fail(ctx, GV_EINVAL, "null argument");
-    if (count > (1ull << 32) - 1) return fail(ctx, GV_EINVAL, "at most 2^32-1 pairs per call");
-    rc = sync_all(ctx);
-    if (rc) return rc;
-    uint32_t *dev_ids = nullptr;
-    float *dev_out = nullptr;
-    GV_HIP(ctx, hipMalloc((void **)&dev_ids, count * 2 * sizeof(uint32_t)));
-    hipError_t e = hipMalloc((void **)&dev_out, count * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(dev_ids, host_first, count * sizeof(uint32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(dev_ids + count, host_second, count * sizeof(uint32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess)
-        e = gv::launch_cosine(ctx->vertex, ctx->n, ctx->cfg.dim, dev_ids, dev_ids + count, (uint32_t)count, dev_out,
-                              ctx->error_flag, ctx->compute);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->compute);
-    if (e == hipSuccess) e = hipMemcpy(host_out, dev_out, count * sizeof(float), hipMemcpyDeviceToHost);
-    (void)hipFree(dev_ids);
-    if (dev_out) (void)hipFree(dev_out);
-    GV_HIP(ctx, e);
-    return sync_all(ctx);
+int gv_auc(const float *host_pos, uint64_t num_pos, const float *host_neg, uint64_t num_neg, double *auc) {
+    if (!auc) return GV_EINVAL;
+    *auc = 0.0;
+    if (num_pos == 0 || num_neg == 0 || !host_pos || !host_neg) return GV_EINVAL;
+    return guarded(nullptr, [&]() -> int {
+        for (uint64_t i = 0; i < num_pos; ++i)
+            if (!isfinite(host_pos[i])) return fail(nullptr, GV_EINVAL, "positive score %llu is not finite", (unsigned long long)i);
+        for (uint64_t i = 0; i < num_neg; ++i)
+            if (!isfinite(host_neg[i])) return fail(nullptr, GV_EINVAL, "negative score %llu is not finite", (unsigned long long)i);
+        *auc = rank_auc(host_pos, num_pos, host_neg, num_neg);
+        return GV_OK;
+    });
+}
+
+int gv_link_prediction_auc(gv_ctx *ctx, const uint32_t *host_edge_first, const uint32_t *host_edge_second,
+                           uint64_t num_edges, const uint32_t *host_other_first, const uint32_t *host_other_second,
+                           uint64_t num_others, double *auc) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_graph(ctx);
+        if (rc) return rc;
+        if (!auc || !host_edge_first || !host_edge_second || !host_other_first || !host_other_second)
+            return fail(ctx, GV_EINVAL, "null argument");
+        if (num_edges == 0 || num_others == 0 || num_edges + num_others > (1ull << 31))
+            return fail(ctx, GV_EINVAL, "both pair sets must be non-empty and hold at most 2^31 pairs together");
+        rc = sync_all(ctx);
+        if (rc) return rc;
+        std::vector<float> scores(num_edges + num_others);
+        rc = cosine_scores(ctx, host_edge_first, host_edge_second, num_edges, scores.data());
+        if (rc) return rc;
+        rc = cosine_scores(ctx, host_other_first, host_other_second, num_others, scores.data() + num_edges);
+        if (rc) return rc;
+        rc = sync_all(ctx);  // ids >= n
+        if (rc) return rc;
+        for (float x : scores)
+            if (!isfinite(x)) return fail(ctx, GV_EINVAL, "an embedding row is not finite");
+        *auc = rank_auc(scores.data(), num_edges, scores.data() + num_edges, num_others);
+        return GV_OK;
+    });
 }
 
 int gv_sync(gv_ctx *ctx) {
     if (!ctx) return GV_EINVAL;
-    int rc = bind_device(ctx);
-    if (rc) return rc;
-    return sync_all(ctx);
+    return guarded(ctx, [&]() -> int {
+        int rc = bind_device(ctx);
+        if (rc) return rc;
+        return sync_all(ctx);
+    });
 }
 
 int gv_get_stats(gv_ctx *ctx, gv_stats *out) {

@@ -4,6 +4,9 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <atomic>
+#include <exception>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -42,16 +45,16 @@ constexpr uint32_t kWalkStream = 4;
 
 }  // namespace
 
-extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
-                          uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
-                          uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
+static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
+                   uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
+                   uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
     if (walks_used) *walks_used = 0;
     if (count == 0) return GV_OK;
     if (!host_offsets || !host_adj || !host_pairs || n == 0 || walk_length == 0 || window == 0 ||
-        shuffle > GV_SHUFFLE_PSEUDO)
+        window > GV_MAX_WINDOW || shuffle > GV_SHUFFLE_PSEUDO)
         return GV_EINVAL;
     const uint64_t half_edges = host_offsets[n];
-    if (half_edges == 0) return GV_EINVAL;
+    if (half_edges == 0 || host_offsets[0] != 0) return GV_EINVAL;
     const uint32_t L = walk_length, s = window;
     uint64_t per_walk = 0;  // pairs (i, j), i < j <= min(i + s, L)
     for (uint32_t d = 1; d <= s && d <= L; ++d) per_walk += L + 1 - d;
@@ -66,22 +69,41 @@ extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32
     for (uint32_t b = 0; b < s; ++b) block_start[b + 1] = block_start[b] + (count > b ? (count - b + s - 1) / s : 0);
 
     const uint32_t workers = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(threads ? threads : 1, walks));
+    // The adjacency is checked where a walk touches it (a full scan per pool would cost as much as
+    // the walks): a row that is empty, runs backwards or past the end, or an entry >= n stops the
+    // walk's worker and the call reports GV_EINVAL.
+    std::atomic<bool> broken{false};
+    std::vector<std::vector<uint32_t>> paths(workers);
+    for (auto &path : paths) path.resize((size_t)L + 1);
     auto work = [&](uint32_t worker) {
-        std::vector<uint32_t> path(L + 1);
+        std::vector<uint32_t> &path = paths[worker];
         const uint64_t lo = walks * worker / workers, hi = walks * (worker + 1) / workers;
         for (uint64_t w = lo; w < hi; ++w) {
             // departure: owner of a uniformly chosen half-edge = probability proportional to degree
             const uint64_t e = pick(philox(seed, first_walk + w, 0, kWalkStream), half_edges);
             const uint64_t *owner = std::upper_bound(host_offsets, host_offsets + n + 1, e) - 1;
+            if (owner < host_offsets || owner >= host_offsets + n) {  // offsets not ascending from 0
+                broken.store(true, std::memory_order_relaxed);
+                return;
+            }
             path[0] = (uint32_t)(owner - host_offsets);
             for (uint32_t t = 1; t <= L; ++t) {
                 const uint32_t x = path[t - 1];
-                const uint64_t begin = host_offsets[x], degree = host_offsets[x + 1] - begin;
-                path[t] = host_adj[begin + pick(philox(seed, first_walk + w, t, kWalkStream), degree)];
+                const uint64_t begin = host_offsets[x], end = host_offsets[x + 1];
+                if (end <= begin || end > half_edges) {
+                    broken.store(true, std::memory_order_relaxed);
+                    return;
+                }
+                const uint32_t next = host_adj[begin + pick(philox(seed, first_walk + w, t, kWalkStream), end - begin)];
+                if (next >= n) {
+                    broken.store(true, std::memory_order_relaxed);
+                    return;
+                }
+                path[t] = next;
             }
             uint64_t t_global = w * per_walk;
             for (uint32_t i = 0; i <= L; ++i)
-                for (uint32_t j = i + 1; j <= L && j <= i + s; ++j, ++t_global) {
+                for (uint32_t j = i + 1; j <= L && j - i <= s; ++j, ++t_global) {
                     if (t_global >= count) return;
                     const uint64_t at = shuffle == GV_SHUFFLE_PSEUDO ? block_start[t_global % s] + t_global / s : t_global;
                     host_pairs[2 * at] = path[i];
@@ -94,8 +116,26 @@ extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32
     } else {
         std::vector<std::thread> pool;
         pool.reserve(workers);
-        for (uint32_t i = 0; i < workers; ++i) pool.emplace_back(work, i);
+        try {
+            for (uint32_t i = 0; i < workers; ++i) pool.emplace_back(work, i);
+        } catch (...) {  // a thread could not start: finish the ones that did, then report
+            for (std::thread &t : pool) t.join();
+            throw;
+        }
         for (std::thread &t : pool) t.join();
     }
-    return GV_OK;
+    return broken.load() ? GV_EINVAL : GV_OK;
+}
+
+extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
+                          uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
+                          uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
+    try {
+        return augment(n, host_offsets, host_adj, seed, walk_length, window, first_walk, count, shuffle, threads,
+                       host_pairs, walks_used);
+    } catch (const std::bad_alloc &) {
+        return GV_ENOMEM;
+    } catch (...) {  // std::system_error of a thread that could not start, and anything else
+        return GV_EHIP;
+    }
 }

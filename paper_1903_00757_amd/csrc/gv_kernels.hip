@@ -15,6 +15,12 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 constexpr int kBlock = 256;  // 4 waves per workgroup
+#ifndef GV_TUNE_BATCH
+#define GV_TUNE_BATCH 4
+#endif
+#ifndef GV_TUNE_GRID
+#define GV_TUNE_GRID 0
+#endif
 // Row traffic policies (gv_config.coherence).
 constexpr int kPlain = 0;        // cached loads and stores
 constexpr int kAgent = 1;        // device-scope loads and stores
@@ -100,8 +106,10 @@ __device__ __forceinline__ uint32_t lane_value(uint32_t x, uint32_t lane) {
 // accesses use 16-byte segments when the row allows, device-scope accesses use
 // 8-byte segments (the widest single-copy-atomic access).  Element e of segment
 // s sits at row[s * 64 * W + lane * W + e], so each segment is one contiguous
-// 64 * W * 4 byte request per wave.
-template <int kV, int kCoherence>
+// 64 * W * 4 byte request per wave.  kFull says that the row is exactly 64 * kV floats long:
+// then no lane is ever past the end and the per-lane bounds tests (and the execution-mask
+// bookkeeping they cost around every memory instruction) are compiled out.
+template <int kV, int kCoherence, bool kFull = false>
 struct RowIo {
     static constexpr int W = is_agent(kCoherence) ? (kV >= 2 ? 2 : 1) : (kV >= 4 ? 4 : kV);
     static constexpr int S = kV / W;
@@ -110,7 +118,7 @@ struct RowIo {
     static __device__ __forceinline__ void load(const float *row, int lane, uint32_t dim, float (&x)[kV]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if ((uint32_t)(s * (kWave * W) + lane * W) >= dim) {
+            if (!kFull && (uint32_t)(s * (kWave * W) + lane * W) >= dim) {
 #pragma unroll
                 for (int e = 0; e < W; ++e) x[s * W + e] = 0.0f;
                 continue;
@@ -154,12 +162,12 @@ struct RowIo {
                 const float first = __int_as_float((lane & 1) ? lo1 : lo0);
                 const float second = __int_as_float((lane & 1) ? hi1 : hi0);
                 float *p = row + s * (kWave * 2) + lane;
-                if ((uint32_t)(s * (kWave * 2) + lane) < dim)
+                if (kFull || (uint32_t)(s * (kWave * 2) + lane) < dim)
                     (void)__hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
+                if (kFull || (uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
                     (void)__hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                if ((uint32_t)(s * kWave + lane) < dim)
+                if (kFull || (uint32_t)(s * kWave + lane) < dim)
                     (void)__hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -182,9 +190,9 @@ struct RowIo {
                 float first = __int_as_float((lane & 1) ? lo1 : lo0);    // element lane of the segment
                 float second = __int_as_float((lane & 1) ? hi1 : hi0);   // element 64 + lane
                 float *p = row + s * (kWave * 2) + lane;
-                if ((uint32_t)(s * (kWave * 2) + lane) < dim)
+                if (kFull || (uint32_t)(s * (kWave * 2) + lane) < dim)
                     first += __hip_atomic_fetch_add(p, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
+                if (kFull || (uint32_t)(s * (kWave * 2) + kWave + lane) < dim)
                     second += __hip_atomic_fetch_add(p + kWave, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 // lane l wants elements 2l and 2l + 1: lanes 2l, 2l + 1 hold them in `first` when
                 // l < 32, lanes 2l - 64, 2l - 63 in `second` otherwise
@@ -197,7 +205,7 @@ struct RowIo {
                 x[s * 2 + 1] = __int_as_float(lane < 32 ? f_odd : s_odd);
                 delta[s * 2] = delta[s * 2 + 1] = 0.0f;
             } else {
-                if ((uint32_t)(s * kWave + lane) < dim)
+                if (kFull || (uint32_t)(s * kWave + lane) < dim)
                     x[s] = delta[s] + __hip_atomic_fetch_add(row + s * kWave + lane, delta[s], __ATOMIC_RELAXED,
                                                              __HIP_MEMORY_SCOPE_AGENT);
                 delta[s] = 0.0f;
@@ -208,7 +216,7 @@ struct RowIo {
     static __device__ __forceinline__ void store(float *row, int lane, uint32_t dim, const float (&x)[kV]) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if ((uint32_t)(s * (kWave * W) + lane * W) >= dim) continue;
+            if (!kFull && (uint32_t)(s * (kWave * W) + lane * W) >= dim) continue;
             float *p = row + s * (kWave * W) + lane * W;
             if constexpr (is_agent(kCoherence)) {
                 if constexpr (W == 2) {
@@ -242,10 +250,10 @@ __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + __expf
 // with coef_0 = lr (1 - sigmoid(s_0)), coef_k = -lr w sigmoid(s_k).  A context
 // row named more than once in the sample is written once with the summed
 // coefficient.  u and rows[] are wave-uniform.
-template <int kV, int kK, int kCoherence>
+template <int kV, int kK, int kCoherence, bool kFull>
 __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__restrict__ context, uint32_t u,
                                           const uint32_t (&rows)[kK + 1], float lr, float w, int lane, uint32_t D) {
-    using Io = RowIo<kV, kCoherence>;
+    using Io = RowIo<kV, kCoherence, kFull>;
     float *xp = vertex + (size_t)u * D;
     float x[kV];
     float c[kK + 1][kV];
@@ -306,7 +314,7 @@ __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__r
 // consecutive samples: lane l reads sample l of the chunk (one coalesced 512 B
 // read), draws that sample's negatives and learning rate, and the wave then
 // walks the 64 samples in order, fetching each one's ids from the owning lane.
-template <int kV, int kK, int kCoherence>
+template <int kV, int kK, int kCoherence, bool kFull>
 __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
 #pragma unroll
             for (int k = 0; k < kK; ++k) rows[k + 1] = lane_value(neg[k], i);
             const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
-            sgns_step<kV, kK, kCoherence>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane, a.dim);
+            sgns_step<kV, kK, kCoherence, kFull>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane, a.dim);
         }
     }
 }
@@ -342,10 +350,10 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
 // Update of a row that is not held in registers: row += total * other.  Atomic adds keep
 // every concurrent update; the plain variant writes back loaded + total * other and can
 // lose an update that another wave makes between this wave's load and store.
-template <int kV, int kCoherence>
+template <int kV, int kCoherence, bool kFull>
 __device__ __forceinline__ void remote_update(float *row, int lane, uint32_t D, bool warm, float total,
                                               const float (&other)[kV], const float (&loaded)[kV]) {
-    using Io = RowIo<kV, kCoherence>;
+    using Io = RowIo<kV, kCoherence, kFull>;
     if (kCoherence == kAtomicAgent || (kCoherence == kMixed && warm)) {
         float d[kV];
 #pragma unroll
@@ -396,18 +404,10 @@ __device__ __forceinline__ void sort_tile(uint32_t *word) {
     }
 }
 
-// Wave-uniform description of one sample of a sorted tile.  Its rows are numbered
-// 0 = vertex[u], 1 = context[v], 2 + k = context[negative k].
-template <int kK>
-struct TileSample {
-    uint32_t id[kK + 2];  // u, v, negatives
-    uint32_t warm;        // bit j: row j is warm
-    uint32_t held;        // number of the stationary row
-    float lr;
-    float *stationary;    // address of the stationary row
-};
+// bit of the pair of context rows j1 < j2 (rows 1 .. K + 1 of a sample) in a sample's `same` word
+__host__ __device__ constexpr int pair_bit(int j1, int j2) { return (j1 - 1) * 6 + (j2 - 1); }
 
-template <int kV, int kK, int kCoherence, int kTile>
+template <int kV, int kK, int kCoherence, int kTile, bool kFull>
 __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     const uint32_t D = a.dim;
     // One sort word per sample.  On top, 14 bits for its stationary row: the matrix, then either
@@ -424,9 +424,26 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
     // samples whose gathers are in flight together: bounded by the registers their rows take
-    constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
-    using Io = RowIo<kV, kCoherence>;
+    constexpr int kBatch = kV * (kK + 1) <= 4 ? GV_TUNE_BATCH : (kV * (kK + 1) <= 12 ? 2 : 1);
+    // A held row trades with memory every four samples where four samples are gathered at once, every two
+    // where rows are so long that one or two samples fill the registers: there an exchange is a small part of
+    // a sample's traffic, and the shorter interval halves how far the run's scores lag behind the other
+    // holders of the row (measured on d = 512, K = 5: distance to the sequential trajectory after 4 pools
+    // -0.33 % -> -0.10 % in loss at 3 % more time).
+    constexpr uint32_t kExchangeEvery = kBatch >= 4 ? 4u : 2u;
+    constexpr int kRows = kK + 2;  // rows of a sample: 0 = vertex[u], 1 = context[v], 2 + k = context[negative k]
+    constexpr uint32_t kNoRow = 0xFFFFFFFFu;  // never a node id (ids are below n <= 2^31)
+    // layout of a sample's flag word in the walk: 3 bits stationary row number, kRows warm bits, kRows
+    // register-copy bits, 2 kBatch - 1 clash bits, and (K = 1 only) the one same-row bit
+    constexpr uint32_t kWarmShift = 3, kTakesShift = kWarmShift + kRows, kClashShift = kTakesShift + kRows,
+                       kSameShift = kClashShift + 2 * kBatch - 1;
+    static_assert(kSameShift < 32, "flag word");
+    using Io = RowIo<kV, kCoherence, kFull>;
     __shared__ uint32_t s_word[kTile];
+#ifdef GV_TUNE_LDS_PAD
+    __shared__ uint32_t s_pad[GV_TUNE_LDS_PAD / 4];
+    if (a.count == 0xFFFFFFFFu) s_pad[threadIdx.x] = 1u;  // keeps the padding allocated
+#endif
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
@@ -492,6 +509,9 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 
         float *held = nullptr;   // address of the row kept in y[]
         bool held_warm = true;   // its merge must not lose concurrent updates
+        uint32_t since_exchange = 0;  // samples of the current run since memory last saw the held row
+        // the held row as (matrix, id), for the lane-parallel clash tests of the next chunk; kNoRow: none
+        uint32_t carried_id = kNoRow, carried_is_vertex = 0u;
         float y[kV], moved[kV];
 #pragma unroll
         for (int j = 0; j < kV; ++j) y[j] = moved[j] = 0.0f;
@@ -508,89 +528,152 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
         };
 
         for (uint32_t base = wave_in_group * kPerWave; base < (wave_in_group + 1) * kPerWave; base += kWave) {
+            // ---- per chunk, lane l works out everything about sample l of the chunk, so that the walk
+            // below only has to fetch ready-made scalars from the owning lane (the scalar unit of a
+            // compute unit is shared by its four SIMDs and is what this kernel runs out of first).
             const uint32_t word = s_word[base + lane];
             const bool mine = word != kSkip;
             const uint32_t pos = tile_base + ((word >> 2) & ((1u << kSlotBits) - 1u));
             const uint32_t *record = a.records + (size_t)pos * kRecord;
-            const uint2 p = mine ? make_uint2(record[0], record[1]) : make_uint2(0u, 0u);
-            const uint64_t g = a.first_g + pos;
-            uint32_t neg[kK];
+            uint32_t id[kRows];  // u, v, negatives
+            id[0] = mine ? record[0] : 0u;
+            id[1] = mine ? record[1] : 0u;
 #pragma unroll
-            for (int k = 0; k < kK; ++k) neg[k] = mine ? record[2 + k] : 0u;
+            for (int k = 0; k < kK; ++k) id[2 + k] = mine ? record[2 + k] : 0u;
             // bit j: row j of the sample is warm (u and v from the sort word, the negatives from the record)
             const uint32_t warm = (word & 3u) | (mine ? record[2 + kK] << 2 : 0u);
-            const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
+            const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + pos, a.total);
+            const uint32_t h = (word >> 15) & 7u;  // number of the stationary row
+            uint32_t stationary_id = id[0];
+#pragma unroll
+            for (int j = 1; j < kRows; ++j)
+                if (h == (uint32_t)j) stationary_id = id[j];
+            const uint32_t is_vertex = h == 0u ? 1u : 0u;
+            // bit j: row j is the stationary row, or the same context row again (a row can be named twice in
+            // a sample: positive and negative, or two negatives): its value is the register copy
+            uint32_t takes = 1u << h;
+#pragma unroll
+            for (int j = 1; j < kRows; ++j) takes |= (h != 0u && id[j] == stationary_id ? 1u : 0u) << j;
+            // bit pair_bit(j1, j2): context rows j1 < j2 of the sample are the same row
+            uint32_t same = 0u;
+#pragma unroll
+            for (int j1 = 1; j1 < kRows; ++j1)
+#pragma unroll
+                for (int j2 = j1 + 1; j2 < kRows; ++j2) same |= (id[j1] == id[j2] ? 1u : 0u) << pair_bit(j1, j2);
+            // Clash bits.  The walk gathers up to kBatch samples at once.  A sample must not be gathered
+            // while this wave still owes memory an update of one of its rows: a row that an earlier sample of
+            // the batch names, or the row held when the batch starts -- unless that row is the held row simply
+            // continuing from sample to sample.  It would read the row as it was before the wave's own
+            // update, and under a store policy write the stale value back over it.
+            //   bit d - 1           (d < kBatch):  a row of this sample is a row of the sample d places before
+            //   bit kBatch - 1 + d - 1 (d <= kBatch): a row of this sample is the stationary row of that sample
+            // The row held when the chunk starts stands in for "the sample before sample 0".
+            uint32_t clash = 0u;
+#ifndef GV_TUNE_NOCLASH
+#define GV_TUNE_NOCLASH 0
+#endif
+            if constexpr (kCoherence != kAtomicAgent && GV_TUNE_NOCLASH != 1) {
+                auto from_before = [&](uint32_t x, int d) {  // x of the lane d places down
+                    return (uint32_t)__builtin_amdgcn_ds_bpermute((lane - d) * 4, (int)x);
+                };
+                // run[d]: this sample and the d before it all have the same stationary row
+                const uint32_t prev_id = lane >= 1 ? from_before(stationary_id, 1) : carried_id;
+                const uint32_t prev_is_vertex = lane >= 1 ? from_before(is_vertex, 1) : carried_is_vertex;
+                const uint32_t same_as_before = prev_id == stationary_id && prev_is_vertex == is_vertex ? 1u : 0u;
+                uint32_t run[kBatch + 1];
+                run[0] = 1u;
+#pragma unroll
+                for (int d = 1; d <= kBatch; ++d)
+                    run[d] = run[d - 1] & (d == 1 ? same_as_before : (lane >= d - 1 ? from_before(same_as_before, d - 1) : 0u));
+#pragma unroll
+                for (int d = 1; d <= kBatch; ++d) {
+                    // the stationary row of the sample d before (the carried row for the sample "before sample 0")
+                    const bool real = lane >= d;
+                    const uint32_t their_stationary = real ? from_before(stationary_id, d) : (lane == d - 1 ? carried_id : kNoRow);
+                    const uint32_t their_is_vertex = real ? from_before(is_vertex, d) : carried_is_vertex;
+                    bool names_their_stationary = false;
+#pragma unroll
+                    for (int j = 0; j < kRows; ++j)
+                        names_their_stationary |= id[j] == their_stationary && (j == 0) == (their_is_vertex != 0u) &&
+                                                  !(run[d] != 0u && h == (uint32_t)j);
+                    clash |= (names_their_stationary && their_stationary != kNoRow ? 1u : 0u) << (kBatch - 1 + d - 1);
+                    if (d < kBatch) {
+                        uint32_t theirs[kRows];
+#pragma unroll
+                        for (int j = 0; j < kRows; ++j) theirs[j] = from_before(id[j], d);
+                        const uint32_t their_h = from_before(h, d);
+                        bool shares = id[0] == theirs[0] && !(run[d] != 0u && h == 0u && their_h == 0u);
+#pragma unroll
+                        for (int j1 = 1; j1 < kRows; ++j1)
+#pragma unroll
+                            for (int j2 = 1; j2 < kRows; ++j2)
+                                shares |= id[j1] == theirs[j2] &&
+                                          !(run[d] != 0u && h == (uint32_t)j1 && their_h == (uint32_t)j2);
+                        clash |= (real && shares ? 1u : 0u) << (d - 1);
+                    }
+                }
+            }
+            // one word for the walk: stationary row number, warm bits, register-copy bits, clash bits
+            const uint32_t flags = h | warm << kWarmShift | takes << kTakesShift | clash << kClashShift |
+                                   (kK == 1 ? ((same >> pair_bit(1, 2)) & 1u) << kSameShift : 0u);
             // sorted order puts the skipped slots last: the first one ends this wave's work
             const uint64_t live = __ballot(mine);
             const uint32_t in_chunk = live == ~0ull ? (uint32_t)kWave : (uint32_t)__builtin_ctzll(~live);
 
-            auto row_address = [&](const TileSample<kK> &s, int j) {
-                return j == 0 ? a.vertex + (size_t)s.id[0] * D : a.context + (size_t)s.id[j] * D;
+            // ---- the walk: wave-uniform copies of one sample's scalars
+            struct Sample {
+                float *row[kRows];   // addresses of vertex[u], context[v], context[negative k]
+                float *stationary;   // the one of them that is kept in registers
+                uint32_t flags, same;
+                float lr;
             };
             auto decode = [&](uint32_t i) {
-                TileSample<kK> s;
-                s.id[0] = lane_value(p.x, i);
-                s.id[1] = lane_value(p.y, i);
+                Sample s;
+                s.flags = lane_value(flags, i);
+                s.row[0] = a.vertex + (size_t)lane_value(id[0], i) * D;
 #pragma unroll
-                for (int k = 0; k < kK; ++k) s.id[2 + k] = lane_value(neg[k], i);
-                s.warm = lane_value(warm, i);
+                for (int j = 1; j < kRows; ++j) s.row[j] = a.context + (size_t)lane_value(id[j], i) * D;
+                const size_t stationary_at = (size_t)lane_value(stationary_id, i) * D;
+                s.stationary = (s.flags & 7u) == 0u ? a.vertex + stationary_at : a.context + stationary_at;
+                s.same = kK > 1 ? lane_value(same, i) : ((s.flags >> kSameShift) & 1u) << pair_bit(1, 2);
                 s.lr = __uint_as_float(lane_value(__float_as_uint(lr), i));
-                s.held = (lane_value(word, i) >> 15) & 7u;
-                s.stationary = row_address(s, 0);
-#pragma unroll
-                for (int j = 1; j <= kK + 1; ++j)
-                    if (s.held == (uint32_t)j) s.stationary = row_address(s, j);
                 return s;
             };
-            // Issue the loads of a sample: its K+1 rows other than the stationary one, in row order
-            // (other[i] is row i if i comes before the stationary row, else row i + 1), and the
+            // Issue the loads of a sample: every row whose value is not the register copy, and the
             // stationary row when that is not the row the wave will be holding at that point.
-            auto fetch = [&](const TileSample<kK> &s, const float *held_then, float (&other)[kK + 1][kV],
-                             float (&fresh)[kV]) {
+            auto fetch = [&](const Sample &s, const float *held_then, float (&loaded)[kRows][kV], float (&fresh)[kV]) {
 #pragma unroll
-                for (int i = 0; i <= kK; ++i)
-                    Io::load((uint32_t)i < s.held ? row_address(s, i) : row_address(s, i + 1), lane, D, other[i]);
+                for (int j = 0; j < kRows; ++j)
+                    if (!((s.flags >> (kTakesShift + j)) & 1u)) Io::load(s.row[j], lane, D, loaded[j]);
                 if (s.stationary != held_then) Io::load(s.stationary, lane, D, fresh);
             };
 
             // One sample (same arithmetic as sgns_step): switch the held row if needed, then all
             // scores and coefficients from the rows as they are before the sample, then the updates:
             // into the register copy for the held row, to memory for the others.
-            auto train_one = [&](const TileSample<kK> &cur, float (&other)[kK + 1][kV], const float (&fresh)[kV]) {
+            auto train_one = [&](const Sample &cur, const float (&loaded)[kRows][kV], const float (&fresh)[kV]) {
                 if (cur.stationary != held) {
                     flush();
 #pragma unroll
-                    for (int j = 0; j < kV; ++j) {
-                        y[j] = fresh[j];
-                        moved[j] = 0.0f;
+                    for (int e = 0; e < kV; ++e) {
+                        y[e] = fresh[e];
+                        moved[e] = 0.0f;
                     }
                     held = cur.stationary;
-                    held_warm = ((cur.warm >> cur.held) & 1u) != 0;
+                    held_warm = ((cur.flags >> kWarmShift >> (cur.flags & 7u)) & 1u) != 0;
                 }
                 const float lrw = cur.lr * a.neg_weight;
-                const bool vertex_held = cur.held == 0u;
-                uint32_t held_id = cur.id[1];  // id of the held context row (unused when vertex[u] is held)
-#pragma unroll
-                for (int j = 2; j <= kK + 1; ++j)
-                    if (cur.held == (uint32_t)j) held_id = cur.id[j];
-
-                // x = vertex[u]; c[j - 1] = context row j, taken from the register copy when it is the
-                // held row (a row can be named twice in a sample: positive and negative, or two negatives)
+                // x = vertex[u], c[k] = context row 1 + k: the register copy where the flags say so
                 float x[kV], c[kK + 1][kV];
-                bool is_held[kK + 1];
+                bool held_row[kRows];
 #pragma unroll
-                for (int e = 0; e < kV; ++e) x[e] = vertex_held ? y[e] : other[0][e];
+                for (int j = 0; j < kRows; ++j) held_row[j] = ((cur.flags >> (kTakesShift + j)) & 1u) != 0;
 #pragma unroll
-                for (int j = 1; j <= kK + 1; ++j) {
-                    is_held[j - 1] = !vertex_held && cur.id[j] == held_id;
-                    const bool before = (uint32_t)j < cur.held;  // its place in other[]: j before the held row, else j - 1
-                    const int at = j <= kK ? j : kK;             // (the last row is never before the held one)
+                for (int e = 0; e < kV; ++e) x[e] = held_row[0] ? y[e] : loaded[0][e];
 #pragma unroll
-                    for (int e = 0; e < kV; ++e) {
-                        const float value = before ? other[at][e] : other[j - 1][e];
-                        c[j - 1][e] = is_held[j - 1] ? y[e] : value;
-                    }
-                }
+                for (int k = 0; k <= kK; ++k)
+#pragma unroll
+                    for (int e = 0; e < kV; ++e) c[k][e] = held_row[1 + k] ? y[e] : loaded[1 + k][e];
                 float coef[kK + 1];
 #pragma unroll
                 for (int k = 0; k <= kK; ++k) {
@@ -605,12 +688,13 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                 for (int k = 0; k <= kK; ++k) {
                     bool repeated = false;
 #pragma unroll
-                    for (int k2 = 0; k2 < k; ++k2) repeated |= cur.id[1 + k2] == cur.id[1 + k];
+                    for (int k2 = 0; k2 < k; ++k2) repeated |= ((cur.same >> pair_bit(1 + k2, 1 + k)) & 1u) != 0;
                     if (repeated) continue;
                     float total = coef[k];
 #pragma unroll
-                    for (int k2 = k + 1; k2 <= kK; ++k2) total += cur.id[1 + k2] == cur.id[1 + k] ? coef[k2] : 0.0f;
-                    if (is_held[k]) {
+                    for (int k2 = k + 1; k2 <= kK; ++k2)
+                        total += (cur.same >> pair_bit(1 + k, 1 + k2)) & 1u ? coef[k2] : 0.0f;
+                    if (held_row[1 + k]) {
 #pragma unroll
                         for (int e = 0; e < kV; ++e) {
                             const float d = total * x[e];
@@ -618,8 +702,8 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                             moved[e] += d;
                         }
                     } else {
-                        remote_update<kV, kCoherence>(a.context + (size_t)cur.id[1 + k] * D, lane, D,
-                                                      (cur.warm >> (k + 1)) & 1u, total, x, c[k]);
+                        remote_update<kV, kCoherence, kFull>(cur.row[1 + k], lane, D,
+                                                             (cur.flags >> (kWarmShift + 1 + k)) & 1u, total, x, c[k]);
                     }
                 }
                 float dx[kV];
@@ -630,44 +714,76 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                     for (int k = 0; k <= kK; ++k) acc = fmaf(coef[k], c[k][e], acc);
                     dx[e] = acc;
                 }
-                if (vertex_held) {
+                if (held_row[0]) {
 #pragma unroll
                     for (int e = 0; e < kV; ++e) {
                         y[e] += dx[e];
                         moved[e] += dx[e];
                     }
                 } else {
-                    remote_update<kV, kCoherence>(a.vertex + (size_t)cur.id[0] * D, lane, D, cur.warm & 1u, 1.0f, dx, x);
+                    remote_update<kV, kCoherence, kFull>(cur.row[0], lane, D, (cur.flags >> kWarmShift) & 1u, 1.0f, dx, x);
                 }
             };
 
-            // Samples go through in batches of kBatch: all gathers of a batch are issued first,
+            // Samples go through in batches of up to kBatch: all gathers of a batch are issued first,
             // then the samples are computed one after the other (a later sample of the batch sees
             // the held row as the earlier ones left it), so one memory round trip serves kBatch
-            // samples instead of one.
-            for (uint32_t i0 = 0; i0 < in_chunk; i0 += kBatch) {
-                TileSample<kK> batch[kBatch];
-                float other[kBatch][kK + 1][kV], fresh[kBatch][kV];
-                // A run that goes on past four samples first trades with memory: its change so far is
-                // added and the register copy takes in what other waves added meanwhile, so a held
-                // row is never more than four samples behind the other holders of that row.
-                if (held && (i0 & 3u) == 0 && held == decode(i0).stationary &&
-                    (kCoherence == kAtomicAgent || (kCoherence == kMixed && held_warm)))
+            // samples instead of one.  A sample whose clash bits name a sample of the batch, or the row
+            // held when the batch starts, is left for the next batch (and that held row is merged first).
+            for (uint32_t i0 = 0; i0 < in_chunk;) {
+                Sample batch[kBatch];
+                float loaded[kBatch][kRows][kV], fresh[kBatch][kV];
+                batch[0] = decode(i0);
+                // A run that goes on trades with memory before its staleness would pass kExchangeEvery
+                // samples: its change so far is added and the register copy takes in what other waves
+                // added meanwhile, so a held row is never more than that many samples behind the other
+                // holders of that row.
+                if (held && held == batch[0].stationary && since_exchange > 0u &&
+                    since_exchange + kBatch > kExchangeEvery &&
+                    (kCoherence == kAtomicAgent || (kCoherence == kMixed && held_warm))) {
                     Io::exchange(held, lane, D, moved, y);
+                    since_exchange = 0;
+                }
+                if constexpr (kCoherence != kAtomicAgent) {
+                    if (GV_TUNE_NOCLASH != 2 && held && ((batch[0].flags >> (kClashShift + kBatch - 1)) & 1u)) {
+                        flush();
+                        held = nullptr;
+                    }
+                }
                 const float *then = held;
+                uint32_t taken = 0;
 #pragma unroll
                 for (int b = 0; b < kBatch; ++b) {
 #pragma unroll
-                    for (int j = 0; j < kV; ++j) fresh[b][j] = 0.0f;
-                    if (i0 + b < in_chunk) {
-                        batch[b] = decode(i0 + b);
-                        fetch(batch[b], then, other[b], fresh[b]);
+                    for (int e = 0; e < kV; ++e) fresh[b][e] = 0.0f;
+                    if (taken == (uint32_t)b && i0 + b < in_chunk) {
+                        if (b > 0) {
+                            batch[b] = decode(i0 + b);
+                            // earlier samples of the batch (b places at most), and the row held at its start
+                            const uint32_t kEarlier = ((1u << b) - 1u) | 1u << (kBatch - 1 + b);
+                            if (GV_TUNE_NOCLASH != 2 && kCoherence != kAtomicAgent && ((batch[b].flags >> kClashShift) & kEarlier)) continue;
+                        }
+                        fetch(batch[b], then, loaded[b], fresh[b]);
                         then = batch[b].stationary;
+                        taken = b + 1;
                     }
                 }
+                // All gathers of the batch are awaited here, once, whichever of them were issued: the
+                // counter of outstanding vector memory operations also counts stores and atomic adds, so a
+                // wait placed between the samples would sit out the previous sample's updates as well.
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), the other counters untouched
 #pragma unroll
                 for (int b = 0; b < kBatch; ++b)
-                    if (i0 + b < in_chunk) train_one(batch[b], other[b], fresh[b]);
+                    if ((uint32_t)b < taken) {
+                        since_exchange = batch[b].stationary == held ? since_exchange + 1u : 1u;
+                        train_one(batch[b], loaded[b], fresh[b]);
+                    }
+                i0 += taken;
+            }
+            // what the next chunk's clash tests compare with: the row held now
+            if (in_chunk > 0u) {
+                carried_id = lane_value(stationary_id, in_chunk - 1u);
+                carried_is_vertex = lane_value(is_vertex, in_chunk - 1u);
             }
             if (in_chunk < (uint32_t)kWave) break;
         }
@@ -679,7 +795,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 // Deterministic mode: wave i trains sample i of a batch whose samples share no
 // vertex row and no context row (Def. 1, Sec. 3.2: such samples commute), so the
 // result equals the sequential order up to fp32 rounding inside a sample.
-template <int kV, int kK>
+template <int kV, int kK, bool kFull>
 __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t i = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
@@ -694,7 +810,7 @@ __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
 #pragma unroll
     for (int k = 0; k < kK; ++k) rows[k + 1] = a.negatives[(size_t)i * kK + k];
     const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + i, a.total);
-    sgns_step<kV, kK, kPlain>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim);
+    sgns_step<kV, kK, kPlain, kFull>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim);
 }
 
 // ---------------------------------------------------------------------------
@@ -852,7 +968,7 @@ __global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
     uint64_t t_global = w * a.per_walk;
     for (uint32_t i = 0; i <= L; ++i) {
         const uint32_t from = s_path[i][threadIdx.x];
-        for (uint32_t j = i + 1; j <= L && j <= i + s; ++j, ++t_global) {
+        for (uint32_t j = i + 1; j <= L && j - i <= s; ++j, ++t_global) {
             if (t_global >= a.count) return;
             uint64_t at = t_global;
             if (a.pseudo_shuffle) {
@@ -867,21 +983,13 @@ __global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
     }
 }
 
-uint32_t env_u32(const char *name, uint32_t fallback) {
-    const char *s = getenv(name);
-    if (!s || !*s) return fallback;
-    const long v = strtol(s, nullptr, 10);
-    return v > 0 ? (uint32_t)v : fallback;
-}
-
 // Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy; each
 // wave strides over the chunks.  The number of samples in flight is also kept below
 // |V|/32: every in-flight sample works on values that miss the updates of the others
 // (Def. 1, Sec. 3.2: the order of updates stops mattering only while concurrent samples
 // rarely share rows), and a small graph gains nothing from thousands of waves.
-// GV_GRID_BLOCKS overrides the upper limit for tuning sweeps.
 uint32_t hogwild_blocks(uint32_t count, uint32_t n) {
-    static const uint32_t max_blocks = env_u32("GV_GRID_BLOCKS", 256u * 8u);
+    constexpr uint32_t max_blocks = 256u * 8u;
     const uint32_t chunks = (count + kWave - 1) / kWave;
     const uint32_t wanted = (chunks + (kBlock / kWave) - 1) / (kBlock / kWave);
     const uint32_t by_rows = (n / 32u) / (kBlock / kWave);
@@ -890,34 +998,39 @@ uint32_t hogwild_blocks(uint32_t count, uint32_t n) {
     return blocks;
 }
 
-template <int kV, int kK>
-hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
-    const uint32_t blocks = hogwild_blocks(a.count, a.n);
-    if (blocks == 0) return hipSuccess;
+// A row that fills its lanes exactly (d = 64, 128, 256, 512) takes the kernels without per-lane bounds tests.
+template <int kV, int kK, bool kFull>
+hipError_t launch_hogwild_vkf(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
     switch (coherence) {
         case kAgent:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAgent, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
         case kAtomicAgent:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
-            break;
-        case kMixed:  // the per-row choice exists in the grouped kernel only
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        case kMixed:  // the per-row choice exists in the tiled kernel only
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
         default:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
     }
     return hipGetLastError();
 }
 
-template <int kV, int kK, int kTile>
+template <int kV, int kK>
+hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t stream) {
+    const uint32_t blocks = hogwild_blocks(a.count, a.n);
+    if (blocks == 0) return hipSuccess;
+    return a.dim == (uint32_t)(kWave * kV) ? launch_hogwild_vkf<kV, kK, true>(a, coherence, blocks, stream)
+                                           : launch_hogwild_vkf<kV, kK, false>(a, coherence, blocks, stream);
+}
+
+template <int kV, int kK, int kTile, bool kFull>
 hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
     if (coherence == kAgent)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
     else if (coherence == kMixed)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
     else
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -931,16 +1044,20 @@ hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t s
     // strides over the tiles.
     const uint32_t limit = hogwild_blocks(a.count, a.n);
     const uint32_t tiles = (a.count + tile - 1) / tile;
-    static const uint32_t fixed_grid = env_u32("GV_GRID_BLOCKS", 0u);
-    const uint32_t blocks = (limit >= 2048u && fixed_grid == 0u) || limit > tiles ? tiles : limit;
-    return launch_tiled_vkt<kV, kK, (int)tile>(a, coherence, blocks, stream);
+    uint32_t blocks = limit >= 2048u || limit > tiles ? tiles : limit;
+    if (GV_TUNE_GRID > 0 && blocks > (uint32_t)GV_TUNE_GRID) blocks = GV_TUNE_GRID;
+    return a.dim == (uint32_t)(kWave * kV) ? launch_tiled_vkt<kV, kK, (int)tile, true>(a, coherence, blocks, stream)
+                                           : launch_tiled_vkt<kV, kK, (int)tile, false>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
 hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
     const uint32_t blocks = (a.count + (kBlock / kWave) - 1) / (kBlock / kWave);
-    hipLaunchKernelGGL((k_train_batch<kV, kK>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    if (a.dim == (uint32_t)(kWave * kV))
+        hipLaunchKernelGGL((k_train_batch<kV, kK, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_train_batch<kV, kK, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -12,6 +12,13 @@ checkpoints are written as they are reached, and the test uses those that exist)
     python tests/golden/make_long_run_reference.py c2
     python tests/golden/make_long_run_reference.py c3
     python tests/golden/make_long_run_reference.py c4
+
+A second argument replaces the training seed (the key of the negative-sampling stream) and writes
+long_run_<name>_seed<seed>.txt: the same run with other negatives.  How far two such runs of the
+oracle lie apart is the scale against which the asynchronous trainer's distance is read:
+
+    python tests/golden/make_long_run_reference.py c2 4321
+    python tests/golden/make_long_run_reference.py c3 4321
 """
 import os
 import sys
@@ -47,8 +54,11 @@ def pool_of(offsets, adj, seed, first_walk, count, s):
 
 def main():
     name = sys.argv[1] if len(sys.argv) > 1 else "c2"
-    s = SETUPS[name]
+    s = dict(SETUPS[name])
     out_path = os.path.join(HERE, f"long_run_{name}.txt")
+    if len(sys.argv) > 2:
+        s["train_seed"] = int(sys.argv[2])
+        out_path = os.path.join(HERE, f"long_run_{name}_seed{s['train_seed']}.txt")
     n, src, dst = W.make_graph(s["graph"])
     tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
     deg = W.degrees(n, tr_s, tr_d)

@@ -409,6 +409,79 @@ def test_single_samples_with_repeated_rows(gv, policy):
                 assert np.abs(got - ref).max() <= 1e-4 * step + 1e-7, (pattern, g, u, v)
 
 
+@pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
+@pytest.mark.parametrize("shape", ["shared context", "shared vertex", "interleaved runs"])
+def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape):
+    """Four samples that end up next to each other in one wave and share a cold row (one that the store
+    policies update with plain device-scope stores).  The wave gathers several samples at once, so a later one
+    must not be gathered before the earlier ones' updates of the shared row are out: nothing that the wave
+    itself wrote may be lost.  The rows that multiply the shared row have disjoint supports, so its result
+    does not depend on the order of the samples: it must equal the sequential oracle's.
+      shared context    (u_i, R): context[R] is fetched per sample and written back per sample
+      shared vertex     (R, v_i): vertex[R] is the row the wave keeps in registers through the run
+      interleaved runs  (a, .), (b, .), (a, .), (b, .) with a and b in one sort group: the register copy of
+                        vertex[a] is written back when b takes over, and must be re-read when a returns
+    Uniform degrees and ids beyond the ranked range: every row is cold and vertex[u] is the row kept."""
+    n, d, K, w, seed, T, count = 100_000, 128, 1, 5.0, 41, 1000, 4
+    deg = np.ones(n, dtype=np.uint32)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    rng = np.random.default_rng(7)
+    negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias)[:, 0]
+    free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), negs)
+    if shape == "shared context":
+        shared = [free[0]]
+        pool = np.stack([free[1:1 + count], np.full(count, shared[0], dtype=np.uint32)], axis=1)
+        blocks_in, check = ("vertex", free[1:1 + count]), "context"
+    elif shape == "shared vertex":
+        shared = [free[0]]
+        pool = np.stack([np.full(count, shared[0], dtype=np.uint32), free[1:1 + count]], axis=1)
+        blocks_in, check = ("context", np.concatenate([free[1:1 + count], negs])), "vertex"
+    else:
+        group = ((free.astype(np.uint64) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(20)
+        values, first, counts = np.unique(group, return_index=True, return_counts=True)
+        g0 = values[counts >= 2][0]
+        a, b = free[group == g0][:2]  # two nodes whose samples the tile sort puts in one group
+        shared = [a, b]
+        rest = np.setdiff1d(free, shared)[:count]
+        pool = np.stack([np.array([a, b, a, b], dtype=np.uint32), rest], axis=1)
+        blocks_in, check = ("context", np.concatenate([rest, negs])), "vertex"
+    vertex, context = random_embeddings(n, d, seed=13)
+    target = vertex if blocks_in[0] == "vertex" else context
+    for j, r in enumerate(blocks_in[1]):  # row j of the multiplying rows lives on coordinates 8j .. 8j+7
+        target[r] = 0.0
+        target[r, 8 * j:8 * j + 8] = rng.uniform(0.5, 1.0, size=8)
+    assert np.unique(blocks_in[1]).size == len(blocks_in[1])
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, T, seed, policy)
+    ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, T, seed)
+    got, ref, start = (got_v, ref_v, vertex) if check == "vertex" else (got_c, ref_c, context)
+    for r in shared:
+        step = np.abs(ref[r] - start[r]).max()
+        assert step > 1e-3
+        assert np.abs(got[r] - ref[r]).max() <= 1e-4 * step + 1e-7, (shape, policy, int(r))
+
+
+def test_schedule_is_chosen_from_the_graph(gv, tiny_graph):
+    """GV_SCHEDULE_AUTO: a graph with rows that concurrent samples share is trained with the tiled schedule, one
+    without (4*10^5 nodes of equal degree: each is named by 2 of 8192 samples in flight with probability 0.04) in
+    pool order."""
+    g = tiny_graph
+    rng = np.random.default_rng(1)
+    flat_n = 400_000
+    cases = ((g["deg"], np.stack([g["src"][:5000], g["dst"][:5000]], axis=1), True),
+             (np.full(flat_n, 3, dtype=np.uint32), rng.integers(flat_n, size=(5000, 2)).astype(np.uint32), False))
+    for deg, pool, tiled in cases:
+        with context_for(gv, dim=32, num_neg=1, total_samples=10_000, pool_capacity=5000) as ctx:
+            gv.gv_set_degrees(ctx, deg)
+            gv.gv_build_alias(ctx, 0.75)
+            gv.gv_init_embeddings(ctx, 1)
+            gv.gv_push_pool(ctx, pool)
+            gv.gv_train_pool(ctx)
+            gv.gv_sync(ctx)
+            stats = gv.gv_get_stats(ctx)
+            assert (stats["tiled_launches"] == 1) == tiled and (stats["warm_rows"] > 0) == tiled
+            assert np.abs(gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, deg.size, 32)).max() > 0
+
+
 def evaluation_loss(deg, vertex, context, eval_pool, K, w):
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     return oracle.loss(vertex, context, eval_pool, K=K, w=w, seed=99, thresh=thresh, alias=alias)
@@ -625,6 +698,108 @@ def test_streamed_pools_equal_resident_pools(gv, tiny_graph):
         assert np.array_equal(v, results[0][0]) and np.array_equal(c, results[0][1])
     ref_v, ref_c = run_oracle(g["deg"], K, w, pools, vertex, context, total, seed)
     assert rel_errors(results[0][0], ref_v)[0] <= 1e-5 and rel_errors(results[0][1], ref_c)[0] <= 1e-5
+
+
+def test_ring_of_pinned_slots_is_cycled_without_refilling(gv, tiny_graph):
+    """pool_slots = 4: four pools are written into the slots once; acquiring and pushing the slots again,
+    without touching their contents, trains the same pools again.  Equal to pushing the same sequence from
+    plain host arrays (deterministic mode: bit for bit)."""
+    g = tiny_graph
+    d, K, w, seed, R, P = 64, 1, 5.0, 5, 4, 20_000
+    pools = [oracle.augment(300 + r, g["offsets"], g["adj"], 40, 5, P - 100 * r, shuffle_seed=r)[0] for r in range(R)]
+    order = list(range(R)) * 3
+    vertex, context = random_embeddings(g["n"], d, seed=9)
+    results = []
+    for how in ("host", "ring"):
+        with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_DETERMINISTIC,
+                         total_samples=len(order) * P, seed=seed, pool_capacity=P, lr0=LR0, pool_slots=R) as ctx:
+            gv.gv_set_degrees(ctx, g["deg"])
+            gv.gv_build_alias(ctx, 0.75)
+            gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+            gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+            if how == "host":
+                for r in order:
+                    gv.gv_push_pool(ctx, pools[r])
+                    gv.gv_train_pool(ctx)
+            else:
+                addresses = []
+                for turn, r in enumerate(order):
+                    slot = gv.gv_acquire_pool_slot(ctx, P)
+                    if turn < R:  # first time round: fill
+                        slot[:pools[r].shape[0]] = pools[r]
+                        addresses.append(slot.ctypes.data)
+                    else:         # afterwards the ring hands the same slots out again, contents kept
+                        assert slot.ctypes.data == addresses[r]
+                        assert np.array_equal(slot[:pools[r].shape[0]], pools[r])
+                    gv.gv_push_pool(ctx, slot, pools[r].shape[0])
+                    if turn >= 2:
+                        gv.gv_train_pool(ctx)  # keep three pools in flight
+                for _ in range(2):
+                    gv.gv_train_pool(ctx)
+            gv.gv_sync(ctx)
+            assert gv.gv_get_stats(ctx)["pools_trained"] == len(order)
+            results.append((gv.gv_read_embeddings(ctx, gv.GV_VERTEX, g["n"], d),
+                            gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, g["n"], d)))
+    assert np.array_equal(results[0][0], results[1][0]) and np.array_equal(results[0][1], results[1][1])
+    assert not np.array_equal(results[0][0], vertex)
+
+
+def test_ring_limits_and_failed_pushes(gv, tiny_graph):
+    g = tiny_graph
+    ok = np.stack([g["src"][:500], g["dst"][:500]], axis=1)
+    with context_for(gv, dim=64, num_neg=1, total_samples=100_000, pool_capacity=1000, pool_slots=3) as ctx:
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, 3)
+        for _ in range(3):
+            gv.gv_push_pool(ctx, ok)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_push_pool(ctx, ok)
+        assert e.value.code == gv.GV_ESTATE  # three pools queued in a ring of three
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_acquire_pool_slot(ctx, 1000)
+        assert e.value.code == gv.GV_ESTATE
+        for _ in range(3):
+            gv.gv_train_pool(ctx)
+        # a push that fails hands its acquired slot back: the ring stays complete
+        for _ in range(5):
+            slot = gv.gv_acquire_pool_slot(ctx, 1000)
+            with pytest.raises(gv.GvError) as e:
+                gv.gv_push_pool(ctx, slot, 1001)
+            assert e.value.code == gv.GV_EINVAL
+        slots = [gv.gv_acquire_pool_slot(ctx, 1000) for _ in range(3)]
+        assert len({s.ctypes.data for s in slots}) == 3
+        for s_ in slots:
+            s_[:500] = ok
+            gv.gv_push_pool(ctx, s_, 500)
+        for _ in range(3):
+            gv.gv_train_pool(ctx)
+        gv.gv_sync(ctx)
+        assert gv.gv_get_stats(ctx)["samples_trained"] == 3000
+
+
+def test_link_prediction_auc_matches_oracle(gv, tiny_graph):
+    """gv_link_prediction_auc against the oracle's cosine + rank statistic, with many exact ties (zero rows
+    score 0 on both sides)."""
+    g = tiny_graph
+    n, d = g["n"], 96
+    rng = np.random.default_rng(12)
+    vertex = (rng.standard_normal((n, d)) * 0.3).astype(np.float32)
+    vertex[rng.integers(n, size=n // 5)] = 0.0
+    a, b = g["src"][:20_000], g["dst"][:20_000]
+    na, nb = W.uniform_negative_pairs(n, 15_000, seed=5)
+    with context_for(gv, dim=d, num_neg=1, total_samples=1, pool_capacity=1) as ctx:
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        got = gv.gv_link_prediction_auc(ctx, a, b, na, nb)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_link_prediction_auc(ctx, a, b, np.array([n], dtype=np.uint32), np.array([0], dtype=np.uint32))
+        assert e.value.code == gv.GV_EINVAL
+    pos, neg = oracle.cosine(vertex, a, b), oracle.cosine(vertex, na, nb)
+    assert np.mean(pos == 0.0) > 0.2  # ties are exercised
+    # fp32 cosines of the device decide the ranks: compare with the oracle's statistic of the same quantities
+    # rounded to fp32 (ties at 0 are exact on both sides), and with its fp64 statistic within rounding noise
+    assert abs(got - oracle.auc(pos, neg)) <= 1e-5
 
 
 def test_errors_are_reported_not_fatal(gv, tiny_graph):
@@ -939,12 +1114,11 @@ def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, name, policy):
     """c2: 32 pools of 2^24 samples (5.4*10^8 samples, learning rate decaying to zero) on the configuration-2
     graph with 1 % of its edges held out; c3: 4 such pools with d = 512 and 5 negatives of weight 1 (the oracle
     needs two minutes per pool there).  Pools are produced on the fly by the library's host producer into the
-    pinned slots.  At the end the evaluation loss must be within 2 % of the oracle's, at the earlier checkpoints
-    of the stored oracle trajectory within 3 %, and no row may have grown beyond twice the oracle's longest row (asynchronous updates
+    pinned slots.  The evaluation loss must be within 2 % of the oracle's at every checkpoint of the stored
+    oracle trajectory, and no row may have grown beyond twice the oracle's longest row (asynchronous updates
     that overshoot show up as a few very long rows well before the loss moves); at the end the
-    link-prediction AUC must match too.  This graph has no structure beyond its degrees, so its AUC measures
-    nothing but how far training has got and drops steeply over the run: it is held to 0.01, the
-    planted-partition test above holds the AUC of a graph that has structure to 0.005."""
+    link-prediction AUC must be within 0.005 of the oracle's (this graph has no structure beyond its degrees, so
+    its AUC measures how far training has got and still falls steeply when the run ends)."""
     s, reference = read_long_run_reference(name)
     n, src, dst = W.make_graph(s["graph"])
     tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
@@ -978,14 +1152,12 @@ def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, name, policy):
                 nc = np.linalg.norm(gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d), axis=1).max()
                 print(f"long run {name} {policy} after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
                       f"longest rows {nv:.2f}/{nc:.2f} vs {ref_nv:.2f}/{ref_nc:.2f}")
-                # 2 % at the end; 3 % on the way, where the learning rate is high and the loss falls fastest
-                # (the default policy has been seen between +1.1 % and +1.7 % after the first pool)
-                assert abs(loss - ref_loss) <= (0.02 if k + 1 == pools else 0.03) * ref_loss
+                assert abs(loss - ref_loss) <= 0.02 * ref_loss
                 assert nv <= 2.0 * ref_nv and nc <= 2.0 * ref_nc
-        auc = oracle.auc(gv.gv_cosine(ctx, te_s, te_d), gv.gv_cosine(ctx, na, nb))
+        auc = gv.gv_link_prediction_auc(ctx, te_s, te_d, na, nb)
         print(f"long run {name} {policy}: auc {auc:.4f} vs {checkpoints[pools][1]:.4f}")
         assert gv.gv_get_stats(ctx)["samples_trained"] == P * pools
-        assert abs(auc - checkpoints[pools][1]) <= 0.01
+        assert abs(auc - checkpoints[pools][1]) <= 0.005
 
 
 def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
@@ -993,8 +1165,9 @@ def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
     edges, 1 % held out, d = 128, K = 1, 4*10^9 samples (238 pools of 2^24, learning rate decaying to zero);
     pools written in HBM by the device producer, default asynchronous policy.  The oracle's trajectory is
     stored (`tests/golden/long_run_c4.txt`, one CPU core for two hours); the evaluation loss must be within
-    2 % at the end and within 3 % at the earlier checkpoints (one of them lies in the middle of the steep drop),
-    the link-prediction AUC of the held-out edges within 0.005 throughout."""
+    2 % at every checkpoint (one of them lies in the middle of the steep drop), the link-prediction AUC of the
+    held-out edges within 0.005 throughout.  The graph has no warm row, so GV_SCHEDULE_AUTO trains it in pool
+    order."""
     import torch
 
     s, reference = read_long_run_reference("c4")
@@ -1028,9 +1201,11 @@ def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
                 ref_loss, ref_auc, ref_nv, ref_nc = checkpoints[k + 1]
                 gv.gv_sync(ctx)
                 loss = gv.gv_eval_loss(ctx, eval_pool, s["eval_seed"])
-                auc = oracle.auc(gv.gv_cosine(ctx, te_s, te_d), gv.gv_cosine(ctx, na, nb))
+                auc = gv.gv_link_prediction_auc(ctx, te_s, te_d, na, nb)
                 print(f"configuration 4 after {k + 1} pools: loss {loss:.4f} vs {ref_loss:.4f}; "
                       f"auc {auc:.4f} vs {ref_auc:.4f}", flush=True)
-                assert abs(loss - ref_loss) <= (0.02 if k + 1 == last else 0.03) * ref_loss
+                assert abs(loss - ref_loss) <= 0.02 * ref_loss
                 assert abs(auc - ref_auc) <= 0.005
-        assert gv.gv_get_stats(ctx)["samples_trained"] == P * last
+        stats = gv.gv_get_stats(ctx)
+        assert stats["samples_trained"] == P * last
+        assert stats["warm_rows"] == 0 and stats["tiled_launches"] == 0  # the default schedule went pool-order
