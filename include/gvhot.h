@@ -184,6 +184,20 @@ int gv_train_pool(gv_ctx *ctx);
  * count <= 2^31.                                                               */
 int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
 
+/* gv_train_device_pool for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it): the same training step, in
+ * asynchronous mode only, with the kernels' per-sample scratch in a static device array of
+ * GV_STATIC_SCRATCH_WORDS 32-bit words (16 MiB, part of the loaded library, held by every GPU
+ * the library runs on until the process ends) instead of a buffer allocated on demand.  The call
+ * allocates nothing, on the device or through any library, and times nothing (gv_stats'
+ * train_kernel_ms does not grow).  GV_EINVAL when count * (K + 3) exceeds
+ * GV_STATIC_SCRATCH_WORDS under the tiled schedule (2^20 samples at K = 1; the pool-order
+ * schedule needs no scratch and takes any count <= 2^31); GV_ESTATE in deterministic mode.
+ * All contexts of one GPU share that GPU's array: launches of one context are ordered on its
+ * stream, but calls of two contexts that overlap on one GPU race on it.                      */
+#define GV_STATIC_SCRATCH_WORDS (1u << 22)
+int gv_train_device_pool_static(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
+
 /* Host producer of a pool (Sec. 3.1, Alg. 2, parallel online augmentation): walk number
  * first_walk + w departs from a node drawn with probability proportional to its degree,
  * takes walk_length uniform steps over the adjacency (host_offsets[n+1], host_adj[] = CSR

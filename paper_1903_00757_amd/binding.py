@@ -17,6 +17,7 @@ GV_COHERENCE_PLAIN, GV_COHERENCE_AGENT, GV_COHERENCE_ATOMIC_AGENT, GV_COHERENCE_
 GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED, GV_SCHEDULE_AUTO = 0, 1, 2
 GV_NEG_WEIGHT_DEFAULT = -1.0
 GV_MAX_POOL_SLOTS = 16
+GV_STATIC_SCRATCH_WORDS = 1 << 22
 GV_SHUFFLE_NONE, GV_SHUFFLE_PSEUDO = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
@@ -26,7 +27,7 @@ EXPORTS = [
     "gv_init_embeddings", "gv_set_embeddings", "gv_read_embeddings", "gv_device_embeddings",
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
     "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
-    "gv_set_adjacency", "gv_augment_device", "gv_auc", "gv_link_prediction_auc",
+    "gv_set_adjacency", "gv_augment_device", "gv_auc", "gv_link_prediction_auc", "gv_train_device_pool_static",
 ]
 
 
@@ -91,6 +92,7 @@ def load():
     L.gv_push_pool.argtypes = [vp, vp, C.c_uint64]
     L.gv_train_pool.argtypes = [vp]
     L.gv_train_device_pool.argtypes = [vp, vp, C.c_uint64]
+    L.gv_train_device_pool_static.argtypes = [vp, vp, C.c_uint64]
     L.gv_draw_negatives.argtypes = [vp, C.c_uint64, C.c_uint64, u32p]
     L.gv_sync.argtypes = [vp]
     L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
@@ -209,6 +211,10 @@ def gv_train_pool(ctx):
 
 def gv_train_device_pool(ctx, dev_ptr, count):
     _check(ctx, load().gv_train_device_pool(ctx, C.c_void_p(dev_ptr), count))
+
+
+def gv_train_device_pool_static(ctx, dev_ptr, count):
+    _check(ctx, load().gv_train_device_pool_static(ctx, C.c_void_p(dev_ptr), count))
 
 
 def gv_draw_negatives(ctx, first_g, count, num_neg):

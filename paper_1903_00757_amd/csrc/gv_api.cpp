@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <exception>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -40,6 +41,17 @@ struct TimedSpan {
 
 }  // namespace
 
+// Scratch of the entry point that must not allocate (gv_train_device_pool_static): the per-sample records
+// of the tiled kernel, in a device array that is part of the loaded code object.  Every GPU holds its own
+// copy at its own address; the name below is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) uint32_t scratch[GV_STATIC_SCRATCH_WORDS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t *g_scratch_address[kMaxDevices];  // device address of `scratch` on each GPU, looked up once per GPU
+}  // namespace
+
 struct gv_ctx {
     gv_config cfg{};
     uint32_t n = 0;
@@ -59,6 +71,7 @@ struct gv_ctx {
     uint64_t negatives_capacity = 0;      // in uint32 elements
     uint32_t *records = nullptr;          // device scratch of the tiled kernel: K + 3 words per sample of a launch
     uint64_t records_capacity = 0;        // in uint32 elements
+    uint32_t *static_records = nullptr;   // this GPU's copy of the `scratch` array (GV_STATIC_SCRATCH_WORDS words)
     void *eval_scratch = nullptr;         // device scratch of gv_eval_loss / gv_cosine / gv_auc, grown on demand
     uint64_t eval_capacity = 0;           // in bytes
     hipStream_t compute = nullptr;
@@ -286,7 +299,9 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
 
 // Asynchronous training of `count` samples at dev_pairs: one launch of the tiled
 // stationary-row kernel, or of the plain pool-order kernel.
-int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
+// `fixed_records`: null, or the static scratch of the entry point that must not allocate: then nothing is
+// allocated on the way (no scratch growth, no events: the launch is not timed).
+int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32_t *fixed_records = nullptr) {
     // GV_SCHEDULE_AUTO: the tiled schedule exists for rows that many samples of a tile share.  A graph
     // without a single warm row has none, and there the sort, the records and the rank reads are pure
     // cost: such a graph is trained in pool order (with the mixed policy all of its rows are cold, i.e.
@@ -297,19 +312,26 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
     uint32_t coherence = ctx->cfg.coherence;
     if (!tiled && ctx->cfg.schedule == GV_SCHEDULE_AUTO && coherence == GV_COHERENCE_MIXED && ctx->warm_ranks == 0)
         coherence = GV_COHERENCE_AGENT;
-    if (tiled) {  // before the timed span: an allocation must not count as kernel time
+    if (tiled && fixed_records) {
+        const uint64_t words = count * (ctx->cfg.num_neg + 3);
+        if (words > GV_STATIC_SCRATCH_WORDS)
+            return fail(ctx, GV_EINVAL, "pool of %llu samples needs %llu words of scratch, the static scratch holds %llu "
+                        "(at most %llu samples at K = %u)", (unsigned long long)count, (unsigned long long)words,
+                        (unsigned long long)GV_STATIC_SCRATCH_WORDS,
+                        (unsigned long long)(GV_STATIC_SCRATCH_WORDS / (ctx->cfg.num_neg + 3)), ctx->cfg.num_neg);
+    } else if (tiled) {  // before the timed span: an allocation must not count as kernel time
         int rc = ensure_records(ctx, count * (ctx->cfg.num_neg + 3));
         if (rc) return rc;
     }
     TimedSpan span{};
-    const bool timed = ctx->cfg.profile != 0;
+    const bool timed = ctx->cfg.profile != 0 && !fixed_records;
     if (timed) {
         int rc = begin_span(ctx, 0, ctx->compute, &span);
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
     if (tiled) {
-        a.records = ctx->records;
+        a.records = fixed_records ? fixed_records : ctx->records;
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
     } else {
         GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
@@ -519,6 +541,15 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
             return bail(GV_ENOMEM);
         }
         GV_TRY(hipSetDevice(cfg->device));
+        if (cfg->device < kMaxDevices) {  // once per GPU, with that GPU current: where its copy of `scratch` lies
+            std::lock_guard<std::mutex> lock(g_scratch_mutex);
+            if (!g_scratch_address[cfg->device]) {
+                void *address = nullptr;
+                GV_TRY(hipGetSymbolAddress(&address, HIP_SYMBOL(scratch)));
+                g_scratch_address[cfg->device] = (uint32_t *)address;
+            }
+            ctx->static_records = g_scratch_address[cfg->device];
+        }
         GV_TRY(hipStreamCreateWithFlags(&ctx->compute, hipStreamNonBlocking));
         GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
         GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
@@ -873,6 +904,25 @@ int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count)
         if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
         if (count > 0 && !dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
         return train_any(ctx, dev_pairs, nullptr, count);
+    });
+}
+
+int gv_train_device_pool_static(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (ctx->cfg.mode != GV_MODE_HOGWILD)
+            return fail(ctx, GV_ESTATE, "gv_train_device_pool_static trains asynchronously only (GV_MODE_HOGWILD)");
+        if (!ctx->static_records) return fail(ctx, GV_ESTATE, "no static scratch on device %d", ctx->cfg.device);
+        if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
+        if (count == 0) return GV_OK;
+        if (!dev_pairs) return fail(ctx, GV_EINVAL, "null pool");
+        rc = train_hogwild(ctx, dev_pairs, count, ctx->static_records);
+        if (rc) return rc;
+        ctx->next_g += count;
+        ctx->stats.samples_trained = ctx->next_g;
+        ctx->stats.pools_trained += 1;
+        return GV_OK;
     });
 }
 

@@ -50,6 +50,8 @@ def test_config_struct_layout_matches_header(gv):
     assert float(re.search(r"#define GV_NEG_WEIGHT_DEFAULT \((-?[0-9.]+)f\)", text).group(1)) == gv.GV_NEG_WEIGHT_DEFAULT
     assert int(re.search(r"#define GV_MAX_POOL_SLOTS (\d+)", text).group(1)) == gv.GV_MAX_POOL_SLOTS
     assert re.search(r"GV_SCHEDULE_AUTO = (\d+)", text).group(1) == str(gv.GV_SCHEDULE_AUTO)
+    assert re.search(r"#define GV_STATIC_SCRATCH_WORDS \(1u << (\d+)\)", text).group(1) == "22" and \
+        gv.GV_STATIC_SCRATCH_WORDS == 1 << 22
 
 
 def test_argument_errors_need_no_device(gv):
