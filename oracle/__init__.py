@@ -50,6 +50,17 @@ def lib():
                                 C.c_uint64, C.c_uint64, C.c_float, C.c_float, C.c_float, C.c_uint64,
                                 u32p, u32p, u32p]
         L.orc_train.restype = None
+        L.orc_train_ordered.argtypes = L.orc_train.argtypes + [u32p]
+        L.orc_train_ordered.restype = None
+        L.orc_zigzag_partition.argtypes = [C.c_uint64, u32p, C.c_uint32, u32p]
+        L.orc_zigzag_partition.restype = None
+        L.orc_partition_alias.argtypes = [C.c_uint64, u32p, C.c_uint32, u32p, u64p, u32p, u32p, u32p]
+        L.orc_partition_alias.restype = C.c_int
+        L.orc_draw_negatives_partitioned.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32,
+                                                     u32p, u32p, u64p, u32p, u32p, u32p, u32p]
+        L.orc_draw_negatives_partitioned.restype = None
+        L.orc_block_order.argtypes = [C.c_uint64, u32p, C.c_uint32, u32p, u32p, u64p]
+        L.orc_block_order.restype = None
         L.orc_loss.argtypes = [f32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, u32p, C.c_uint64,
                                C.c_float, C.c_uint64, C.c_uint32, u32p, u32p]
         L.orc_loss.restype = C.c_double
@@ -144,9 +155,67 @@ def learning_rate(lr0, lr_min_ratio, g, T):
     return float(lib().orc_learning_rate(lr0, lr_min_ratio, g, T))
 
 
-def train(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, thresh, alias, negatives=None):
+def zigzag_partition(deg, B):
+    """Partition number of every node (uint32[n]): degree-sorted nodes dealt back and forth."""
+    deg = _arr(deg, np.uint32)
+    part = np.empty(deg.size, dtype=np.uint32)
+    lib().orc_zigzag_partition(deg.size, _p(deg, C.c_uint32), B, _p(part, C.c_uint32))
+    return part
+
+
+def partition_alias(deg, B, part):
+    """One alias table per partition, concatenated: (offsets uint64[B+1], members, thresh, alias uint32[n])."""
+    deg = _arr(deg, np.uint32)
+    part = _arr(part, np.uint32)
+    offsets = np.empty(B + 1, dtype=np.uint64)
+    members = np.empty(deg.size, dtype=np.uint32)
+    thresh = np.empty(deg.size, dtype=np.uint32)
+    alias = np.empty(deg.size, dtype=np.uint32)
+    rc = lib().orc_partition_alias(deg.size, _p(deg, C.c_uint32), B, _p(part, C.c_uint32), _p(offsets, C.c_uint64),
+                                   _p(members, C.c_uint32), _p(thresh, C.c_uint32), _p(alias, C.c_uint32))
+    if rc:
+        raise ValueError("a partition has no weight")
+    return offsets, members, thresh, alias
+
+
+def draw_negatives_partitioned(seed, first_g, v, K, part, tables, stream=STREAM_NEG):
+    """Negatives of positive samples first_g .. with context nodes ``v``, each from the partition of its v."""
+    offsets, members, thresh, alias = tables
+    v = _arr(v, np.uint32)
+    part = _arr(part, np.uint32)
+    out = np.empty((v.size, K), dtype=np.uint32)
+    lib().orc_draw_negatives_partitioned(seed, stream, first_g, v.size, K, _p(v, C.c_uint32), _p(part, C.c_uint32),
+                                         _p(offsets, C.c_uint64), _p(members, C.c_uint32), _p(thresh, C.c_uint32),
+                                         _p(alias, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def block_order(pairs, B, part):
+    """(order uint32[count], block_offsets uint64[B*B+1]) of the pool under the orthogonal-block schedule."""
+    pairs = _arr(pairs, np.uint32)
+    part = _arr(part, np.uint32)
+    order = np.empty(pairs.shape[0], dtype=np.uint32)
+    block_offsets = np.empty(B * B + 1, dtype=np.uint64)
+    lib().orc_block_order(pairs.shape[0], _p(pairs, C.c_uint32), B, _p(part, C.c_uint32), _p(order, C.c_uint32),
+                          _p(block_offsets, C.c_uint64))
+    return order, block_offsets
+
+
+def train_blocked(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, B, part, tables):
+    """Sequential SGD over ``pairs`` in orthogonal-block order with negatives restricted to the partition of
+    each sample's context node; a sample keeps the position (negatives, learning rate) of its place in the pool."""
+    pairs = _arr(pairs, np.uint32)
+    negatives = draw_negatives_partitioned(seed, first_g, pairs[:, 1].copy(), K, part, tables)
+    order, _ = block_order(pairs, B, part)
+    train(vertex, context, pairs, K=K, first_g=first_g, T=T, lr0=lr0, lr_min_ratio=lr_min_ratio, w=w, seed=seed,
+          thresh=tables[2], alias=tables[3], negatives=negatives, order=order)
+
+
+def train(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, thresh, alias, negatives=None,
+          order=None):
     """In-place sequential SGD over ``pairs``; ``vertex``/``context`` must be
-    C-contiguous float32 arrays of shape (n, d)."""
+    C-contiguous float32 arrays of shape (n, d).  ``order``: the sequence in which the samples are taken
+    (indices into ``pairs``), pool order when None."""
     assert vertex.dtype == np.float32 and context.dtype == np.float32
     assert vertex.flags.c_contiguous and context.flags.c_contiguous
     pairs = _arr(pairs, np.uint32)
@@ -156,9 +225,14 @@ def train(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, 
         negatives = _arr(negatives, np.uint32)
         assert negatives.size == pairs.shape[0] * K
         negp = _p(negatives, C.c_uint32)
-    lib().orc_train(_p(vertex, C.c_float), _p(context, C.c_float), n, d, K, _p(pairs, C.c_uint32),
-                    pairs.shape[0], first_g, T, lr0, lr_min_ratio, w, seed,
-                    _p(thresh, C.c_uint32), _p(alias, C.c_uint32), negp)
+    orderp = None
+    if order is not None:
+        order = _arr(order, np.uint32)
+        assert order.size == pairs.shape[0]
+        orderp = _p(order, C.c_uint32)
+    lib().orc_train_ordered(_p(vertex, C.c_float), _p(context, C.c_float), n, d, K, _p(pairs, C.c_uint32),
+                            pairs.shape[0], first_g, T, lr0, lr_min_ratio, w, seed,
+                            _p(thresh, C.c_uint32), _p(alias, C.c_uint32), negp, orderp)
 
 
 def loss(vertex, context, pairs, *, K, w, seed, thresh, alias, stream=STREAM_EVAL):

@@ -268,22 +268,56 @@ float orc_learning_rate(float lr0, float lr_min_ratio, uint64_t g, uint64_t T)
  * rows named twice within a sample receive the sum of their updates.
  * `negatives` may be NULL (then they are drawn here from stream 0) or hold K
  * indices per sample.                                                        */
-void orc_train(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
-               const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
-               float lr0, float lr_min_ratio, float w, uint64_t seed,
-               const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives)
+/* One positive sample at global position g: u, v, its K negatives in neg[1..K] (neg[0] = v).  Scratch
+ * arrays of d doubles (dx, xu) and K + 1 doubles (coef) come from the caller.                          */
+static void train_sample(float *vertex, float *context, uint32_t d, uint32_t K, uint32_t u, const uint32_t *neg,
+                         uint64_t g, uint64_t T, float lr0, float lr_min_ratio, float w,
+                         double *dx, double *xu, double *coef)
+{
+    double lr = (double)orc_learning_rate(lr0, lr_min_ratio, g, T);
+    float *x = vertex + (size_t)u * d;
+    for (uint32_t k = 0; k <= K; ++k) {
+        const float *c = context + (size_t)neg[k] * d;
+        double score = 0.0;
+        for (uint32_t j = 0; j < d; ++j) score += (double)x[j] * (double)c[j];
+        coef[k] = k == 0 ? lr * (1.0 - sigmoid(score)) : -lr * (double)w * sigmoid(score);
+    }
+    for (uint32_t j = 0; j < d; ++j) { xu[j] = (double)x[j]; dx[j] = 0.0; }
+    for (uint32_t k = 0; k <= K; ++k) {
+        const float *c = context + (size_t)neg[k] * d;
+        for (uint32_t j = 0; j < d; ++j) dx[j] += coef[k] * (double)c[j];
+    }
+    /* context rows: a row named several times gets the summed coefficient once */
+    for (uint32_t k = 0; k <= K; ++k) {
+        int seen = 0;
+        for (uint32_t k2 = 0; k2 < k; ++k2) if (neg[k2] == neg[k]) seen = 1;
+        if (seen) continue;
+        double total = 0.0;
+        for (uint32_t k2 = k; k2 <= K; ++k2) if (neg[k2] == neg[k]) total += coef[k2];
+        float *c = context + (size_t)neg[k] * d;
+        for (uint32_t j = 0; j < d; ++j) c[j] = (float)((double)c[j] + total * xu[j]);
+    }
+    for (uint32_t j = 0; j < d; ++j) x[j] = (float)(xu[j] + dx[j]);
+}
+
+/* `order` (may be NULL = pool order): the sequence in which the samples are taken, order[k] = index into
+ * pairs / negatives of the k-th sample trained; a sample keeps the position first_g + its index whatever
+ * its turn (position decides its negatives and its learning rate).                                      */
+void orc_train_ordered(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
+                       const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
+                       float lr0, float lr_min_ratio, float w, uint64_t seed,
+                       const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives,
+                       const uint32_t *order)
 {
     double *dx = (double *)malloc((size_t)d * sizeof(double));
     double *xu = (double *)malloc((size_t)d * sizeof(double));
     uint32_t *neg = (uint32_t *)malloc(((size_t)K + 1) * sizeof(uint32_t));
     double *coef = (double *)malloc(((size_t)K + 1) * sizeof(double));
-    for (uint64_t i = 0; i < count; ++i) {
+    for (uint64_t turn = 0; turn < count; ++turn) {
+        uint64_t i = order ? order[turn] : turn;
         uint64_t g = first_g + i;
-        uint32_t u = pairs[2 * i], v = pairs[2 * i + 1];
-        double lr = (double)orc_learning_rate(lr0, lr_min_ratio, g, T);
-        float *x = vertex + (size_t)u * d;
         /* row 0 of the sample is the positive context row, rows 1..K the negatives */
-        neg[0] = v;
+        neg[0] = pairs[2 * i + 1];
         for (uint32_t k = 0; k < K; ++k) {
             if (negatives) neg[k + 1] = negatives[i * K + k];
             else {
@@ -292,30 +326,117 @@ void orc_train(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K
                 neg[k + 1] = alias_draw(r, n, thresh, alias);
             }
         }
-        for (uint32_t k = 0; k <= K; ++k) {
-            const float *c = context + (size_t)neg[k] * d;
-            double score = 0.0;
-            for (uint32_t j = 0; j < d; ++j) score += (double)x[j] * (double)c[j];
-            coef[k] = k == 0 ? lr * (1.0 - sigmoid(score)) : -lr * (double)w * sigmoid(score);
-        }
-        for (uint32_t j = 0; j < d; ++j) { xu[j] = (double)x[j]; dx[j] = 0.0; }
-        for (uint32_t k = 0; k <= K; ++k) {
-            const float *c = context + (size_t)neg[k] * d;
-            for (uint32_t j = 0; j < d; ++j) dx[j] += coef[k] * (double)c[j];
-        }
-        /* context rows: a row named several times gets the summed coefficient once */
-        for (uint32_t k = 0; k <= K; ++k) {
-            int seen = 0;
-            for (uint32_t k2 = 0; k2 < k; ++k2) if (neg[k2] == neg[k]) seen = 1;
-            if (seen) continue;
-            double total = 0.0;
-            for (uint32_t k2 = k; k2 <= K; ++k2) if (neg[k2] == neg[k]) total += coef[k2];
-            float *c = context + (size_t)neg[k] * d;
-            for (uint32_t j = 0; j < d; ++j) c[j] = (float)((double)c[j] + total * xu[j]);
-        }
-        for (uint32_t j = 0; j < d; ++j) x[j] = (float)(xu[j] + dx[j]);
+        train_sample(vertex, context, d, K, pairs[2 * i], neg, g, T, lr0, lr_min_ratio, w, dx, xu, coef);
     }
     free(dx); free(xu); free(neg); free(coef);
+}
+
+void orc_train(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
+               const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
+               float lr0, float lr_min_ratio, float w, uint64_t seed,
+               const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives)
+{
+    orc_train_ordered(vertex, context, n, d, K, pairs, count, first_g, T, lr0, lr_min_ratio, w, seed,
+                      thresh, alias, negatives, NULL);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Orthogonal blocks (Sec. 3.2, Alg. 3) on partitioned matrices.
+ *
+ * Degree-guided partition (Sec. 4.3; its figure is missing from the text at hand): the nodes are sorted by
+ * falling degree (ties by id) and dealt to the B partitions back and forth, 0, 1, .., B-1, B-1, .., 1, 0,
+ * 0, 1, ..: every partition gets the same number of nodes (up to one) and about the same degree mass.   */
+struct by_degree { uint32_t degree, id; };
+static int hotter_first(const void *a, const void *b)
+{
+    const struct by_degree *x = (const struct by_degree *)a, *y = (const struct by_degree *)b;
+    if (x->degree != y->degree) return x->degree > y->degree ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+void orc_zigzag_partition(uint64_t n, const uint32_t *deg, uint32_t B, uint32_t *part)
+{
+    struct by_degree *order = (struct by_degree *)malloc(n * sizeof *order);
+    for (uint64_t i = 0; i < n; ++i) { order[i].degree = deg[i]; order[i].id = (uint32_t)i; }
+    qsort(order, n, sizeof *order, hotter_first);
+    for (uint64_t r = 0; r < n; ++r) {
+        uint64_t round = r / B;
+        uint32_t k = (uint32_t)(r % B);
+        part[order[r].id] = round % 2 == 0 ? k : B - 1 - k;
+    }
+    free(order);
+}
+
+/* One alias table per partition (Sec. 3.2: negatives are drawn only from the context rows of the partition
+ * at hand), over the partition's nodes in increasing id with the same weights degree^(3/4).  Concatenated:
+ * partition j owns entries offsets[j] .. offsets[j+1]-1; entry e stands for node members[e], is accepted
+ * below thresh[e] and otherwise gives node alias[e].  Returns 0, or -1 when a partition has no weight.   */
+int orc_partition_alias(uint64_t n, const uint32_t *deg, uint32_t B, const uint32_t *part,
+                        uint64_t *offsets, uint32_t *members, uint32_t *thresh, uint32_t *alias)
+{
+    for (uint32_t j = 0; j <= B; ++j) offsets[j] = 0;
+    for (uint64_t i = 0; i < n; ++i) offsets[part[i] + 1] += 1;
+    for (uint32_t j = 0; j < B; ++j) offsets[j + 1] += offsets[j];
+    uint64_t *fill = (uint64_t *)calloc(B, sizeof(uint64_t));
+    for (uint64_t i = 0; i < n; ++i) members[offsets[part[i]] + fill[part[i]]++] = (uint32_t)i;
+    free(fill);
+    int rc = 0;
+    for (uint32_t j = 0; j < B && rc == 0; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint32_t *mine = members + offsets[j];
+        uint32_t *degrees = (uint32_t *)malloc(nj * sizeof(uint32_t));
+        double *q = (double *)malloc(nj * sizeof(double));
+        uint32_t *local = (uint32_t *)malloc(nj * sizeof(uint32_t));
+        for (uint64_t l = 0; l < nj; ++l) degrees[l] = deg[mine[l]];
+        orc_degree_weights(nj, degrees, q);
+        if (nj == 0 || orc_alias_build(nj, q, thresh + offsets[j], local) != 0) rc = -1;
+        else for (uint64_t l = 0; l < nj; ++l) alias[offsets[j] + l] = mine[local[l]];
+        free(degrees); free(q); free(local);
+    }
+    return rc;
+}
+
+/* Negatives restricted to the partition of the positive context node: out[i*K + k] for positive samples
+ * first_g + i with context nodes v[i].                                                                  */
+void orc_draw_negatives_partitioned(uint64_t seed, uint32_t stream, uint64_t first_g, uint64_t count, uint32_t K,
+                                    const uint32_t *v, const uint32_t *part, const uint64_t *offsets,
+                                    const uint32_t *members, const uint32_t *thresh, const uint32_t *alias,
+                                    uint32_t *out)
+{
+    for (uint64_t i = 0; i < count; ++i) {
+        uint32_t j = part[v[i]];
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        for (uint32_t k = 0; k < K; ++k) {
+            uint32_t r[4];
+            words(seed, first_g + i, k, stream, r);
+            uint64_t e = offsets[j] + scale64(r[0], r[1], nj);
+            out[i * K + k] = r[2] < thresh[e] ? members[e] : alias[e];
+        }
+    }
+}
+
+/* Order of training under Alg. 3 run by one worker: the pool is redistributed into the B x B grid, sample
+ * (u, v) to block (part[u], part[v]); sub-episode o = 0..B-1 takes the blocks (i, (i + o) mod B), i = 0..B-1
+ * (blocks of one sub-episode share no row, Def. 1); inside a block the samples keep their pool order.
+ * order[k] = pool index of the k-th sample; block_offsets[o*B + i] = first k of block (i, (i + o) mod B).  */
+void orc_block_order(uint64_t count, const uint32_t *pairs, uint32_t B, const uint32_t *part,
+                     uint32_t *order, uint64_t *block_offsets)
+{
+    uint64_t blocks = (uint64_t)B * B;
+    for (uint64_t b = 0; b <= blocks; ++b) block_offsets[b] = 0;
+    for (uint64_t i = 0; i < count; ++i) {
+        uint32_t pi = part[pairs[2 * i]], pj = part[pairs[2 * i + 1]];
+        uint32_t o = (pj + B - pi) % B;
+        block_offsets[(uint64_t)o * B + pi + 1] += 1;
+    }
+    for (uint64_t b = 0; b < blocks; ++b) block_offsets[b + 1] += block_offsets[b];
+    uint64_t *fill = (uint64_t *)calloc(blocks, sizeof(uint64_t));
+    for (uint64_t i = 0; i < count; ++i) {
+        uint32_t pi = part[pairs[2 * i]], pj = part[pairs[2 * i + 1]];
+        uint64_t b = (uint64_t)((pj + B - pi) % B) * B + pi;
+        order[block_offsets[b] + fill[b]++] = (uint32_t)i;
+    }
+    free(fill);
 }
 
 /* Mean per-sample loss (the objective the step above descends) over a fixed
