@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-online", action="store_true", help="skip the legs with pools produced on the fly")
     ap.add_argument("--cpu-samples", type=int, default=1 << 24)
+    ap.add_argument("--blocked-partitions", type=int, default=0,
+                    help="also time the orthogonal-block schedule (Sec. 3.2) with this many partitions")
+    ap.add_argument("--episode-pools", type=int, default=8, help="pools per episode of the orthogonal-block leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -292,6 +295,54 @@ def main():
     finally:
         gv.gv_destroy(ctx)
 
+    blocked = None
+    if args.blocked_partitions and adj is not None:
+        # Orthogonal blocks (Sec. 3.2, Alg. 3) on one GPU: an episode of several pools is redistributed into the
+        # B x B grid on the host (not timed, like pool production), then trained block after block; a launch
+        # touches one vertex partition and one context partition only.
+        B, E = args.blocked_partitions, args.episode_pools
+        ctx = gv.gv_create(dim=dim, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=total,
+                           seed=W.configs.TRAIN_SEED, pool_capacity=8, coherence=args.coherence, schedule=args.schedule,
+                           profile=1, partitions=B)
+        try:
+            gv.gv_set_degrees(ctx, deg)
+            gv.gv_build_alias(ctx, 0.75)
+            gv.gv_init_embeddings(ctx, 1)
+            part = gv.gv_get_partitions(ctx, n, B)[0]
+            t0 = time.perf_counter()
+            episode = np.empty((E * P, 2), dtype=np.uint32)
+            for r in range(E):
+                gv.gv_augment(offsets, adj, seed=100 * cfg["number"], first_walk=r * walks_per_pool, count=P,
+                              threads=threads, out=episode[r * P:(r + 1) * P])
+            sorted_pairs, order, block_offsets = gv.gv_redistribute_pool(part, B, episode, threads=threads)
+            log(f"episode of {E} pools produced and redistributed into {B}x{B} blocks ({time.perf_counter() - t0:.1f} s)")
+            del episode
+            dev_pairs = torch.from_numpy(sorted_pairs.view(np.int32)).cuda()
+            dev_order = torch.from_numpy(order.view(np.int32)).cuda()
+            torch.cuda.synchronize()
+
+            def episode_steps(count):
+                for _ in range(count):
+                    gv.gv_train_device_blocks(ctx, dev_pairs.data_ptr(), dev_order.data_ptr(), block_offsets, E * P)
+
+            episode_steps(1)
+            reps = timed_legs(gv, ctx, episode_steps, max(1, args.steps // E))
+            episodes = max(1, args.steps // E)
+            walls = sorted(r["wall_s"] for r in reps)
+            sizes = np.diff(block_offsets.astype(np.int64))
+            blocked = {"partitions": B, "episode_samples": E * P, "launches_per_episode": int((sizes > 0).sum()),
+                       "samples_per_s_median": episodes * E * P / walls[len(walls) // 2],
+                       "samples_per_s_best": episodes * E * P / walls[0],
+                       "kernel_ms_per_launch": [r["kernel_ms"] for r in reps],
+                       "block_samples_min_max": [int(sizes.min()), int(sizes.max())],
+                       "warm_rows": gv.gv_get_stats(ctx)["warm_rows"],
+                       "note": "negatives restricted to the context partition of the block; redistribution on the host, "
+                               "outside the timed region"}
+            log(f"orthogonal blocks {B}x{B}, episode {E} pools: {blocked['samples_per_s_median']:.4g} samples/s")
+            del dev_pairs, dev_order
+        finally:
+            gv.gv_destroy(ctx)
+
     if args.calibrate_copy:
         src_t = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         dst_t = torch.empty_like(src_t)
@@ -336,6 +387,7 @@ def main():
         "streamed": s_sum,
         "resident": r_sum,
         "online": online or None,
+        "blocked": blocked,
     }
     print(json.dumps(out), flush=True)
 

@@ -76,6 +76,8 @@ enum { GV_SCHEDULE_POOL_ORDER = 0, GV_SCHEDULE_TILED = 1, GV_SCHEDULE_AUTO = 2 }
 #define GV_NEG_WEIGHT_DEFAULT (-1.0f)
 /* Largest number of pinned pool slots of a context (gv_config.pool_slots).              */
 #define GV_MAX_POOL_SLOTS 16
+/* Largest number of partitions of the orthogonal-block schedule (gv_config.partitions).   */
+#define GV_MAX_PARTITIONS 64
 
 typedef struct gv_config {
     uint32_t dim;            /* d: a multiple of 32 in 32..512 (128, or 96 in Sec. 4.3)       */
@@ -95,6 +97,9 @@ typedef struct gv_config {
     uint32_t schedule;       /* GV_SCHEDULE_* (asynchronous mode)                              */
     uint32_t pool_slots;     /* pinned pool slots in the ring: 0 (= 2, the two pools of Sec. 3.3)
                                 or 2..GV_MAX_POOL_SLOTS                                        */
+    uint32_t partitions;     /* 0, or the number B of partitions of the rows for the orthogonal-block
+                                schedule of Sec. 3.2 (2..GV_MAX_PARTITIONS): gv_build_alias then also
+                                partitions the nodes and builds one alias table per partition    */
 } gv_config;
 
 typedef struct gv_stats {
@@ -197,6 +202,40 @@ int gv_train_device_pool(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count)
  * stream, but calls of two contexts that overlap on one GPU race on it.                      */
 #define GV_STATIC_SCRATCH_WORDS (1u << 22)
 int gv_train_device_pool_static(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count);
+
+/* Orthogonal blocks (Sec. 3.2, Alg. 3; degree-guided partition, Sec. 4.3), for contexts created with
+ * gv_config.partitions = B > 0.  The rows of both matrices are partitioned B ways: gv_build_alias sorts the
+ * nodes by falling degree (ties by id), deals them to the partitions back and forth (0, 1, .., B-1, B-1, .., 0,
+ * 0, ..), and builds one alias table per partition over its nodes in increasing id, same weights and
+ * construction as the whole-graph table.  A pool is redistributed into the B x B grid, sample (u, v) to block
+ * (partition of u, partition of v); sub-episode o = 0..B-1 trains the blocks (i, (i + o) mod B), i = 0..B-1, which
+ * share no row; the negatives of a sample are drawn from the alias table of the partition of its context node v
+ * only (Sec. 3.2), so a block touches one vertex partition and one context partition.  A sample keeps the
+ * position (negatives, learning rate) of its place in the pool it came from.  On one GPU the blocks are
+ * trained one after the other: what this buys is a working set of 2/B of the matrices per launch.
+ * gv_get_partitions (test hook): host_part[n] = partition of every node; host_offsets[B + 1], and, concatenated
+ *   by partition, host_members[n] (the node of every table bucket), host_thresh[n], host_alias[n] (node ids).
+ * gv_redistribute_pool (host, no context, no GPU; the Redistribute step of Alg. 3): stable counting sort of
+ *   host_pairs[count][2] by block in training order (sub-episode first, then vertex partition) with `threads`
+ *   workers: host_pairs_out[count][2], host_order[count] = pool index of every sorted sample,
+ *   host_block_offsets[B * B + 1] = first sorted sample of block number o * B + i.  count <= 2^32.  GV_EINVAL
+ *   for an id >= n or a partition number >= B.
+ * gv_train_device_blocks: trains a redistributed pool that lies in device memory (dev_pairs[count][2],
+ *   dev_order[count]; both must stay valid until gv_sync; host_block_offsets as written by
+ *   gv_redistribute_pool, read before the call returns): one asynchronous launch per block, in training order, with the
+ *   context's schedule and coherence; positions g + dev_order[k].  GV_ESTATE without partitions or in
+ *   deterministic mode.
+ * gv_draw_negatives_partitioned (parity hook): the K negatives of positive samples first_g .. first_g+count-1
+ *   with context nodes host_v[count], as block training draws them: host_out[count][K].                  */
+int gv_get_partitions(gv_ctx *ctx, uint32_t *host_part, uint64_t *host_offsets, uint32_t *host_members,
+                      uint32_t *host_thresh, uint32_t *host_alias);
+int gv_redistribute_pool(uint32_t n, const uint32_t *host_part, uint32_t partitions, const uint32_t *host_pairs,
+                         uint64_t count, uint32_t threads, uint32_t *host_pairs_out, uint32_t *host_order,
+                         uint64_t *host_block_offsets);
+int gv_train_device_blocks(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *dev_order,
+                           const uint64_t *host_block_offsets, uint64_t count);
+int gv_draw_negatives_partitioned(gv_ctx *ctx, uint64_t first_g, uint64_t count, const uint32_t *host_v,
+                                  uint32_t *host_out);
 
 /* Host producer of a pool (Sec. 3.1, Alg. 2, parallel online augmentation): walk number
  * first_walk + w departs from a node drawn with probability proportional to its degree,

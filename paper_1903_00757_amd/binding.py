@@ -18,6 +18,7 @@ GV_SCHEDULE_POOL_ORDER, GV_SCHEDULE_TILED, GV_SCHEDULE_AUTO = 0, 1, 2
 GV_NEG_WEIGHT_DEFAULT = -1.0
 GV_MAX_POOL_SLOTS = 16
 GV_STATIC_SCRATCH_WORDS = 1 << 22
+GV_MAX_PARTITIONS = 64
 GV_SHUFFLE_NONE, GV_SHUFFLE_PSEUDO = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgvhot.so")
@@ -28,6 +29,7 @@ EXPORTS = [
     "gv_acquire_pool_slot", "gv_push_pool", "gv_train_pool", "gv_train_device_pool", "gv_draw_negatives",
     "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
     "gv_set_adjacency", "gv_augment_device", "gv_auc", "gv_link_prediction_auc", "gv_train_device_pool_static",
+    "gv_get_partitions", "gv_redistribute_pool", "gv_train_device_blocks", "gv_draw_negatives_partitioned",
 ]
 
 
@@ -38,7 +40,7 @@ class gv_config(C.Structure):
         ("mode", C.c_uint32),
         ("total_samples", C.c_uint64), ("seed", C.c_uint64), ("pool_capacity", C.c_uint64),
         ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("schedule", C.c_uint32),
-        ("pool_slots", C.c_uint32),
+        ("pool_slots", C.c_uint32), ("partitions", C.c_uint32),
     ]
 
 
@@ -93,6 +95,11 @@ def load():
     L.gv_train_pool.argtypes = [vp]
     L.gv_train_device_pool.argtypes = [vp, vp, C.c_uint64]
     L.gv_train_device_pool_static.argtypes = [vp, vp, C.c_uint64]
+    u64p = C.POINTER(C.c_uint64)
+    L.gv_get_partitions.argtypes = [vp, u32p, u64p, u32p, u32p, u32p]
+    L.gv_redistribute_pool.argtypes = [C.c_uint32, u32p, C.c_uint32, vp, C.c_uint64, C.c_uint32, vp, u32p, u64p]
+    L.gv_train_device_blocks.argtypes = [vp, vp, vp, u64p, C.c_uint64]
+    L.gv_draw_negatives_partitioned.argtypes = [vp, C.c_uint64, C.c_uint64, u32p, u32p]
     L.gv_draw_negatives.argtypes = [vp, C.c_uint64, C.c_uint64, u32p]
     L.gv_sync.argtypes = [vp]
     L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
@@ -126,10 +133,11 @@ def _u32(a):
 
 def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=GV_NEG_WEIGHT_DEFAULT, mode=GV_MODE_HOGWILD,
               total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_MIXED, profile=0,
-              schedule=GV_SCHEDULE_AUTO, pool_slots=0):
+              schedule=GV_SCHEDULE_AUTO, pool_slots=0, partitions=0):
     cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio, neg_weight=neg_weight, mode=mode,
                     total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,
-                    coherence=coherence, profile=profile, schedule=schedule, pool_slots=pool_slots)
+                    coherence=coherence, profile=profile, schedule=schedule, pool_slots=pool_slots,
+                    partitions=partitions)
     ctx = C.c_void_p()
     rc = load().gv_create(C.byref(cfg), C.byref(ctx))
     _check(None, rc)
@@ -215,6 +223,47 @@ def gv_train_device_pool(ctx, dev_ptr, count):
 
 def gv_train_device_pool_static(ctx, dev_ptr, count):
     _check(ctx, load().gv_train_device_pool_static(ctx, C.c_void_p(dev_ptr), count))
+
+
+def gv_get_partitions(ctx, n, partitions):
+    """(part uint32[n], offsets uint64[B+1], members, thresh, alias uint32[n]) of a context with partitions."""
+    part = np.empty(n, dtype=np.uint32)
+    offsets = np.empty(partitions + 1, dtype=np.uint64)
+    members, thresh, alias = (np.empty(n, dtype=np.uint32) for _ in range(3))
+    u32 = C.POINTER(C.c_uint32)
+    _check(ctx, load().gv_get_partitions(ctx, part.ctypes.data_as(u32), offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                         members.ctypes.data_as(u32), thresh.ctypes.data_as(u32),
+                                         alias.ctypes.data_as(u32)))
+    return part, offsets, members, thresh, alias
+
+
+def gv_redistribute_pool(part, partitions, pairs, threads=1):
+    """(sorted pairs uint32[count][2], order uint32[count], block_offsets uint64[B*B+1])."""
+    part, pp = _u32(part)
+    pairs = np.ascontiguousarray(pairs, dtype=np.uint32)
+    count = pairs.shape[0]
+    out = np.empty((count, 2), dtype=np.uint32)
+    order = np.empty(count, dtype=np.uint32)
+    offsets = np.empty(partitions * partitions + 1, dtype=np.uint64)
+    rc = load().gv_redistribute_pool(part.size, pp, partitions, C.c_void_p(pairs.ctypes.data), count, threads,
+                                     C.c_void_p(out.ctypes.data), order.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                     offsets.ctypes.data_as(C.POINTER(C.c_uint64)))
+    if rc != GV_OK:
+        raise GvError(rc, "gv_redistribute_pool: bad argument, node id or partition number")
+    return out, order, offsets
+
+
+def gv_train_device_blocks(ctx, dev_pairs_ptr, dev_order_ptr, block_offsets, count):
+    block_offsets = np.ascontiguousarray(block_offsets, dtype=np.uint64)
+    _check(ctx, load().gv_train_device_blocks(ctx, C.c_void_p(dev_pairs_ptr), C.c_void_p(dev_order_ptr),
+                                              block_offsets.ctypes.data_as(C.POINTER(C.c_uint64)), count))
+
+
+def gv_draw_negatives_partitioned(ctx, first_g, v, num_neg):
+    v, pv = _u32(v)
+    out = np.empty((v.size, num_neg), dtype=np.uint32)
+    _check(ctx, load().gv_draw_negatives_partitioned(ctx, first_g, v.size, pv, out.ctypes.data_as(C.POINTER(C.c_uint32))))
+    return out
 
 
 def gv_draw_negatives(ctx, first_g, count, num_neg):

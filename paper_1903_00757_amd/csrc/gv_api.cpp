@@ -63,6 +63,13 @@ struct gv_ctx {
     uint16_t *dev_rank = nullptr;         // device, per node: hot rank (see gv::TrainArgs)
     uint32_t *dev_ranked = nullptr;       // device, bitmap of the nodes that have a hot rank
     uint32_t warm_ranks = 0;              // number of warm rows
+    // orthogonal blocks (cfg.partitions > 0): partition of every node, and one alias table per partition
+    std::vector<uint32_t> part;           // host, per node
+    std::vector<uint64_t> part_offsets;   // host, partitions + 1: partition j owns table buckets [j] .. [j + 1] - 1
+    std::vector<uint32_t> part_members, part_thresh, part_alias;  // host copies of the concatenated tables
+    uint4 *dev_part_tables = nullptr;     // device, n buckets
+    uint64_t *dev_part_offsets = nullptr; // device
+    uint8_t *dev_part = nullptr;          // device, per node
     uint64_t *dev_offsets = nullptr;      // device CSR of the graph (gv_set_adjacency), for the device producer
     uint32_t *dev_adj = nullptr;
     uint64_t half_edges = 0;
@@ -184,6 +191,12 @@ void free_matrices(gv_ctx *ctx) {
     ctx->dev_ranked = nullptr;
     if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
     if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
+    if (ctx->dev_part_tables) (void)hipFree(ctx->dev_part_tables);
+    if (ctx->dev_part_offsets) (void)hipFree(ctx->dev_part_offsets);
+    if (ctx->dev_part) (void)hipFree(ctx->dev_part);
+    ctx->dev_part_tables = nullptr;
+    ctx->dev_part_offsets = nullptr;
+    ctx->dev_part = nullptr;
     ctx->dev_offsets = nullptr;
     ctx->dev_adj = nullptr;
     ctx->half_edges = 0;
@@ -209,6 +222,7 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
     ctx->degree = std::move(deg);
+    ctx->part.clear();
     ctx->n = n;
     ctx->stamp_vertex.clear();
     ctx->stamp_context.clear();
@@ -259,8 +273,10 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.vertex = ctx->vertex;
     a.context = ctx->context;
     a.alias = ctx->alias;
+    a.alias_n = ctx->n;
     a.pairs = dev_pairs;
     a.negatives = nullptr;
+    a.order = nullptr;
     a.rank = ctx->dev_rank;
     a.ranked = ctx->n > 20u * 0xFFFFu ? ctx->dev_ranked : nullptr;  // under 5 % of the nodes ranked
     a.warm_ranks = ctx->warm_ranks;
@@ -301,7 +317,14 @@ int end_span(gv_ctx *ctx, hipStream_t stream, const TimedSpan &span) {
 // stationary-row kernel, or of the plain pool-order kernel.
 // `fixed_records`: null, or the static scratch of the entry point that must not allocate: then nothing is
 // allocated on the way (no scratch growth, no events: the launch is not timed).
-int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32_t *fixed_records = nullptr) {
+// `block`: null, or the part of a redistributed pool that one orthogonal block covers: its samples' pool indices
+// and the context partition whose alias table its negatives come from.
+struct BlockOfPool {
+    const uint32_t *dev_order;
+    uint32_t partition;
+};
+int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32_t *fixed_records = nullptr,
+                  const BlockOfPool *block = nullptr) {
     // GV_SCHEDULE_AUTO: the tiled schedule exists for rows that many samples of a tile share.  A graph
     // without a single warm row has none, and there the sort, the records and the rank reads are pure
     // cost: such a graph is trained in pool order (with the mixed policy all of its rows are cold, i.e.
@@ -330,6 +353,11 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32
         if (rc) return rc;
     }
     gv::TrainArgs a = train_args(ctx, dev_pairs, ctx->next_g, (uint32_t)count);
+    if (block) {
+        a.order = block->dev_order;
+        a.alias = ctx->dev_part_tables + ctx->part_offsets[block->partition];
+        a.alias_n = (uint32_t)(ctx->part_offsets[block->partition + 1] - ctx->part_offsets[block->partition]);
+    }
     if (tiled) {
         a.records = fixed_records ? fixed_records : ctx->records;
         GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
@@ -450,6 +478,43 @@ int pick_free_slot(gv_ctx *ctx, int *index) {
     return fail(ctx, GV_ESTATE, "all %d pool slots are filling or queued: train a pool first", slots);
 }
 
+// Alias table over weights q (Vose's method, the construction both sides of the parity tests follow: sum left
+// to right in fp64, p_i = q_i * size / sum, two index-ordered stacks, leftovers keep themselves, thresholds
+// floor(p * 2^32) saturated).  alias[i] is an index into q.  False when the weights sum to zero.
+bool vose_table(const std::vector<double> &q, std::vector<uint32_t> &thresh, std::vector<uint32_t> &alias, double *sum_out) {
+    const uint32_t size = (uint32_t)q.size();
+    double sum = 0.0;
+    for (uint32_t i = 0; i < size; ++i) sum += q[i];
+    if (sum_out) *sum_out = sum;
+    if (!(sum > 0.0)) return false;
+    std::vector<double> p(size), keep(size, 1.0);
+    std::vector<uint32_t> below, above;  // stacks of entries under / at-or-over the mean
+    below.reserve(size);
+    above.reserve(size);
+    thresh.assign(size, 0u);
+    alias.resize(size);
+    for (uint32_t i = 0; i < size; ++i) {
+        p[i] = q[i] * (double)size / sum;
+        (p[i] < 1.0 ? below : above).push_back(i);
+        alias[i] = i;
+    }
+    while (!below.empty() && !above.empty()) {
+        const uint32_t poor = below.back();
+        below.pop_back();
+        const uint32_t rich = above.back();
+        above.pop_back();
+        keep[poor] = p[poor];
+        alias[poor] = rich;
+        p[rich] = (p[rich] + p[poor]) - 1.0;
+        (p[rich] < 1.0 ? below : above).push_back(rich);
+    }
+    for (uint32_t i = 0; i < size; ++i) {
+        const double scaled = floor(keep[i] * 4294967296.0);
+        thresh[i] = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
+    }
+    return true;
+}
+
 // Device scratch shared by the evaluation calls: grown when a call needs more, kept otherwise.
 int ensure_eval_scratch(gv_ctx *ctx, uint64_t bytes) {
     if (bytes <= ctx->eval_capacity) return GV_OK;
@@ -499,6 +564,8 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
         if (cfg->total_samples == 0) return fail(nullptr, GV_EINVAL, "total_samples must be > 0");
         if (cfg->pool_capacity == 0 || cfg->pool_capacity > (1ull << 31))
             return fail(nullptr, GV_EINVAL, "pool_capacity must be in 1..2^31 samples");
+        if (cfg->partitions == 1 || cfg->partitions > GV_MAX_PARTITIONS)
+            return fail(nullptr, GV_EINVAL, "partitions must be 0 (none) or in 2..%d", GV_MAX_PARTITIONS);
         if (cfg->pool_slots == 1 || cfg->pool_slots > GV_MAX_POOL_SLOTS)
             return fail(nullptr, GV_EINVAL, "pool_slots must be 0 (= 2) or in 2..%d", GV_MAX_POOL_SLOTS);
         if (cfg->mode > GV_MODE_DETERMINISTIC || cfg->coherence > GV_COHERENCE_MIXED ||
@@ -634,25 +701,23 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         if (power != 0.75 && power != 1.0 && power != 0.0)
             return fail(ctx, GV_EINVAL, "power must be 0.75, 1.0 or 0.0");
         const uint32_t n = ctx->n;
-        // scaled weights p_i = q_i * n / S, S accumulated in index order
-        std::vector<double> p(n);
-        double sum = 0.0, degree_sum = 0.0;
-        for (uint32_t i = 0; i < n; ++i) degree_sum += (double)ctx->degree[i];
-        for (uint32_t i = 0; i < n; ++i) {
-            const double d = (double)ctx->degree[i];
-            double q;
+        auto weight = [&](uint32_t node) {
+            const double d = (double)ctx->degree[node];
             if (power == 0.75) {
                 const double root = sqrt(d);
-                q = root * sqrt(root);
-            } else if (power == 1.0) {
-                q = d;
-            } else {
-                q = 1.0;
+                return root * sqrt(root);
             }
-            p[i] = q;
-            sum += q;
+            return power == 1.0 ? d : 1.0;
+        };
+        std::vector<double> q(n);
+        double degree_sum = 0.0;
+        for (uint32_t i = 0; i < n; ++i) {
+            degree_sum += (double)ctx->degree[i];
+            q[i] = weight(i);
         }
-        if (!(sum > 0.0)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+        std::vector<uint32_t> thresh, alias;
+        double sum = 0.0;
+        if (!vose_table(q, thresh, alias, &sum)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
         // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
         // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
         // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
@@ -662,18 +727,24 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
         // update only when two of the few samples naming such a row are in flight together.  The
         // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
+        // Under the orthogonal-block schedule the samples in flight all come from one block, where a
+        // row's share is `partitions` times its share of the pool.
 #ifndef GV_TUNE_WARM
 #define GV_TUNE_WARM 0.1
 #endif
-        const double kInFlight = 8192.0, kWarmThreshold = GV_TUNE_WARM;
+        const uint32_t B = ctx->cfg.partitions;
+        const double kInFlight = 8192.0 * (B > 0 ? (double)B : 1.0), kWarmThreshold = GV_TUNE_WARM;
         const uint32_t kRanked = 0xFFFFu;
-        std::vector<uint32_t> order(n);
-        for (uint32_t i = 0; i < n; ++i) order[i] = i;
-        const uint32_t ranked = n < kRanked ? n : kRanked;
         auto hotter = [&](uint32_t x, uint32_t y) {
             return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;
         };
-        std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
+        std::vector<uint32_t> order(n);
+        for (uint32_t i = 0; i < n; ++i) order[i] = i;
+        const uint32_t ranked = n < kRanked ? n : kRanked;
+        if (B > 0)
+            std::sort(order.begin(), order.end(), hotter);  // the partition needs the whole order
+        else
+            std::partial_sort(order.begin(), order.begin() + ranked, order.end(), hotter);
         std::vector<uint16_t> rank(n, (uint16_t)kRanked);
         std::vector<uint32_t> ranked_bits(((size_t)n + 31) / 32, 0u);
         uint32_t warm_ranks = 0;
@@ -681,43 +752,76 @@ int gv_build_alias(gv_ctx *ctx, double power) {
             const uint32_t i = order[r];
             rank[i] = (uint16_t)r;
             ranked_bits[i >> 5] |= 1u << (i & 31u);
-            const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + p[i] / sum;
+            const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + q[i] / sum;
             if (share * kInFlight > kWarmThreshold) warm_ranks = r + 1;
+        }
+        std::vector<uint4> table(n);
+        for (uint32_t i = 0; i < n; ++i)  // ranks of both candidates and the bucket's node save the kernel gathers
+            table[i] = make_uint4(thresh[i], alias[i], (uint32_t)rank[i] | (uint32_t)rank[alias[i]] << 16, i);
+
+        // Orthogonal blocks (Sec. 3.2, Alg. 3): degree-guided partition (Sec. 4.3: nodes by falling degree dealt
+        // back and forth over the partitions) and one alias table per partition, over its nodes in increasing id.
+        std::vector<uint32_t> part, members, part_thresh, part_alias;
+        std::vector<uint64_t> part_offsets;
+        std::vector<uint4> part_tables;
+        std::vector<uint8_t> part_bytes;
+        if (B > 0) {
+            part.resize(n);
+            for (uint32_t r = 0; r < n; ++r) {
+                const uint32_t round = r / B, k = r % B;
+                part[order[r]] = round % 2 == 0 ? k : B - 1 - k;
+            }
+            part_offsets.assign(B + 1, 0);
+            for (uint32_t i = 0; i < n; ++i) part_offsets[part[i] + 1] += 1;
+            for (uint32_t j = 0; j < B; ++j) part_offsets[j + 1] += part_offsets[j];
+            members.resize(n);
+            std::vector<uint64_t> fill(part_offsets.begin(), part_offsets.end() - 1);
+            for (uint32_t i = 0; i < n; ++i) members[fill[part[i]]++] = i;
+            part_thresh.resize(n);
+            part_alias.resize(n);
+            part_tables.resize(n);
+            for (uint32_t j = 0; j < B; ++j) {
+                const uint64_t lo = part_offsets[j], size = part_offsets[j + 1] - lo;
+                std::vector<double> qj(size);
+                for (uint64_t l = 0; l < size; ++l) qj[l] = weight(members[lo + l]);
+                std::vector<uint32_t> tj, aj;
+                if (size == 0 || !vose_table(qj, tj, aj, nullptr))
+                    return fail(ctx, GV_EINVAL, "partition %u of %u has no node with a positive weight", j, B);
+                for (uint64_t l = 0; l < size; ++l) {
+                    const uint32_t self = members[lo + l], other = members[lo + aj[l]];
+                    part_thresh[lo + l] = tj[l];
+                    part_alias[lo + l] = other;
+                    part_tables[lo + l] = make_uint4(tj[l], other, (uint32_t)rank[self] | (uint32_t)rank[other] << 16, self);
+                }
+            }
+            part_bytes.resize(n);
+            for (uint32_t i = 0; i < n; ++i) part_bytes[i] = (uint8_t)part[i];
         }
         order.clear();
         order.shrink_to_fit();
-        std::vector<uint32_t> below, above;  // stacks of nodes under / at-or-over the mean
-        below.reserve(n);
-        above.reserve(n);
-        for (uint32_t i = 0; i < n; ++i) {
-            p[i] = p[i] * (double)n / sum;
-            (p[i] < 1.0 ? below : above).push_back(i);
-        }
-        std::vector<uint4> table(n);
-        std::vector<double> keep(n, 1.0);
-        for (uint32_t i = 0; i < n; ++i) table[i].y = i;
-        while (!below.empty() && !above.empty()) {
-            const uint32_t poor = below.back();
-            below.pop_back();
-            const uint32_t rich = above.back();
-            above.pop_back();
-            keep[poor] = p[poor];
-            table[poor].y = rich;
-            p[rich] = (p[rich] + p[poor]) - 1.0;
-            (p[rich] < 1.0 ? below : above).push_back(rich);
-        }
-        for (uint32_t i = 0; i < n; ++i) {
-            const double scaled = floor(keep[i] * 4294967296.0);
-            table[i].x = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
-            table[i].z = (uint32_t)rank[i] | (uint32_t)rank[table[i].y] << 16;  // saves the kernel a second gather
-            table[i].w = 0u;
-        }
+
         rc = sync_all(ctx);
         if (rc != GV_OK && rc != GV_EINVAL) return rc;
         GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
         GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
         GV_HIP(ctx, hipMemcpy(ctx->dev_ranked, ranked_bits.data(), ranked_bits.size() * sizeof(uint32_t),
                               hipMemcpyHostToDevice));
+        if (B > 0) {
+            if (!ctx->dev_part_tables) {
+                GV_HIP(ctx, hipMalloc((void **)&ctx->dev_part_tables, (size_t)n * sizeof(uint4)));
+                GV_HIP(ctx, hipMalloc((void **)&ctx->dev_part_offsets, ((size_t)B + 1) * sizeof(uint64_t)));
+                GV_HIP(ctx, hipMalloc((void **)&ctx->dev_part, (size_t)n));
+            }
+            GV_HIP(ctx, hipMemcpy(ctx->dev_part_tables, part_tables.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
+            GV_HIP(ctx, hipMemcpy(ctx->dev_part_offsets, part_offsets.data(), ((size_t)B + 1) * sizeof(uint64_t),
+                                  hipMemcpyHostToDevice));
+            GV_HIP(ctx, hipMemcpy(ctx->dev_part, part_bytes.data(), (size_t)n, hipMemcpyHostToDevice));
+            ctx->part = std::move(part);
+            ctx->part_offsets = std::move(part_offsets);
+            ctx->part_members = std::move(members);
+            ctx->part_thresh = std::move(part_thresh);
+            ctx->part_alias = std::move(part_alias);
+        }
         ctx->warm_ranks = warm_ranks;
         ctx->stats.warm_rows = warm_ranks;
         ctx->alias_ready = true;
@@ -922,6 +1026,90 @@ int gv_train_device_pool_static(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t
         ctx->next_g += count;
         ctx->stats.samples_trained = ctx->next_g;
         ctx->stats.pools_trained += 1;
+        return GV_OK;
+    });
+}
+
+int gv_get_partitions(gv_ctx *ctx, uint32_t *host_part, uint64_t *host_offsets, uint32_t *host_members,
+                      uint32_t *host_thresh, uint32_t *host_alias) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (ctx->cfg.partitions == 0 || ctx->part.size() != ctx->n)
+            return fail(ctx, GV_ESTATE, "the context was created without partitions");
+        if (!host_part || !host_offsets || !host_members || !host_thresh || !host_alias)
+            return fail(ctx, GV_EINVAL, "null output");
+        std::copy(ctx->part.begin(), ctx->part.end(), host_part);
+        std::copy(ctx->part_offsets.begin(), ctx->part_offsets.end(), host_offsets);
+        std::copy(ctx->part_members.begin(), ctx->part_members.end(), host_members);
+        std::copy(ctx->part_thresh.begin(), ctx->part_thresh.end(), host_thresh);
+        std::copy(ctx->part_alias.begin(), ctx->part_alias.end(), host_alias);
+        return GV_OK;
+    });
+}
+
+int gv_train_device_blocks(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *dev_order,
+                           const uint64_t *host_block_offsets, uint64_t count) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        const uint32_t B = ctx->cfg.partitions;
+        if (B == 0 || ctx->part.size() != ctx->n) return fail(ctx, GV_ESTATE, "the context was created without partitions");
+        if (ctx->cfg.mode != GV_MODE_HOGWILD)
+            return fail(ctx, GV_ESTATE, "orthogonal blocks are trained asynchronously only (GV_MODE_HOGWILD)");
+        if (count > (1ull << 32)) return fail(ctx, GV_EINVAL, "at most 2^32 samples per call");
+        if (!host_block_offsets) return fail(ctx, GV_EINVAL, "null block offsets");
+        const uint64_t blocks = (uint64_t)B * B;
+        if (host_block_offsets[0] != 0 || host_block_offsets[blocks] != count)
+            return fail(ctx, GV_EINVAL, "block offsets must run from 0 to count");
+        for (uint64_t b = 0; b < blocks; ++b)
+            if (host_block_offsets[b] > host_block_offsets[b + 1] ||
+                host_block_offsets[b + 1] - host_block_offsets[b] > (1ull << 31))
+                return fail(ctx, GV_EINVAL, "block offsets must ascend, at most 2^31 samples per block");
+        if (count == 0) return GV_OK;
+        if (!dev_pairs || !dev_order) return fail(ctx, GV_EINVAL, "null pool");
+        // sub-episode o = b / B trains the blocks (i, (i + o) mod B), i = b mod B, one launch each, in order
+        for (uint64_t b = 0; b < blocks; ++b) {
+            const uint64_t lo = host_block_offsets[b], size = host_block_offsets[b + 1] - lo;
+            if (size == 0) continue;
+            const uint32_t o = (uint32_t)(b / B), i = (uint32_t)(b % B);
+            const BlockOfPool block{dev_order + lo, (i + o) % B};
+            rc = train_hogwild(ctx, dev_pairs + 2 * lo, size, nullptr, &block);
+            if (rc) return rc;
+        }
+        ctx->next_g += count;
+        ctx->stats.samples_trained = ctx->next_g;
+        ctx->stats.pools_trained += 1;
+        return GV_OK;
+    });
+}
+
+int gv_draw_negatives_partitioned(gv_ctx *ctx, uint64_t first_g, uint64_t count, const uint32_t *host_v,
+                                  uint32_t *host_out) {
+    return guarded(ctx, [&]() -> int {
+        int rc = need_trainable(ctx);
+        if (rc) return rc;
+        if (ctx->cfg.partitions == 0 || ctx->part.size() != ctx->n)
+            return fail(ctx, GV_ESTATE, "the context was created without partitions");
+        if (count == 0) return GV_OK;
+        if (!host_v || !host_out) return fail(ctx, GV_EINVAL, "null argument");
+        if (count > (1ull << 31)) return fail(ctx, GV_EINVAL, "at most 2^31 samples per call");
+        for (uint64_t i = 0; i < count; ++i)
+            if (host_v[i] >= ctx->n) return fail(ctx, GV_EINVAL, "sample %llu names node id >= n", (unsigned long long)i);
+        const uint32_t K = ctx->cfg.num_neg;
+        rc = sync_all(ctx);
+        if (rc) return rc;
+        rc = ensure_negatives(ctx, count * K);
+        if (rc) return rc;
+        rc = ensure_eval_scratch(ctx, count * sizeof(uint32_t));
+        if (rc) return rc;
+        uint32_t *dev_v = (uint32_t *)ctx->eval_scratch;
+        GV_HIP(ctx, hipMemcpyAsync(dev_v, host_v, count * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->compute));
+        GV_HIP(ctx, gv::launch_draw_negatives_partitioned(ctx->dev_part_tables, ctx->dev_part_offsets, ctx->dev_part, dev_v,
+                                                          ctx->cfg.seed, first_g, count, K, ctx->negatives, ctx->compute));
+        GV_HIP(ctx, hipMemcpyAsync(host_out, ctx->negatives, count * K * sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                   ctx->compute));
+        GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
         return GV_OK;
     });
 }

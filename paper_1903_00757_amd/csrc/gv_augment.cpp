@@ -139,3 +139,90 @@ extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32
         return GV_EHIP;
     }
 }
+
+
+// Redistribution of a pool into the grid of orthogonal blocks (Sec. 3.2, Alg. 3, the Redistribute step, done on
+// the host as in the paper): a stable counting sort of the samples by block, blocks in training order.
+static int redistribute(uint32_t n, const uint32_t *host_part, uint32_t partitions, const uint32_t *host_pairs,
+                        uint64_t count, uint32_t threads, uint32_t *host_pairs_out, uint32_t *host_order,
+                        uint64_t *host_block_offsets) {
+    if (!host_block_offsets || partitions == 0 || partitions > GV_MAX_PARTITIONS) return GV_EINVAL;
+    const uint32_t B = partitions;
+    const uint64_t blocks = (uint64_t)B * B;
+    for (uint64_t b = 0; b <= blocks; ++b) host_block_offsets[b] = 0;
+    if (count == 0) return GV_OK;
+    if (!host_part || !host_pairs || !host_pairs_out || !host_order || n == 0 || count > (1ull << 32)) return GV_EINVAL;
+    const uint32_t workers = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(threads ? threads : 1, (count + 65535) / 65536));
+    // worker w owns samples [count w / workers, count (w + 1) / workers): counts per block, then its first
+    // output place per block = everything of earlier blocks + that block's samples of earlier workers
+    std::vector<std::vector<uint64_t>> place(workers, std::vector<uint64_t>(blocks, 0));
+    std::atomic<bool> broken{false};
+    auto block_of = [&](uint64_t i, uint64_t *b) {
+        const uint32_t u = host_pairs[2 * i], v = host_pairs[2 * i + 1];
+        if (u >= n || v >= n) return false;
+        const uint32_t pi = host_part[u], pj = host_part[v];
+        if (pi >= B || pj >= B) return false;
+        *b = (uint64_t)((pj + B - pi) % B) * B + pi;  // sub-episode (pj - pi) mod B, then the vertex partition
+        return true;
+    };
+    auto run = [&](auto &&body) {
+        if (workers == 1) {
+            body(0);
+            return;
+        }
+        std::vector<std::thread> pool;
+        pool.reserve(workers);
+        try {
+            for (uint32_t w = 0; w < workers; ++w) pool.emplace_back(body, w);
+        } catch (...) {
+            for (std::thread &t : pool) t.join();
+            throw;
+        }
+        for (std::thread &t : pool) t.join();
+    };
+    run([&](uint32_t w) {
+        for (uint64_t i = count * w / workers; i < count * (w + 1) / workers; ++i) {
+            uint64_t b;
+            if (!block_of(i, &b)) {
+                broken.store(true, std::memory_order_relaxed);
+                return;
+            }
+            place[w][b] += 1;
+        }
+    });
+    if (broken.load()) return GV_EINVAL;
+    uint64_t at = 0;
+    for (uint64_t b = 0; b < blocks; ++b) {
+        host_block_offsets[b] = at;
+        for (uint32_t w = 0; w < workers; ++w) {
+            const uint64_t mine = place[w][b];
+            place[w][b] = at;
+            at += mine;
+        }
+    }
+    host_block_offsets[blocks] = at;
+    run([&](uint32_t w) {
+        for (uint64_t i = count * w / workers; i < count * (w + 1) / workers; ++i) {
+            uint64_t b;
+            (void)block_of(i, &b);
+            const uint64_t to = place[w][b]++;
+            host_pairs_out[2 * to] = host_pairs[2 * i];
+            host_pairs_out[2 * to + 1] = host_pairs[2 * i + 1];
+            host_order[to] = (uint32_t)i;
+        }
+    });
+    return GV_OK;
+}
+
+extern "C" int gv_redistribute_pool(uint32_t n, const uint32_t *host_part, uint32_t partitions,
+                                    const uint32_t *host_pairs, uint64_t count, uint32_t threads,
+                                    uint32_t *host_pairs_out, uint32_t *host_order, uint64_t *host_block_offsets) {
+    try {
+        return redistribute(n, host_part, partitions, host_pairs, count, threads, host_pairs_out, host_order,
+                            host_block_offsets);
+    } catch (const std::bad_alloc &) {
+        return GV_ENOMEM;
+    } catch (...) {
+        return GV_EHIP;
+    }
+}

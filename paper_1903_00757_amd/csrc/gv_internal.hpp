@@ -11,9 +11,15 @@ namespace gv {
 struct TrainArgs {
     float *vertex;            // |V| x d, row-major
     float *context;           // |V| x d, row-major
-    const uint4 *alias;       // per node {threshold, alias, hot rank of the node | hot rank of the alias << 16, 0}
+    const uint4 *alias;       // alias table: per bucket {threshold, alias node, hot rank of the bucket's node | hot rank
+                              // of the alias << 16, the bucket's node}; the whole graph's table (bucket = node), or
+                              // the table of one partition of the nodes (orthogonal blocks)
+    uint32_t alias_n;         // buckets in that table
     const uint32_t *pairs;    // count x (u, v)
     const uint32_t *negatives;// deterministic mode: count x K precomputed draws (else unused)
+    const uint32_t *order;    // null, or per sample its index in the pool it was redistributed from: sample i then has
+                              // global position first_g + order[i] (its negatives and learning rate) instead of
+                              // first_g + i
     const uint16_t *rank;     // per node: its place among the nodes by falling degree (ties by id), 0xFFFF
                               // from place 65535 on ("hot rank")
     const uint32_t *ranked;   // bit i set: node i has a hot rank below 0xFFFF (small enough to stay in cache,
@@ -45,6 +51,12 @@ hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg
 // out[i*K + k] = negative k of positive sample first_g + i.
 hipError_t launch_draw_negatives(const uint4 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
                                  uint32_t num_neg, uint32_t *out, hipStream_t stream);
+// The same with one alias table per partition of the nodes: sample i draws from the table of the partition of its
+// context node v[i]; tables[] holds the tables one after the other, partition j owning buckets offsets[j] ..
+// offsets[j + 1] - 1.
+hipError_t launch_draw_negatives_partitioned(const uint4 *tables, const uint64_t *offsets, const uint8_t *part,
+                                             const uint32_t *v, uint64_t seed, uint64_t first_g, uint64_t count,
+                                             uint32_t num_neg, uint32_t *out, hipStream_t stream);
 // vertex ~ U(-0.5/d, 0.5/d) from Philox stream 1 (context is cleared by the caller).
 hipError_t launch_init_vertex(float *vertex, uint64_t rows, uint32_t dim, uint64_t seed, hipStream_t stream);
 

@@ -51,7 +51,8 @@ __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 // Negative k of positive sample g (Alg. 1, NegativeSampling; Sec. 4.3 alias
 // table): bucket = floor(R * n / 2^64) from the first two words, accepted when
 // the third word is below the bucket's threshold, else the bucket's alias.
-// The table entry also carries the hot ranks of both candidates.
+// The table entry also carries the node of the bucket (the table may cover a partition of the nodes only) and
+// the hot ranks of both candidates.
 struct Drawn {
     uint32_t id;
     uint32_t rank;
@@ -64,7 +65,7 @@ __device__ __forceinline__ Drawn draw_ranked_negative(const uint4 *__restrict__ 
     const uint32_t j = (uint32_t)__umul64hi(R, (uint64_t)n);
     const uint4 e = alias[j];
     const bool keep = r.z < e.x;
-    return Drawn{keep ? j : e.y, keep ? (e.z & 0xFFFFu) : (e.z >> 16)};
+    return Drawn{keep ? e.w : e.y, keep ? (e.z & 0xFFFFu) : (e.z >> 16)};
 }
 __device__ __forceinline__ uint32_t draw_negative(const uint4 *__restrict__ alias, uint32_t n, uint64_t seed,
                                                   uint64_t g, uint32_t k, uint32_t stream = 0u) {
@@ -327,10 +328,10 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
         const uint32_t in_chunk = min((uint32_t)kWave, a.count - base);
         const bool mine = (uint32_t)lane < in_chunk;
         const uint2 p = mine ? pairs[base + lane] : make_uint2(0u, 0u);
-        const uint64_t g = a.first_g + base + lane;
+        const uint64_t g = a.first_g + (a.order && mine ? a.order[base + lane] : base + lane);
         uint32_t neg[kK];
 #pragma unroll
-        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, g, k);
+        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.alias_n, a.seed, g, k);
         const float lr = learning_rate(a.lr0, a.lr_min_ratio, g, a.total);
         if (mine && (p.x >= a.n || p.y >= a.n)) *a.error_flag = 1u;
 
@@ -477,6 +478,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                         held = 1u;
                         row = p.y;
                     }
+                    const uint64_t g = a.first_g + (a.order ? a.order[tile_base + t] : tile_base + t);
                     // the walk below takes the sample from this record instead of drawing it again
                     uint32_t *record = a.records + (size_t)(tile_base + t) * kRecord;
                     uint32_t warm_negatives = 0;
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                     record[1] = p.y;
 #pragma unroll
                     for (int k = 0; k < kK; ++k) {
-                        const Drawn nk = draw_ranked_negative(a.alias, a.n, a.seed, a.first_g + tile_base + t, k);
+                        const Drawn nk = draw_ranked_negative(a.alias, a.alias_n, a.seed, g, k);
                         record[2 + k] = nk.id;
                         warm_negatives |= (nk.rank < a.warm_ranks ? 1u : 0u) << k;
                         if (nk.rank < best) {
@@ -542,7 +544,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             for (int k = 0; k < kK; ++k) id[2 + k] = mine ? record[2 + k] : 0u;
             // bit j: row j of the sample is warm (u and v from the sort word, the negatives from the record)
             const uint32_t warm = (word & 3u) | (mine ? record[2 + kK] << 2 : 0u);
-            const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + pos, a.total);
+            const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + (a.order && mine ? a.order[pos] : pos), a.total);
             const uint32_t h = (word >> 15) & 7u;  // number of the stationary row
             uint32_t stationary_id = id[0];
 #pragma unroll
@@ -838,7 +840,7 @@ __global__ __launch_bounds__(kBlock) void k_eval_loss(TrainArgs a, double *__res
         const uint2 p = mine ? pairs[base + lane] : make_uint2(0u, 0u);
         uint32_t neg[kK];
 #pragma unroll
-        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.n, a.seed, (uint64_t)base + lane, k, 2u);
+        for (int k = 0; k < kK; ++k) neg[k] = draw_negative(a.alias, a.alias_n, a.seed, (uint64_t)base + lane, k, 2u);
         if (mine && (p.x >= a.n || p.y >= a.n)) *a.error_flag = 1u;
         for (uint32_t i = 0; i < in_chunk; ++i) {
             const uint32_t u = lane_value(p.x, i), v = lane_value(p.y, i);
@@ -905,6 +907,23 @@ __global__ __launch_bounds__(kBlock) void k_draw_negatives(const uint4 *__restri
         const uint64_t i = t / num_neg;
         const uint32_t k = (uint32_t)(t - i * num_neg);
         out[t] = draw_negative(alias, n, seed, first_g + i, k);
+    }
+}
+
+// Negatives restricted to a partition (Sec. 3.2): sample i draws from the alias table of the partition of its
+// context node v[i].
+__global__ __launch_bounds__(kBlock) void k_draw_negatives_partitioned(const uint4 *__restrict__ tables,
+                                                                       const uint64_t *__restrict__ offsets,
+                                                                       const uint8_t *__restrict__ part,
+                                                                       const uint32_t *__restrict__ v, uint64_t seed,
+                                                                       uint64_t first_g, uint64_t count, uint32_t num_neg,
+                                                                       uint32_t *__restrict__ out) {
+    const uint64_t total = count * num_neg;
+    for (uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x; t < total; t += (uint64_t)gridDim.x * kBlock) {
+        const uint64_t i = t / num_neg;
+        const uint32_t k = (uint32_t)(t - i * num_neg);
+        const uint32_t j = part[v[i]];
+        out[t] = draw_negative(tables + offsets[j], (uint32_t)(offsets[j + 1] - offsets[j]), seed, first_g + i, k);
     }
 }
 
@@ -1143,6 +1162,18 @@ hipError_t launch_draw_negatives(const uint4 *alias, uint32_t n, uint64_t seed, 
     const uint32_t blocks = (uint32_t)(wanted < 65536 ? wanted : 65536);
     hipLaunchKernelGGL(k_draw_negatives, dim3(blocks), dim3(kBlock), 0, stream, alias, n, seed, first_g, count,
                        num_neg, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_draw_negatives_partitioned(const uint4 *tables, const uint64_t *offsets, const uint8_t *part,
+                                             const uint32_t *v, uint64_t seed, uint64_t first_g, uint64_t count,
+                                             uint32_t num_neg, uint32_t *out, hipStream_t stream) {
+    const uint64_t total = count * num_neg;
+    if (total == 0) return hipSuccess;
+    const uint64_t wanted = (total + kBlock - 1) / kBlock;
+    const uint32_t blocks = (uint32_t)(wanted < 65536 ? wanted : 65536);
+    hipLaunchKernelGGL(k_draw_negatives_partitioned, dim3(blocks), dim3(kBlock), 0, stream, tables, offsets, part, v, seed,
+                       first_g, count, num_neg, out);
     return hipGetLastError();
 }
 

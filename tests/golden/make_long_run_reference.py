@@ -12,6 +12,7 @@ checkpoints are written as they are reached, and the test uses those that exist)
     python tests/golden/make_long_run_reference.py c2
     python tests/golden/make_long_run_reference.py c3
     python tests/golden/make_long_run_reference.py c4
+    python tests/golden/make_long_run_reference.py c2-blocks     (c2 under the orthogonal-block schedule, 25 minutes)
 
 A second argument replaces the training seed (the key of the negative-sampling stream) and writes
 long_run_<name>_seed<seed>.txt: the same run with other negatives.  How far two such runs of the
@@ -44,7 +45,13 @@ SETUPS = {
                neg_weight=5.0, lr0=0.025, train_seed=1234, init_seed=1, walk_seed=600, eval_walk_seed=778,
                eval_count=1 << 18, eval_seed=99, negative_pair_seed=62, walk_length=40, window=5),
 }
-CHECKPOINTS = {"c2": (1, 2, 4, 8, 16, 24, 32), "c3": (1, 2, 3, 4), "c4": (4, 16, 32, 64, 96, 128, 160, 192, 238)}
+# c2 under the orthogonal-block schedule of Sec. 3.2: 8 partitions, episodes of 8 pools (2^27 samples) that are
+# redistributed into the 8 x 8 grid and trained block after block with negatives restricted to the block's
+# context partition; same graph, pools, seeds and learning-rate schedule as c2, so the two files differ by the
+# schedule alone
+SETUPS["c2-blocks"] = dict(SETUPS["c2"], partitions=8, episode_pools=8)
+CHECKPOINTS = {"c2": (1, 2, 4, 8, 16, 24, 32), "c3": (1, 2, 3, 4), "c4": (4, 16, 32, 64, 96, 128, 160, 192, 238),
+               "c2-blocks": (8, 16, 24, 32)}
 
 
 def pool_of(offsets, adj, seed, first_walk, count, s):
@@ -69,17 +76,26 @@ def main():
     eval_pool = pool_of(offsets, adj, s["eval_walk_seed"], 0, s["eval_count"], s)
     na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    B, E = s.get("partitions", 0), s.get("episode_pools", 1)
+    if B:
+        part = oracle.zigzag_partition(deg, B)
+        tables = oracle.partition_alias(deg, B, part)
     vertex, context = oracle.init_embeddings(s["init_seed"], n, s["dim"])
     lines = [f"# written by tests/golden/make_long_run_reference.py {name} (CPU oracle only)"]
     lines += [f"# {k} = {v}" for k, v in s.items()]
     lines.append("# pools_trained eval_loss link_prediction_auc max_vertex_norm max_context_norm")
     with open(out_path, "w") as f:
         f.write("\n".join(lines) + "\n")
-    for k in range(pools):
+    for k in range(E - 1, pools, E):  # k = last pool of the step: one pool, or one episode of E pools
         t0 = time.time()
-        pool = pool_of(offsets, adj, s["walk_seed"], k * walks_per_pool, P, s)
-        oracle.train(vertex, context, pool, K=s["num_neg"], first_g=k * P, T=P * pools, lr0=s["lr0"],
-                     lr_min_ratio=0.0, w=s["neg_weight"], seed=s["train_seed"], thresh=thresh, alias=alias)
+        first = k + 1 - E
+        pool = np.concatenate([pool_of(offsets, adj, s["walk_seed"], r * walks_per_pool, P, s) for r in range(first, k + 1)])
+        kw = dict(K=s["num_neg"], first_g=first * P, T=P * pools, lr0=s["lr0"], lr_min_ratio=0.0, w=s["neg_weight"],
+                  seed=s["train_seed"])
+        if B:
+            oracle.train_blocked(vertex, context, pool, B=B, part=part, tables=tables, **kw)
+        else:
+            oracle.train(vertex, context, pool, thresh=thresh, alias=alias, **kw)
         print(f"pool {k + 1}/{pools}: {time.time() - t0:.0f} s", flush=True)
         if k + 1 in CHECKPOINTS[name]:
             loss = oracle.loss(vertex, context, eval_pool, K=s["num_neg"], w=s["neg_weight"], seed=s["eval_seed"],

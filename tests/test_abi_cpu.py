@@ -43,12 +43,13 @@ def test_config_struct_layout_matches_header(gv):
     assert ctypes.sizeof(gv.binding.gv_config) == 72
     assert gv.binding.gv_config.total_samples.offset == 24
     assert gv.binding.gv_config.device.offset == 48
-    assert gv.binding.gv_config.pool_slots.offset == 64
+    assert gv.binding.gv_config.pool_slots.offset == 64 and gv.binding.gv_config.partitions.offset == 68
     assert ctypes.sizeof(gv.binding.gv_stats) == 80
     # constants of the header and of the binding agree
     text = open(os.path.join(ROOT, "include", "gvhot.h")).read()
     assert float(re.search(r"#define GV_NEG_WEIGHT_DEFAULT \((-?[0-9.]+)f\)", text).group(1)) == gv.GV_NEG_WEIGHT_DEFAULT
     assert int(re.search(r"#define GV_MAX_POOL_SLOTS (\d+)", text).group(1)) == gv.GV_MAX_POOL_SLOTS
+    assert int(re.search(r"#define GV_MAX_PARTITIONS (\d+)", text).group(1)) == gv.GV_MAX_PARTITIONS
     assert re.search(r"GV_SCHEDULE_AUTO = (\d+)", text).group(1) == str(gv.GV_SCHEDULE_AUTO)
     assert re.search(r"#define GV_STATIC_SCRATCH_WORDS \(1u << (\d+)\)", text).group(1) == "22" and \
         gv.GV_STATIC_SCRATCH_WORDS == 1 << 22
@@ -62,7 +63,7 @@ def test_argument_errors_need_no_device(gv):
     assert e.value.code == gv.GV_EINVAL and "dim" in str(e.value)
     for bad in (dict(num_neg=0), dict(num_neg=6), dict(total_samples=0), dict(pool_capacity=0), dict(mode=7),
                 dict(lr0=float("nan")), dict(neg_weight=-2.0), dict(neg_weight=float("inf")), dict(pool_slots=1),
-                dict(pool_slots=17), dict(schedule=3)):
+                dict(pool_slots=17), dict(schedule=3), dict(partitions=1), dict(partitions=65)):
         kw = dict(dim=128, num_neg=1, total_samples=10, pool_capacity=10)
         kw.update(bad)
         with pytest.raises(gv.GvError) as e:

@@ -1094,6 +1094,166 @@ def test_device_producer_argument_errors(gv, tiny_graph):
         assert gv.gv_augment_device(ctx, 0, seed=1, count=0) == 0  # nothing to do
 
 
+# --------------------------------------------------------------------------- orthogonal blocks
+@pytest.mark.parametrize("B", [2, 8])
+def test_partitions_and_their_alias_tables_are_bit_identical(gv, tiny_graph, B):
+    g = tiny_graph
+    deg = g["deg"].copy()
+    deg[::97] = 0
+    seed = 0x1234567890ABCDEF
+    with context_for(gv, dim=64, num_neg=3, total_samples=1, pool_capacity=1, partitions=B, seed=seed) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        part, offsets, members, thresh, alias = gv.gv_get_partitions(ctx, g["n"], B)
+        rng = np.random.default_rng(B)
+        v = rng.integers(g["n"], size=100_003).astype(np.uint32)
+        got = gv.gv_draw_negatives_partitioned(ctx, 2**40 + 17, v, 3)
+        whole_t, whole_a = gv.gv_get_alias(ctx, g["n"])  # the whole-graph table is still there, unchanged
+        plain = gv.gv_draw_negatives(ctx, 5, 1000, 3)
+    ref_part = oracle.zigzag_partition(deg, B)
+    tables = oracle.partition_alias(deg, B, ref_part)
+    assert np.array_equal(part, ref_part)
+    for got_table, ref_table in zip((offsets, members, thresh, alias), tables):
+        assert np.array_equal(got_table, ref_table)
+    assert np.array_equal(got, oracle.draw_negatives_partitioned(seed, 2**40 + 17, v, 3, ref_part, tables))
+    ref_t, ref_a = oracle.alias_build(oracle.degree_weights(deg))
+    assert np.array_equal(whole_t, ref_t) and np.array_equal(whole_a, ref_a)
+    assert np.array_equal(plain, oracle.draw_negatives(seed, 5, 1000, 3, ref_t, ref_a))
+
+
+def train_blocks(gv, ctx, part, B, pool, threads=4):
+    """Redistribute on the host, copy to the device, train block by block."""
+    import torch
+
+    sorted_pairs, order, offsets = gv.gv_redistribute_pool(part, B, pool, threads=threads)
+    dev_pairs = torch.from_numpy(sorted_pairs.view(np.int32)).cuda()
+    dev_order = torch.from_numpy(order.view(np.int32)).cuda()
+    torch.cuda.synchronize()
+    gv.gv_train_device_blocks(ctx, dev_pairs.data_ptr(), dev_order.data_ptr(), offsets, pool.shape[0])
+    gv.gv_sync(ctx)  # the device arrays may go once the launches have ended
+
+
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, ATOMIC)])
+def test_block_training_single_steps(gv, policy):
+    """Orthogonal-block training of a sparse pool: samples whose rows nobody else names (negatives restricted to
+    the partition of v) equal one oracle step at the position they had in the pool; rows never named stay bit for
+    bit.  Two pools in a row: positions continue across calls."""
+    n, d, K, w, seed, B = 200_000, 128, 2, 2.5, 31, 8
+    sizes = [9001, 4000]
+    count = sum(sizes)
+    rng = np.random.default_rng(23)
+    deg = rng.integers(1, 50, size=n).astype(np.uint32)
+    pool = rng.integers(n, size=(count, 2)).astype(np.uint32)
+    vertex, context = random_embeddings(n, d, seed=5)
+    part = oracle.zigzag_partition(deg, B)
+    tables = oracle.partition_alias(deg, B, part)
+    negs = oracle.draw_negatives_partitioned(seed, 0, pool[:, 1].copy(), K, part, tables)
+    schedule, coherence = policy
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=10 * count, seed=seed,
+                     pool_capacity=8, lr0=LR0, coherence=coherence, schedule=schedule, partitions=B) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+        train_blocks(gv, ctx, part, B, pool[:sizes[0]])
+        train_blocks(gv, ctx, part, B, pool[sizes[0]:])
+        assert gv.gv_get_stats(ctx)["samples_trained"] == count
+        got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+        got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+    idx, cu, cc = singly_touched(pool, negs, n)
+    assert idx.size > 0.3 * count and (idx >= sizes[0]).sum() > 300
+    picked = np.concatenate([idx[idx < sizes[0]][:700], idx[idx >= sizes[0]][:700]])
+    worst = check_single_steps(pool, negs, picked, 0, 10 * count, K, w, seed, vertex, context, got_v, got_c,
+                               tables[2], tables[3])
+    assert worst <= 1e-5, worst
+    assert np.array_equal(got_v[cu == 0], vertex[cu == 0]) and np.array_equal(got_c[cc == 0], context[cc == 0])
+    assert not np.array_equal(got_v[cu > 0], vertex[cu > 0])
+
+
+@pytest.mark.parametrize("policy", [(TILED, MIXED), (POOL_ORDER, ATOMIC)])
+def test_block_training_quality_matches_blocked_oracle(gv, policy):
+    """Configuration 1 trained in orthogonal blocks (4 partitions, pools of 2^18 samples = episodes): against the
+    oracle run in the same block order with the same restricted negatives, final loss within 2 % and
+    link-prediction AUC within 0.005.  The oracle's plain run is printed beside it: what the schedule itself costs."""
+    n, src, dst = W.make_graph("tiny", cache=False)
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, 0.05, seed=31)
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    total, d, K, w, B, P = 2_000_000, 128, 1, 5.0, 4, 1 << 18
+    pool, _ = oracle.augment(101, offsets, adj, 40, 5, total, shuffle_seed=7)
+    pools = [pool[i:i + P] for i in range(0, total, P)]
+    eval_pool, _ = oracle.augment(202, offsets, adj, 40, 5, 1 << 18, shuffle_seed=8)
+    vertex, context = oracle.init_embeddings(1, n, d)
+    part = oracle.zigzag_partition(deg, B)
+    tables = oracle.partition_alias(deg, B, part)
+    schedule, coherence = policy
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=total, seed=1234,
+                     pool_capacity=8, lr0=LR0, coherence=coherence, schedule=schedule, partitions=B) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+        for p in pools:
+            train_blocks(gv, ctx, part, B, p)
+        got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+        got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+    ref_v, ref_c = vertex.copy(), context.copy()
+    g = 0
+    for p in pools:
+        oracle.train_blocked(ref_v, ref_c, p, K=K, first_g=g, T=total, lr0=LR0, lr_min_ratio=0.0, w=w, seed=1234, B=B,
+                             part=part, tables=tables)
+        g += p.shape[0]
+    plain_v, plain_c = run_oracle(deg, K, w, pools, vertex, context, total, 1234)
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=32)
+    loss = {name: evaluation_loss(deg, v, c, eval_pool, K, w)
+            for name, v, c in (("gpu", got_v, got_c), ("blocked", ref_v, ref_c), ("plain", plain_v, plain_c))}
+    auc = {name: oracle.link_prediction_auc(v, te_s, te_d, na, nb)
+           for name, v in (("gpu", got_v), ("blocked", ref_v), ("plain", plain_v))}
+    print(f"blocks policy={policy}: loss gpu {loss['gpu']:.5f} / blocked oracle {loss['blocked']:.5f} / plain oracle "
+          f"{loss['plain']:.5f}; auc {auc['gpu']:.4f} / {auc['blocked']:.4f} / {auc['plain']:.4f}")
+    assert abs(loss["gpu"] - loss["blocked"]) <= 0.02 * loss["blocked"]
+    assert abs(auc["gpu"] - auc["blocked"]) <= 0.005
+
+
+def test_block_training_argument_errors(gv, tiny_graph):
+    import torch
+
+    g = tiny_graph
+    pool = np.stack([g["src"][:1000], g["dst"][:1000]], axis=1)
+    buf = torch.zeros((1000, 2), dtype=torch.int32, device="cuda")
+    order = torch.zeros(1000, dtype=torch.int32, device="cuda")
+    offsets = np.zeros(17, dtype=np.uint64)
+    with context_for(gv, dim=64, num_neg=1, total_samples=10_000, pool_capacity=8) as ctx:  # no partitions
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        for call in (lambda: gv.gv_get_partitions(ctx, g["n"], 4),
+                     lambda: gv.gv_train_device_blocks(ctx, buf.data_ptr(), order.data_ptr(), offsets, 0),
+                     lambda: gv.gv_draw_negatives_partitioned(ctx, 0, pool[:, 1].copy(), 1)):
+            with pytest.raises(gv.GvError) as e:
+                call()
+            assert e.value.code == gv.GV_ESTATE
+    with context_for(gv, dim=64, num_neg=1, total_samples=10_000, pool_capacity=8, partitions=4) as ctx:
+        gv.gv_set_degrees(ctx, g["deg"])
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, 1)
+        gv.gv_train_device_blocks(ctx, 0, 0, offsets, 0)  # empty pool
+        wrong = offsets.copy()
+        wrong[-1] = 999
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_train_device_blocks(ctx, buf.data_ptr(), order.data_ptr(), wrong, 1000)
+        assert e.value.code == gv.GV_EINVAL  # offsets do not end at count
+        wrong[-1], wrong[3] = 1000, 2000
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_train_device_blocks(ctx, buf.data_ptr(), order.data_ptr(), wrong, 1000)
+        assert e.value.code == gv.GV_EINVAL  # not ascending
+        assert gv.gv_get_stats(ctx)["samples_trained"] == 0
+    with context_for(gv, dim=64, num_neg=1, total_samples=10_000, pool_capacity=8, partitions=4) as ctx:
+        gv.gv_set_degrees(ctx, np.array([3, 0, 0, 0, 0, 0, 0, 0], dtype=np.uint32))
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_build_alias(ctx, 0.75)  # a partition without any weight
+        assert e.value.code == gv.GV_EINVAL
+
+
 def read_long_run_reference(name="c2"):
     """tests/golden/long_run_<name>.txt: the set-up and the oracle's checkpoints (written by the script beside it)."""
     setup, rows = {}, []

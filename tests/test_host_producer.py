@@ -92,3 +92,23 @@ def test_library_producer_rejects_bad_arguments(gv, tiny_graph):
         gv.gv_augment(np.zeros(3, dtype=np.uint64), np.zeros(0, dtype=np.uint32), seed=1, count=10)  # no edges
     pairs, used = gv.gv_augment(g["offsets"], g["adj"], seed=1, count=0)
     assert pairs.shape == (0, 2) and used == 0
+
+
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_library_redistribution_equals_oracle_block_order(gv, tiny_graph, threads):
+    """The Redistribute step of the orthogonal-block schedule (Sec. 3.2, Alg. 3): the library's stable sort of a
+    pool by block gives exactly the oracle's order and block boundaries, for any number of workers."""
+    g = tiny_graph
+    for B, count in ((2, 70_001), (5, 300_000), (8, 1), (3, 0)):
+        part = oracle.zigzag_partition(g["deg"], B)
+        pool, _ = oracle.augment(40 + B, g["offsets"], g["adj"], 40, 5, max(count, 1), shuffle_seed=3)
+        pool = pool[:count]
+        out, order, offsets = gv.gv_redistribute_pool(part, B, pool, threads=threads)
+        ref_order, ref_offsets = oracle.block_order(pool, B, part)
+        assert np.array_equal(order, ref_order) and np.array_equal(offsets, ref_offsets)
+        assert np.array_equal(out, pool[ref_order])
+    bad, _ = oracle.augment(1, g["offsets"], g["adj"], 40, 5, 1000)
+    bad[5, 0] = g["n"]
+    with pytest.raises(gv.GvError) as e:
+        gv.gv_redistribute_pool(part, 3, bad, threads=threads)
+    assert e.value.code == gv.GV_EINVAL
