@@ -36,6 +36,15 @@ def lib():
         L.orc_augment.argtypes = [C.c_uint64, C.c_uint64, u64p, u32p, C.c_uint32, C.c_uint32,
                                   C.c_uint64, C.c_uint64, u32p]
         L.orc_augment.restype = C.c_uint64
+        L.orc_weighted_degrees.argtypes = [C.c_uint64, u64p, f32p, f64p]
+        L.orc_weighted_degrees.restype = None
+        L.orc_weights_pow34.argtypes = [C.c_uint64, f64p, f64p]
+        L.orc_weights_pow34.restype = None
+        L.orc_neighbor_alias.argtypes = [C.c_uint64, u64p, f32p, u32p, u32p]
+        L.orc_neighbor_alias.restype = C.c_int
+        L.orc_augment_weighted.argtypes = [C.c_uint64, C.c_uint64, u64p, u32p, u32p, u32p, u32p, u32p, C.c_uint32,
+                                           C.c_uint32, C.c_uint64, C.c_uint64, u32p]
+        L.orc_augment_weighted.restype = C.c_uint64
         L.orc_shuffle.argtypes = [C.c_uint64, C.c_uint64, u32p]
         L.orc_shuffle.restype = None
         L.orc_pseudo_shuffle.argtypes = [C.c_uint64, C.c_uint32, u32p, u32p]
@@ -121,6 +130,53 @@ def augment(seed, offsets, adj, walk_length, window, count, first_walk=0, shuffl
                               walk_length, window, first_walk, count, _p(pairs, C.c_uint32))
     if shuffle_seed is not None:
         lib().orc_shuffle(shuffle_seed, count, _p(pairs, C.c_uint32))
+    return pairs, int(walks)
+
+
+def weighted_degrees(offsets, weights):
+    offsets = _arr(offsets, np.uint64)
+    weights = _arr(weights, np.float32)
+    out = np.empty(offsets.size - 1, dtype=np.float64)
+    lib().orc_weighted_degrees(out.size, _p(offsets, C.c_uint64), _p(weights, C.c_float), _p(out, C.c_double))
+    return out
+
+
+def weights_pow34(wdeg):
+    wdeg = _arr(wdeg, np.float64)
+    q = np.empty_like(wdeg)
+    lib().orc_weights_pow34(wdeg.size, _p(wdeg, C.c_double), _p(q, C.c_double))
+    return q
+
+
+def neighbor_alias(offsets, weights):
+    """Per-row alias tables over the edge weights: (thresh, alias) per adjacency entry, alias local to the row."""
+    offsets = _arr(offsets, np.uint64)
+    weights = _arr(weights, np.float32)
+    thresh = np.zeros(weights.size, dtype=np.uint32)
+    alias = np.zeros(weights.size, dtype=np.uint32)
+    rc = lib().orc_neighbor_alias(offsets.size - 1, _p(offsets, C.c_uint64), _p(weights, C.c_float),
+                                  _p(thresh, C.c_uint32), _p(alias, C.c_uint32))
+    if rc:
+        raise ValueError("an adjacency row has no weight")
+    return thresh, alias
+
+
+def walk_tables(offsets, weights):
+    """Everything a weighted walk draws from: (node_thresh, node_alias, nbr_thresh, nbr_alias)."""
+    node_thresh, node_alias = alias_build(weighted_degrees(offsets, weights))
+    nbr_thresh, nbr_alias = neighbor_alias(offsets, weights)
+    return node_thresh, node_alias, nbr_thresh, nbr_alias
+
+
+def augment_weighted(seed, offsets, adj, tables, walk_length, window, count, first_walk=0):
+    offsets = _arr(offsets, np.uint64)
+    adj = _arr(adj, np.uint32)
+    node_thresh, node_alias, nbr_thresh, nbr_alias = tables
+    pairs = np.empty((count, 2), dtype=np.uint32)
+    walks = lib().orc_augment_weighted(seed, offsets.size - 1, _p(offsets, C.c_uint64), _p(adj, C.c_uint32),
+                                       _p(node_thresh, C.c_uint32), _p(node_alias, C.c_uint32),
+                                       _p(nbr_thresh, C.c_uint32), _p(nbr_alias, C.c_uint32), walk_length, window,
+                                       first_walk, count, _p(pairs, C.c_uint32))
     return pairs, int(walks)
 
 

@@ -187,6 +187,80 @@ uint64_t orc_augment(uint64_t seed, uint64_t n, const uint64_t *offsets, const u
     return w - first_walk;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Weighted graphs.  Sec. 4.3 names the alias table trick for online augmentation too: on a graph with edge
+ * weights the departure node is drawn in proportion to its weighted degree and every step goes to a
+ * neighbour in proportion to the weight of the edge, each with an alias table (one over the nodes, one per
+ * adjacency row); negatives follow the 3/4 power of the weighted degree.                                  */
+
+/* Weighted degree: the edge weights of a row of the CSR adjacency, summed left to right in fp64.         */
+void orc_weighted_degrees(uint64_t n, const uint64_t *offsets, const float *weights, double *wdeg)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        double total = 0.0;
+        for (uint64_t e = offsets[i]; e < offsets[i + 1]; ++e) total += (double)weights[e];
+        wdeg[i] = total;
+    }
+}
+
+/* The 3/4 power of a weighted degree, with square roots only (as for plain degrees).                     */
+void orc_weights_pow34(uint64_t n, const double *wdeg, double *q)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        double r = sqrt(wdeg[i]);
+        q[i] = r * sqrt(r);
+    }
+}
+
+/* One alias table per adjacency row over that row's edge weights: entry e of row x (offsets[x] <= e <
+ * offsets[x+1]) is accepted below thresh[e], otherwise the step takes entry offsets[x] + alias[e] of the
+ * same row.  Returns 0, or -1 when a row has entries but no weight.                                       */
+int orc_neighbor_alias(uint64_t n, const uint64_t *offsets, const float *weights, uint32_t *thresh, uint32_t *alias)
+{
+    for (uint64_t x = 0; x < n; ++x) {
+        uint64_t begin = offsets[x], deg = offsets[x + 1] - begin;
+        if (deg == 0) continue;
+        double *q = (double *)malloc(deg * sizeof(double));
+        for (uint64_t e = 0; e < deg; ++e) q[e] = (double)weights[begin + e];
+        int rc = orc_alias_build(deg, q, thresh + begin, alias + begin);
+        free(q);
+        if (rc != 0) return -1;
+    }
+    return 0;
+}
+
+/* Online augmentation on a weighted graph (Sec. 3.1, Alg. 2 with the tables above): as orc_augment, but walk w
+ * departs from an alias draw over the nodes (weights = weighted degrees) and step t is an alias draw over the
+ * current node's row; both take their random words like the unweighted walk (stream 4, counter (w, t)).   */
+uint64_t orc_augment_weighted(uint64_t seed, uint64_t n, const uint64_t *offsets, const uint32_t *adj,
+                              const uint32_t *node_thresh, const uint32_t *node_alias,
+                              const uint32_t *nbr_thresh, const uint32_t *nbr_alias,
+                              uint32_t L, uint32_t s, uint64_t first_walk, uint64_t count, uint32_t *pairs)
+{
+    uint32_t *path = (uint32_t *)malloc(((size_t)L + 1) * sizeof(uint32_t));
+    uint64_t produced = 0, w = first_walk;
+    while (produced < count) {
+        uint32_t r[4];
+        words(seed, w, 0, STREAM_WALK, r);
+        path[0] = alias_draw(r, n, node_thresh, node_alias);
+        for (uint32_t t = 1; t <= L; ++t) {
+            uint32_t x = path[t - 1];
+            uint64_t begin = offsets[x], deg = offsets[x + 1] - begin;
+            words(seed, w, t, STREAM_WALK, r);
+            path[t] = adj[begin + alias_draw(r, deg, nbr_thresh + begin, nbr_alias + begin)];
+        }
+        for (uint32_t i = 0; i <= L && produced < count; ++i)
+            for (uint32_t j = i + 1; j <= L && j <= i + s && produced < count; ++j) {
+                pairs[2 * produced] = path[i];
+                pairs[2 * produced + 1] = path[j];
+                ++produced;
+            }
+        ++w;
+    }
+    free(path);
+    return w - first_walk;
+}
+
 /* Uniform shuffle of a pool (Alg. 2, the Shuffle call): Fisher-Yates from the
  * last position down, position i swapped with a uniform j in [0, i].         */
 void orc_shuffle(uint64_t seed, uint64_t count, uint32_t *pairs)

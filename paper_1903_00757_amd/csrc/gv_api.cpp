@@ -733,7 +733,10 @@ int gv_build_alias(gv_ctx *ctx, double power) {
 #define GV_TUNE_WARM 0.1
 #endif
         const uint32_t B = ctx->cfg.partitions;
-        const double kInFlight = 8192.0 * (B > 0 ? (double)B : 1.0), kWarmThreshold = GV_TUNE_WARM;
+#ifndef GV_TUNE_WARM_BLOCKS
+#define GV_TUNE_WARM_BLOCKS 1
+#endif
+        const double kInFlight = 8192.0 * (B > 0 && GV_TUNE_WARM_BLOCKS ? (double)B : 1.0), kWarmThreshold = GV_TUNE_WARM;
         const uint32_t kRanked = 0xFFFFu;
         auto hotter = [&](uint32_t x, uint32_t y) {
             return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;

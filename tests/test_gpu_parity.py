@@ -969,6 +969,67 @@ def test_rows_beyond_2_to_32_elements(gv):
             assert np.array_equal(last, oracle.init_vertex_rows(9, n - 3, 1, d))
 
 
+def test_configuration_5_size_isolated_samples(gv):
+    """The node set of configuration 5 (6.6*10^7 nodes, degrees of the Chung-Lu model with exponent 2.2 for 1.8*10^9
+    edges; 67.6 GB of embeddings) with a pool whose endpoints come from the degree marginal (the graph's adjacency
+    is not generated): the alias table of that size equals the oracle's bit for bit, so do the negatives, and every
+    sample of a 2^22-sample pool whose three rows nobody else names is exactly one oracle step from the initial
+    embeddings, in the launch configuration bench.py times for this workload (device pool, default policy)."""
+    import torch
+
+    n, deg = W.expected_degrees("c5-marginal")
+    d, K, w, seed, T, count = 128, 1, 5.0, 1234, 10_000_000_000, 1 << 22
+    first_g = 6_000_000_000
+    pool = W.marginal_pool(deg, count, seed=505)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    negs = oracle.draw_negatives(seed, first_g, count, K, thresh, alias)
+    print(f"configuration 5 size: tables ready ({n} nodes)", flush=True)
+    dev_pool = torch.from_numpy(pool.view(np.int32)).cuda()
+    torch.cuda.synchronize()
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=8, lr0=LR0) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        got_t, got_a = gv.gv_get_alias(ctx, n)
+        assert np.array_equal(got_t, thresh) and np.array_equal(got_a, alias)
+        del got_t, got_a
+        assert np.array_equal(gv.gv_draw_negatives(ctx, first_g, 1 << 20, K), negs[:1 << 20])
+        gv.gv_init_embeddings(ctx, 9)
+        gv.gv_set_position(ctx, first_g)
+        gv.gv_train_device_pool(ctx, dev_pool.data_ptr(), count)
+        gv.gv_sync(ctx)
+        stats = gv.gv_get_stats(ctx)
+        assert stats["samples_trained"] == first_g + count and stats["tiled_launches"] == 1
+        idx, cu, cc = singly_touched(pool, negs, n)
+        assert idx.size > 1000
+        rng = np.random.default_rng(0)
+        far = idx[np.argsort(pool[idx, 0])[-100:]]  # the samples with the highest vertex rows
+        check = np.concatenate([rng.choice(idx, size=300, replace=False), far])
+        worst = 0.0
+        for i in check:
+            u, v, z = int(pool[i, 0]), int(pool[i, 1]), int(negs[i, 0])
+            x0 = oracle.init_vertex_rows(9, u, 1, d)
+            sub_v, sub_c = x0.copy(), np.zeros((2, d), dtype=np.float32)
+            oracle.train(sub_v, sub_c, np.array([[0, 0]], dtype=np.uint32), K=1, first_g=first_g + int(i), T=T, lr0=LR0,
+                         lr_min_ratio=0.0, w=w, seed=seed, thresh=thresh[:2], alias=alias[:2],
+                         negatives=np.array([1], dtype=np.uint32))
+            got_x = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=u)[0]
+            got_v = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=v)[0]
+            got_z = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=z)[0]
+            scale = np.abs(x0).max()
+            worst = max(worst, np.abs(got_x - sub_v[0]).max() / scale, np.abs(got_v - sub_c[0]).max() / scale,
+                        np.abs(got_z - sub_c[1]).max() / scale)
+            assert np.abs(got_v).max() > 0 and np.abs(got_z).max() > 0
+        print(f"configuration 5 size: {idx.size} isolated samples, {check.size} checked, worst rel. error {worst:.2e}")
+        assert worst <= 1e-5, worst
+        # rows nobody names keep their initial value, at both ends of the matrices
+        for row in (int(np.nonzero(cu == 0)[0][0]), int(np.nonzero(cu == 0)[0][-1])):
+            assert np.array_equal(gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=row)[0],
+                                  oracle.init_vertex_rows(9, row, 1, d)[0])
+        for row in (int(np.nonzero(cc == 0)[0][0]), int(np.nonzero(cc == 0)[0][-1])):
+            assert not gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=row).any()
+
+
 # --------------------------------------------------------------------------- evaluation on the device
 @pytest.mark.parametrize("d,K,w", [(128, 1, 5.0), (96, 1, 5.0), (512, 5, 1.0), (64, 3, 2.0)])
 def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w):
