@@ -276,6 +276,33 @@ int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *
 int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t window, uint64_t first_walk,
                       uint64_t count, uint32_t shuffle, uint32_t *dev_pairs, uint64_t *walks_used);
 
+/* Weighted graphs (Sec. 4.3: the alias table trick also serves online augmentation): the departure node of a walk is
+ * drawn in proportion to its weighted degree (the sum of the weights of its edges) and every step goes to a
+ * neighbour in proportion to the weight of the edge, both with alias tables; negatives follow the 3/4 power of
+ * the weighted degree.  Weights are float >= 0 per adjacency entry (both directions of an edge carry its weight).
+ * gv_build_walk_tables (host, no context): host_wdeg[n] (may be NULL) = weighted degrees, row sums left to right
+ *   in fp64; host_node_thresh/alias[n] = alias table over the nodes with those weights; host_nbr_thresh/alias
+ *   [offsets[n]] = one alias table per adjacency row over its weights, alias = index within the row.  Same
+ *   construction as gv_build_alias.  GV_EINVAL for a negative weight, a row with entries but no weight, or a
+ *   graph without weight.
+ * gv_augment_weighted: gv_augment with those tables: walk w departs at the node table's draw from Philox
+ *   block (w, 0) of stream 4 (bucket from words 0 and 1 over n, accepted when word 2 is below the threshold)
+ *   and step t is the row table's draw from block (w, t).  With all weights 1 every step equals gv_augment's.
+ * gv_set_weighted_graph: the graph of a context from its weighted adjacency (replaces gv_set_graph /
+ *   gv_set_degrees + gv_set_adjacency): keeps weighted degrees, which gv_build_alias then uses in place of
+ *   degrees, allocates the matrices, and uploads adjacency and walk tables, so that gv_augment_device walks the
+ *   weighted graph (bit-identical to gv_augment_weighted).  GV_EINVAL as above or for an entry >= n.        */
+int gv_build_walk_tables(uint32_t n, const uint64_t *host_offsets, const float *host_weights, double *host_wdeg,
+                         uint32_t *host_node_thresh, uint32_t *host_node_alias, uint32_t *host_nbr_thresh,
+                         uint32_t *host_nbr_alias);
+int gv_augment_weighted(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj,
+                        const uint32_t *host_node_thresh, const uint32_t *host_node_alias,
+                        const uint32_t *host_nbr_thresh, const uint32_t *host_nbr_alias, uint64_t seed,
+                        uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
+                        uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used);
+int gv_set_weighted_graph(gv_ctx *ctx, uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj,
+                          const float *host_weights);
+
 /* The K negatives of positive samples first_g .. first_g+count-1, exactly as
  * training draws them (Alg. 1, NegativeSampling; Sec. 4.3 alias table): host_out[count][K].
  * (Parity hook.)                                                                        */

@@ -30,6 +30,7 @@ EXPORTS = [
     "gv_sync", "gv_get_stats", "gv_set_position", "gv_augment", "gv_eval_loss", "gv_cosine",
     "gv_set_adjacency", "gv_augment_device", "gv_auc", "gv_link_prediction_auc", "gv_train_device_pool_static",
     "gv_get_partitions", "gv_redistribute_pool", "gv_train_device_blocks", "gv_draw_negatives_partitioned",
+    "gv_build_walk_tables", "gv_augment_weighted", "gv_set_weighted_graph",
 ]
 
 
@@ -100,6 +101,10 @@ def load():
     L.gv_redistribute_pool.argtypes = [C.c_uint32, u32p, C.c_uint32, vp, C.c_uint64, C.c_uint32, vp, u32p, u64p]
     L.gv_train_device_blocks.argtypes = [vp, vp, vp, u64p, C.c_uint64]
     L.gv_draw_negatives_partitioned.argtypes = [vp, C.c_uint64, C.c_uint64, u32p, u32p]
+    L.gv_build_walk_tables.argtypes = [C.c_uint32, u64p, f32p, C.POINTER(C.c_double), u32p, u32p, u32p, u32p]
+    L.gv_augment_weighted.argtypes = [C.c_uint32, u64p, u32p, u32p, u32p, u32p, u32p, C.c_uint64, C.c_uint32,
+                                      C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, vp, u64p]
+    L.gv_set_weighted_graph.argtypes = [vp, C.c_uint32, u64p, u32p, f32p]
     L.gv_draw_negatives.argtypes = [vp, C.c_uint64, C.c_uint64, u32p]
     L.gv_sync.argtypes = [vp]
     L.gv_get_stats.argtypes = [vp, C.POINTER(gv_stats)]
@@ -342,6 +347,57 @@ def gv_augment(offsets, adj, *, seed, walk_length=40, window=5, first_walk=0, co
         raise GvError(rc, "gv_augment: bad argument or ill-formed adjacency" if rc == GV_EINVAL
                       else "gv_augment: workers could not be set up")
     return out[:count], walks.value
+
+
+def gv_build_walk_tables(offsets, weights):
+    """(wdeg float64[n], node_thresh, node_alias uint32[n], nbr_thresh, nbr_alias uint32[len(weights)])."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    n = offsets.size - 1
+    wdeg = np.empty(n, dtype=np.float64)
+    node_thresh, node_alias = np.empty(n, dtype=np.uint32), np.empty(n, dtype=np.uint32)
+    nbr_thresh, nbr_alias = np.zeros(weights.size, dtype=np.uint32), np.zeros(weights.size, dtype=np.uint32)
+    u32 = C.POINTER(C.c_uint32)
+    rc = load().gv_build_walk_tables(n, offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                     weights.ctypes.data_as(C.POINTER(C.c_float)),
+                                     wdeg.ctypes.data_as(C.POINTER(C.c_double)), node_thresh.ctypes.data_as(u32),
+                                     node_alias.ctypes.data_as(u32), nbr_thresh.ctypes.data_as(u32),
+                                     nbr_alias.ctypes.data_as(u32))
+    if rc != GV_OK:
+        raise GvError(rc, "gv_build_walk_tables: bad argument or a row without weight")
+    return wdeg, node_thresh, node_alias, nbr_thresh, nbr_alias
+
+
+def gv_augment_weighted(offsets, adj, tables, *, seed, walk_length=40, window=5, first_walk=0, count,
+                        shuffle=GV_SHUFFLE_PSEUDO, threads=1, out=None):
+    """gv_augment on a weighted graph; ``tables`` = (node_thresh, node_alias, nbr_thresh, nbr_alias)."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    adj = np.ascontiguousarray(adj, dtype=np.uint32)
+    if out is None:
+        out = np.empty((count, 2), dtype=np.uint32)
+    if out.dtype != np.uint32 or not out.flags.c_contiguous or out.size < 2 * count:
+        raise ValueError("out must be a C-contiguous uint32 array with room for count pairs")
+    t = [np.ascontiguousarray(x, dtype=np.uint32) for x in tables]
+    u32 = C.POINTER(C.c_uint32)
+    walks = C.c_uint64()
+    rc = load().gv_augment_weighted(offsets.size - 1, offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                    adj.ctypes.data_as(u32), t[0].ctypes.data_as(u32), t[1].ctypes.data_as(u32),
+                                    t[2].ctypes.data_as(u32), t[3].ctypes.data_as(u32), seed, walk_length, window,
+                                    first_walk, count, shuffle, threads, C.c_void_p(out.ctypes.data), C.byref(walks))
+    if rc != GV_OK:
+        raise GvError(rc, "gv_augment_weighted: bad argument or ill-formed adjacency / tables")
+    return out[:count], walks.value
+
+
+def gv_set_weighted_graph(ctx, offsets, adj, weights):
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
+    adj = np.ascontiguousarray(adj, dtype=np.uint32)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    if adj.size != weights.size:
+        raise ValueError("adj and weights differ in length")
+    _check(ctx, load().gv_set_weighted_graph(ctx, offsets.size - 1, offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                             adj.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                             weights.ctypes.data_as(C.POINTER(C.c_float))))
 
 
 def gv_set_adjacency(ctx, offsets, adj):

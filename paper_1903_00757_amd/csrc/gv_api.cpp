@@ -17,6 +17,7 @@
 #include <utility>
 #include <vector>
 
+#include "gv_host.hpp"
 #include "gv_internal.hpp"
 
 namespace {
@@ -56,6 +57,9 @@ struct gv_ctx {
     gv_config cfg{};
     uint32_t n = 0;
     std::vector<uint32_t> degree;
+    std::vector<double> wdegree;          // weighted graph: sum of the edge weights of every node (else empty)
+    uint2 *dev_node_table = nullptr;      // weighted graph: alias table of the departure nodes {threshold, alias}
+    uint2 *dev_nbr_table = nullptr;       // weighted graph: one alias table per adjacency row {threshold, alias in row}
     float *vertex = nullptr;
     float *context = nullptr;
     uint4 *alias = nullptr;
@@ -191,6 +195,10 @@ void free_matrices(gv_ctx *ctx) {
     ctx->dev_ranked = nullptr;
     if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
     if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
+    if (ctx->dev_node_table) (void)hipFree(ctx->dev_node_table);
+    if (ctx->dev_nbr_table) (void)hipFree(ctx->dev_nbr_table);
+    ctx->dev_node_table = nullptr;
+    ctx->dev_nbr_table = nullptr;
     if (ctx->dev_part_tables) (void)hipFree(ctx->dev_part_tables);
     if (ctx->dev_part_offsets) (void)hipFree(ctx->dev_part_offsets);
     if (ctx->dev_part) (void)hipFree(ctx->dev_part);
@@ -222,6 +230,7 @@ int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, bytes, ctx->compute));
     GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
     ctx->degree = std::move(deg);
+    ctx->wdegree.clear();
     ctx->part.clear();
     ctx->n = n;
     ctx->stamp_vertex.clear();
@@ -478,43 +487,6 @@ int pick_free_slot(gv_ctx *ctx, int *index) {
     return fail(ctx, GV_ESTATE, "all %d pool slots are filling or queued: train a pool first", slots);
 }
 
-// Alias table over weights q (Vose's method, the construction both sides of the parity tests follow: sum left
-// to right in fp64, p_i = q_i * size / sum, two index-ordered stacks, leftovers keep themselves, thresholds
-// floor(p * 2^32) saturated).  alias[i] is an index into q.  False when the weights sum to zero.
-bool vose_table(const std::vector<double> &q, std::vector<uint32_t> &thresh, std::vector<uint32_t> &alias, double *sum_out) {
-    const uint32_t size = (uint32_t)q.size();
-    double sum = 0.0;
-    for (uint32_t i = 0; i < size; ++i) sum += q[i];
-    if (sum_out) *sum_out = sum;
-    if (!(sum > 0.0)) return false;
-    std::vector<double> p(size), keep(size, 1.0);
-    std::vector<uint32_t> below, above;  // stacks of entries under / at-or-over the mean
-    below.reserve(size);
-    above.reserve(size);
-    thresh.assign(size, 0u);
-    alias.resize(size);
-    for (uint32_t i = 0; i < size; ++i) {
-        p[i] = q[i] * (double)size / sum;
-        (p[i] < 1.0 ? below : above).push_back(i);
-        alias[i] = i;
-    }
-    while (!below.empty() && !above.empty()) {
-        const uint32_t poor = below.back();
-        below.pop_back();
-        const uint32_t rich = above.back();
-        above.pop_back();
-        keep[poor] = p[poor];
-        alias[poor] = rich;
-        p[rich] = (p[rich] + p[poor]) - 1.0;
-        (p[rich] < 1.0 ? below : above).push_back(rich);
-    }
-    for (uint32_t i = 0; i < size; ++i) {
-        const double scaled = floor(keep[i] * 4294967296.0);
-        thresh[i] = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
-    }
-    return true;
-}
-
 // Device scratch shared by the evaluation calls: grown when a call needs more, kept otherwise.
 int ensure_eval_scratch(gv_ctx *ctx, uint64_t bytes) {
     if (bytes <= ctx->eval_capacity) return GV_OK;
@@ -694,6 +666,52 @@ int gv_set_degrees(gv_ctx *ctx, uint32_t n, const uint32_t *host_deg) {
     });
 }
 
+int gv_set_weighted_graph(gv_ctx *ctx, uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj,
+                          const float *host_weights) {
+    if (!ctx) return GV_EINVAL;
+    return guarded(ctx, [&]() -> int {
+        if (n == 0 || !host_offsets || !host_adj || !host_weights) return fail(ctx, GV_EINVAL, "empty graph or null arrays");
+        int rc = bind_device(ctx);
+        if (rc) return rc;
+        if (host_offsets[0] != 0) return fail(ctx, GV_EINVAL, "offsets[0] must be 0");
+        std::vector<uint32_t> counts(n);
+        for (uint32_t i = 0; i < n; ++i) {
+            if (host_offsets[i + 1] < host_offsets[i] || host_offsets[i + 1] - host_offsets[i] > 0xFFFFFFFFull)
+                return fail(ctx, GV_EINVAL, "offsets must ascend (row %u)", i);
+            counts[i] = (uint32_t)(host_offsets[i + 1] - host_offsets[i]);
+        }
+        const uint64_t half_edges = host_offsets[n];
+        if (half_edges == 0) return fail(ctx, GV_EINVAL, "graph without edges");
+        for (uint64_t e = 0; e < half_edges; ++e) {
+            if (host_adj[e] >= n) return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
+            if (!(host_weights[e] >= 0.0f) || !isfinite(host_weights[e]))
+                return fail(ctx, GV_EINVAL, "weight %llu is negative or not finite", (unsigned long long)e);
+        }
+        std::vector<double> wdeg(n);
+        std::vector<uint32_t> node_thresh(n), node_alias(n), nbr_thresh(half_edges), nbr_alias(half_edges);
+        rc = gv_build_walk_tables(n, host_offsets, host_weights, wdeg.data(), node_thresh.data(), node_alias.data(),
+                                  nbr_thresh.data(), nbr_alias.data());
+        if (rc == GV_ENOMEM) return fail(ctx, GV_ENOMEM, "out of host memory");
+        if (rc) return fail(ctx, GV_EINVAL, "a node has edges but no weight, or the graph has no weight at all");
+        rc = adopt_degrees(ctx, n, std::move(counts));
+        if (rc) return rc;
+        std::vector<uint2> node_table(n), nbr_table(half_edges);
+        for (uint32_t i = 0; i < n; ++i) node_table[i] = make_uint2(node_thresh[i], node_alias[i]);
+        for (uint64_t e = 0; e < half_edges; ++e) nbr_table[e] = make_uint2(nbr_thresh[e], nbr_alias[e]);
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_offsets, ((size_t)n + 1) * sizeof(uint64_t)));
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_adj, (size_t)half_edges * sizeof(uint32_t)));
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_node_table, (size_t)n * sizeof(uint2)));
+        GV_HIP(ctx, hipMalloc((void **)&ctx->dev_nbr_table, (size_t)half_edges * sizeof(uint2)));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_offsets, host_offsets, ((size_t)n + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_adj, host_adj, (size_t)half_edges * sizeof(uint32_t), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_node_table, node_table.data(), (size_t)n * sizeof(uint2), hipMemcpyHostToDevice));
+        GV_HIP(ctx, hipMemcpy(ctx->dev_nbr_table, nbr_table.data(), (size_t)half_edges * sizeof(uint2), hipMemcpyHostToDevice));
+        ctx->half_edges = half_edges;
+        ctx->wdegree = std::move(wdeg);
+        return GV_OK;
+    });
+}
+
 int gv_build_alias(gv_ctx *ctx, double power) {
     return guarded(ctx, [&]() -> int {
         int rc = need_graph(ctx);
@@ -701,8 +719,11 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         if (power != 0.75 && power != 1.0 && power != 0.0)
             return fail(ctx, GV_EINVAL, "power must be 0.75, 1.0 or 0.0");
         const uint32_t n = ctx->n;
+        // the degree of a node, or on a weighted graph the sum of the weights of its edges
+        const bool weighted = ctx->wdegree.size() == n;
+        auto degree_of = [&](uint32_t node) { return weighted ? ctx->wdegree[node] : (double)ctx->degree[node]; };
         auto weight = [&](uint32_t node) {
-            const double d = (double)ctx->degree[node];
+            const double d = degree_of(node);
             if (power == 0.75) {
                 const double root = sqrt(d);
                 return root * sqrt(root);
@@ -712,12 +733,13 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         std::vector<double> q(n);
         double degree_sum = 0.0;
         for (uint32_t i = 0; i < n; ++i) {
-            degree_sum += (double)ctx->degree[i];
+            degree_sum += degree_of(i);
             q[i] = weight(i);
         }
-        std::vector<uint32_t> thresh, alias;
+        std::vector<uint32_t> thresh(n), alias(n);
         double sum = 0.0;
-        if (!vose_table(q, thresh, alias, &sum)) return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
+        if (!gv::vose_table(q.data(), n, thresh.data(), alias.data(), &sum))
+            return fail(ctx, GV_EINVAL, "all weights are zero (graph without edges)");
         // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
         // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
         // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
@@ -739,7 +761,8 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         const double kInFlight = 8192.0 * (B > 0 && GV_TUNE_WARM_BLOCKS ? (double)B : 1.0), kWarmThreshold = GV_TUNE_WARM;
         const uint32_t kRanked = 0xFFFFu;
         auto hotter = [&](uint32_t x, uint32_t y) {
-            return ctx->degree[x] != ctx->degree[y] ? ctx->degree[x] > ctx->degree[y] : x < y;
+            const double dx = degree_of(x), dy = degree_of(y);
+            return dx != dy ? dx > dy : x < y;
         };
         std::vector<uint32_t> order(n);
         for (uint32_t i = 0; i < n; ++i) order[i] = i;
@@ -755,7 +778,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
             const uint32_t i = order[r];
             rank[i] = (uint16_t)r;
             ranked_bits[i >> 5] |= 1u << (i & 31u);
-            const double share = (degree_sum > 0.0 ? (double)ctx->degree[i] / degree_sum : 0.0) + q[i] / sum;
+            const double share = (degree_sum > 0.0 ? degree_of(i) / degree_sum : 0.0) + q[i] / sum;
             if (share * kInFlight > kWarmThreshold) warm_ranks = r + 1;
         }
         std::vector<uint4> table(n);
@@ -787,8 +810,8 @@ int gv_build_alias(gv_ctx *ctx, double power) {
                 const uint64_t lo = part_offsets[j], size = part_offsets[j + 1] - lo;
                 std::vector<double> qj(size);
                 for (uint64_t l = 0; l < size; ++l) qj[l] = weight(members[lo + l]);
-                std::vector<uint32_t> tj, aj;
-                if (size == 0 || !vose_table(qj, tj, aj, nullptr))
+                std::vector<uint32_t> tj(size), aj(size);
+                if (size == 0 || !gv::vose_table(qj.data(), size, tj.data(), aj.data(), nullptr))
                     return fail(ctx, GV_EINVAL, "partition %u of %u has no node with a positive weight", j, B);
                 for (uint64_t l = 0; l < size; ++l) {
                     const uint32_t self = members[lo + l], other = members[lo + aj[l]];
@@ -1135,6 +1158,8 @@ int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *
                 return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
         rc = sync_all(ctx);
         if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (ctx->wdegree.size() == n)
+            return fail(ctx, GV_ESTATE, "the graph is weighted: gv_set_weighted_graph has uploaded its adjacency already");
         if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);
         if (ctx->dev_adj) (void)hipFree(ctx->dev_adj);
         ctx->dev_offsets = nullptr;
@@ -1175,6 +1200,8 @@ int gv_augment_device(gv_ctx *ctx, uint64_t seed, uint32_t walk_length, uint32_t
         a.length = walk_length;
         a.window = window;
         a.pseudo_shuffle = shuffle == GV_SHUFFLE_PSEUDO ? 1u : 0u;
+        a.node_table = ctx->dev_node_table;
+        a.nbr_table = ctx->dev_nbr_table;
         if (walks_used) *walks_used = a.walks;
         GV_HIP(ctx, gv::launch_augment(a, ctx->compute));
         return GV_OK;

@@ -3,6 +3,8 @@
 // caller buffer, in particular into the pinned pool slots of a context.
 #include <stdint.h>
 
+#include <math.h>
+
 #include <algorithm>
 #include <atomic>
 #include <exception>
@@ -10,6 +12,7 @@
 #include <thread>
 #include <vector>
 
+#include "gv_host.hpp"
 #include "gvhot.h"
 
 namespace {
@@ -45,9 +48,15 @@ constexpr uint32_t kWalkStream = 4;
 
 }  // namespace
 
-static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,
-                   uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count, uint32_t shuffle,
-                   uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
+// Tables of a weighted graph's walk (null for an unweighted graph): alias table over the nodes for the
+// departure, one alias table per adjacency row for the steps (Sec. 4.3).
+struct WalkTables {
+    const uint32_t *node_thresh, *node_alias, *nbr_thresh, *nbr_alias;
+};
+
+static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, const WalkTables *tables,
+                   uint64_t seed, uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
+                   uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
     if (walks_used) *walks_used = 0;
     if (count == 0) return GV_OK;
     if (!host_offsets || !host_adj || !host_pairs || n == 0 || walk_length == 0 || window == 0 ||
@@ -79,14 +88,25 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
         std::vector<uint32_t> &path = paths[worker];
         const uint64_t lo = walks * worker / workers, hi = walks * (worker + 1) / workers;
         for (uint64_t w = lo; w < hi; ++w) {
-            // departure: owner of a uniformly chosen half-edge = probability proportional to degree
-            const uint64_t e = pick(philox(seed, first_walk + w, 0, kWalkStream), half_edges);
-            const uint64_t *owner = std::upper_bound(host_offsets, host_offsets + n + 1, e) - 1;
-            if (owner < host_offsets || owner >= host_offsets + n) {  // offsets not ascending from 0
-                broken.store(true, std::memory_order_relaxed);
-                return;
+            const Words r0 = philox(seed, first_walk + w, 0, kWalkStream);
+            if (tables) {
+                // weighted graph: alias draw over the nodes, weights = weighted degrees
+                const uint64_t j = pick(r0, n);
+                path[0] = r0.w[2] < tables->node_thresh[j] ? (uint32_t)j : tables->node_alias[j];
+                if (path[0] >= n) {
+                    broken.store(true, std::memory_order_relaxed);
+                    return;
+                }
+            } else {
+                // departure: owner of a uniformly chosen half-edge = probability proportional to degree
+                const uint64_t e = pick(r0, half_edges);
+                const uint64_t *owner = std::upper_bound(host_offsets, host_offsets + n + 1, e) - 1;
+                if (owner < host_offsets || owner >= host_offsets + n) {  // offsets not ascending from 0
+                    broken.store(true, std::memory_order_relaxed);
+                    return;
+                }
+                path[0] = (uint32_t)(owner - host_offsets);
             }
-            path[0] = (uint32_t)(owner - host_offsets);
             for (uint32_t t = 1; t <= L; ++t) {
                 const uint32_t x = path[t - 1];
                 const uint64_t begin = host_offsets[x], end = host_offsets[x + 1];
@@ -94,7 +114,16 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
                     broken.store(true, std::memory_order_relaxed);
                     return;
                 }
-                const uint32_t next = host_adj[begin + pick(philox(seed, first_walk + w, t, kWalkStream), end - begin)];
+                const Words r = philox(seed, first_walk + w, t, kWalkStream);
+                uint64_t at = pick(r, end - begin);
+                if (tables && !(r.w[2] < tables->nbr_thresh[begin + at])) {  // weighted step: the entry or its alias
+                    at = tables->nbr_alias[begin + at];
+                    if (at >= end - begin) {
+                        broken.store(true, std::memory_order_relaxed);
+                        return;
+                    }
+                }
+                const uint32_t next = host_adj[begin + at];
                 if (next >= n) {
                     broken.store(true, std::memory_order_relaxed);
                     return;
@@ -131,11 +160,100 @@ extern "C" int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32
                           uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
                           uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
     try {
-        return augment(n, host_offsets, host_adj, seed, walk_length, window, first_walk, count, shuffle, threads,
+        return augment(n, host_offsets, host_adj, nullptr, seed, walk_length, window, first_walk, count, shuffle, threads,
                        host_pairs, walks_used);
     } catch (const std::bad_alloc &) {
         return GV_ENOMEM;
     } catch (...) {  // std::system_error of a thread that could not start, and anything else
+        return GV_EHIP;
+    }
+}
+
+extern "C" int gv_augment_weighted(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj,
+                                   const uint32_t *host_node_thresh, const uint32_t *host_node_alias,
+                                   const uint32_t *host_nbr_thresh, const uint32_t *host_nbr_alias, uint64_t seed,
+                                   uint32_t walk_length, uint32_t window, uint64_t first_walk, uint64_t count,
+                                   uint32_t shuffle, uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used) {
+    if (walks_used) *walks_used = 0;
+    if (!host_node_thresh || !host_node_alias || !host_nbr_thresh || !host_nbr_alias) return GV_EINVAL;
+    const WalkTables tables{host_node_thresh, host_node_alias, host_nbr_thresh, host_nbr_alias};
+    try {
+        return augment(n, host_offsets, host_adj, &tables, seed, walk_length, window, first_walk, count, shuffle, threads,
+                       host_pairs, walks_used);
+    } catch (const std::bad_alloc &) {
+        return GV_ENOMEM;
+    } catch (...) {
+        return GV_EHIP;
+    }
+}
+
+bool gv::vose_table(const double *q, uint64_t size, uint32_t *thresh, uint32_t *alias, double *sum_out) {
+    double sum = 0.0;
+    for (uint64_t i = 0; i < size; ++i) sum += q[i];
+    if (sum_out) *sum_out = sum;
+    if (size == 0 || size > 0xFFFFFFFFull || !(sum > 0.0)) return false;
+    std::vector<double> p(size), keep(size, 1.0);
+    std::vector<uint32_t> below, above;  // stacks of entries under / at-or-over the mean
+    below.reserve(size);
+    above.reserve(size);
+    for (uint64_t i = 0; i < size; ++i) {
+        p[i] = q[i] * (double)size / sum;
+        (p[i] < 1.0 ? below : above).push_back((uint32_t)i);
+        alias[i] = (uint32_t)i;
+    }
+    while (!below.empty() && !above.empty()) {
+        const uint32_t poor = below.back();
+        below.pop_back();
+        const uint32_t rich = above.back();
+        above.pop_back();
+        keep[poor] = p[poor];
+        alias[poor] = rich;
+        p[rich] = (p[rich] + p[poor]) - 1.0;
+        (p[rich] < 1.0 ? below : above).push_back(rich);
+    }
+    for (uint64_t i = 0; i < size; ++i) {
+        const double scaled = floor(keep[i] * 4294967296.0);
+        thresh[i] = scaled >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scaled;
+    }
+    return true;
+}
+
+// Everything a walk on a weighted graph draws from (Sec. 4.3): weighted degrees (edge weights of a row summed
+// left to right in fp64), the alias table over the nodes with those weights, and one alias table per adjacency
+// row over its edge weights.
+static int build_walk_tables(uint32_t n, const uint64_t *host_offsets, const float *host_weights, double *host_wdeg,
+                             uint32_t *node_thresh, uint32_t *node_alias, uint32_t *nbr_thresh, uint32_t *nbr_alias) {
+    if (n == 0 || !host_offsets || !host_weights || !node_thresh || !node_alias || !nbr_thresh || !nbr_alias)
+        return GV_EINVAL;
+    std::vector<double> wdeg(n), row;
+    for (uint32_t x = 0; x < n; ++x) {
+        const uint64_t begin = host_offsets[x], end = host_offsets[x + 1];
+        if (end < begin) return GV_EINVAL;
+        double total = 0.0;
+        row.resize(end - begin);
+        for (uint64_t e = begin; e < end; ++e) {
+            if (!(host_weights[e] >= 0.0f)) return GV_EINVAL;
+            row[e - begin] = (double)host_weights[e];
+            total += (double)host_weights[e];
+        }
+        wdeg[x] = total;
+        if (end > begin && !gv::vose_table(row.data(), end - begin, nbr_thresh + begin, nbr_alias + begin, nullptr))
+            return GV_EINVAL;  // a row with entries but no weight
+    }
+    if (!gv::vose_table(wdeg.data(), n, node_thresh, node_alias, nullptr)) return GV_EINVAL;
+    if (host_wdeg) std::copy(wdeg.begin(), wdeg.end(), host_wdeg);
+    return GV_OK;
+}
+
+extern "C" int gv_build_walk_tables(uint32_t n, const uint64_t *host_offsets, const float *host_weights,
+                                    double *host_wdeg, uint32_t *host_node_thresh, uint32_t *host_node_alias,
+                                    uint32_t *host_nbr_thresh, uint32_t *host_nbr_alias) {
+    try {
+        return build_walk_tables(n, host_offsets, host_weights, host_wdeg, host_node_thresh, host_node_alias,
+                                 host_nbr_thresh, host_nbr_alias);
+    } catch (const std::bad_alloc &) {
+        return GV_ENOMEM;
+    } catch (...) {
         return GV_EHIP;
     }
 }

@@ -69,6 +69,8 @@ hipError_t launch_cosine(const float *vertex, uint32_t n, uint32_t dim, const ui
 struct AugmentArgs {
     const uint64_t *offsets;  // CSR row starts, n + 1 entries
     const uint32_t *adj;      // neighbours, both directions of every edge
+    const uint2 *node_table;  // weighted graph: alias table of the departure nodes {threshold, alias node}; else null
+    const uint2 *nbr_table;   // weighted graph: per adjacency entry {threshold, alias entry of the same row}; else null
     uint2 *pairs;             // output, count x (u, v)
     uint64_t half_edges;      // offsets[n]
     uint64_t seed, first_walk, walks, count, per_walk;

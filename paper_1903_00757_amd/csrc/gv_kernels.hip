@@ -952,7 +952,7 @@ __global__ __launch_bounds__(kBlock) void k_init_vertex(float *__restrict__ vert
 // Producer on the device: online augmentation (Sec. 3.1, Alg. 2) with the pseudo shuffle of
 // the same section, one thread per random walk.  Walk w departs at the owner of a uniformly
 // chosen half-edge (probability proportional to degree), takes `length` uniform steps over the
-// CSR adjacency and emits every ordered pair (w_i, w_j), i < j <= i + window, in order of i then
+// CSR adjacency (on a weighted graph both are alias draws, see below) and emits every ordered pair (w_i, w_j), i < j <= i + window, in order of i then
 // j; sample number t of the pool (walks concatenated) goes to position t, or, pseudo-shuffled,
 // to block t mod window at offset t / window.  Random numbers: Philox stream 4, counter
 // (walk number, step): the pool depends on nothing but the seed and the walk numbers.
@@ -970,18 +970,33 @@ __global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
     const uint32_t L = a.length, s = a.window;
     const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
     const uint64_t walk = a.first_walk + w;
-    // departure: last node whose first half-edge is at or before the chosen one
-    const uint64_t e = pick_below(philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), 0u, 4u, k0, k1), a.half_edges);
-    uint32_t lo = 0, hi = a.n;  // offsets[lo] <= e < offsets[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = lo + (hi - lo) / 2;
-        if (a.offsets[mid] <= e) lo = mid; else hi = mid;
+    uint32_t x;
+    const uint4 r0 = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), 0u, 4u, k0, k1);
+    if (a.node_table) {
+        // weighted graph (Sec. 4.3): departure by an alias draw over the nodes, weights = weighted degrees
+        const uint32_t j = (uint32_t)pick_below(r0, a.n);
+        const uint2 entry = a.node_table[j];
+        x = r0.z < entry.x ? j : entry.y;
+    } else {
+        // departure: last node whose first half-edge is at or before the chosen one
+        const uint64_t e = pick_below(r0, a.half_edges);
+        uint32_t lo = 0, hi = a.n;  // offsets[lo] <= e < offsets[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = lo + (hi - lo) / 2;
+            if (a.offsets[mid] <= e) lo = mid; else hi = mid;
+        }
+        x = lo;
     }
-    uint32_t x = lo;
     s_path[0][threadIdx.x] = x;
     for (uint32_t t = 1; t <= L; ++t) {
         const uint64_t begin = a.offsets[x], degree = a.offsets[x + 1] - begin;
-        x = a.adj[begin + pick_below(philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), t, 4u, k0, k1), degree)];
+        const uint4 r = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), t, 4u, k0, k1);
+        uint64_t at = pick_below(r, degree);
+        if (a.nbr_table) {  // weighted step: alias draw over the row's edge weights
+            const uint2 entry = a.nbr_table[begin + at];
+            at = r.z < entry.x ? at : entry.y;
+        }
+        x = a.adj[begin + at];
         s_path[t][threadIdx.x] = x;
     }
     uint64_t t_global = w * a.per_walk;

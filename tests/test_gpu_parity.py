@@ -1155,6 +1155,64 @@ def test_device_producer_argument_errors(gv, tiny_graph):
         assert gv.gv_augment_device(ctx, 0, seed=1, count=0) == 0  # nothing to do
 
 
+# --------------------------------------------------------------------------- weighted graphs
+def test_weighted_graph_end_to_end(gv, tiny_graph):
+    """A weighted graph through the library (Sec. 4.3): the negative-sampling table follows the 3/4 power of the
+    weighted degree, the device producer walks by edge weight, bit-identical to the oracle and to the host
+    producer; pools produced that way train to the oracle's embeddings (deterministic mode, 1e-5)."""
+    import torch
+
+    g = tiny_graph
+    n, d, K, w, seed, count = g["n"], 64, 2, 2.5, 19, 60_007
+    rng = np.random.default_rng(4)
+    ew = rng.choice([0.25, 1.0, 4.0, 9.0], size=g["src"].size).astype(np.float32)
+    order = np.argsort(np.concatenate([g["src"], g["dst"]]), kind="stable")
+    offsets, adj, weights = g["offsets"], g["adj"], np.ascontiguousarray(np.concatenate([ew, ew])[order])
+    wdeg = oracle.weighted_degrees(offsets, weights)
+    thresh, alias = oracle.alias_build(oracle.weights_pow34(wdeg))
+    tables = oracle.walk_tables(offsets, weights)
+    vertex, context = random_embeddings(n, d, seed=6)
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_DETERMINISTIC, total_samples=2 * count,
+                     seed=seed, pool_capacity=count, lr0=LR0) as ctx:
+        gv.gv_set_weighted_graph(ctx, offsets, adj, weights)
+        gv.gv_build_alias(ctx, 0.75)
+        got_t, got_a = gv.gv_get_alias(ctx, n)
+        assert np.array_equal(got_t, thresh) and np.array_equal(got_a, alias)
+        assert not np.array_equal(got_t, oracle.alias_build(oracle.degree_weights(g["deg"]))[0])  # weights matter
+        assert np.array_equal(gv.gv_draw_negatives(ctx, 2**34, 50_000, K), oracle.draw_negatives(seed, 2**34, 50_000, K, thresh, alias))
+        gv.gv_set_embeddings(ctx, gv.GV_VERTEX, vertex)
+        gv.gv_set_embeddings(ctx, gv.GV_CONTEXT, context)
+        buf = torch.full((count + 2, 2), -1, dtype=torch.int32, device="cuda")
+        ref_v, ref_c = vertex.copy(), context.copy()
+        for k, (first_walk, shuffle) in enumerate([(0, 1), (2**33, 0)]):
+            walks = gv.gv_augment_device(ctx, buf.data_ptr(), seed=77, first_walk=first_walk, count=count, shuffle=shuffle)
+            gv.gv_sync(ctx)
+            got = buf.cpu().numpy().view(np.uint32)
+            ref, ref_walks = oracle.augment_weighted(77, offsets, adj, tables, 40, 5, count, first_walk=first_walk)
+            if shuffle:
+                ref = oracle.pseudo_shuffle(ref, 5)
+            assert walks == ref_walks and np.array_equal(got[:count], ref) and (got[count:] == 0xFFFFFFFF).all()
+            host, _ = gv.gv_augment_weighted(offsets, adj, tables, seed=77, first_walk=first_walk, count=count,
+                                             shuffle=shuffle, threads=3)
+            assert np.array_equal(host, ref)
+            gv.gv_train_device_pool(ctx, buf.data_ptr(), count)
+            oracle.train(ref_v, ref_c, ref, K=K, first_g=k * count, T=2 * count, lr0=LR0, lr_min_ratio=0.0, w=w,
+                         seed=seed, thresh=thresh, alias=alias)
+        got_v = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, n, d)
+        got_c = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, n, d)
+        for got, ref in ((got_v, ref_v), (got_c, ref_c)):
+            fro, mx = rel_errors(got, ref)
+            assert fro <= 1e-5 and mx <= 1e-4, (fro, mx)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_set_adjacency(ctx, offsets, adj)
+        assert e.value.code == gv.GV_ESTATE  # the weighted adjacency is in place
+        bad = weights.copy()
+        bad[10] = -1.0
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_set_weighted_graph(ctx, offsets, adj, bad)
+        assert e.value.code == gv.GV_EINVAL
+
+
 # --------------------------------------------------------------------------- orthogonal blocks
 @pytest.mark.parametrize("B", [2, 8])
 def test_partitions_and_their_alias_tables_are_bit_identical(gv, tiny_graph, B):

@@ -112,3 +112,38 @@ def test_library_redistribution_equals_oracle_block_order(gv, tiny_graph, thread
     with pytest.raises(gv.GvError) as e:
         gv.gv_redistribute_pool(part, 3, bad, threads=threads)
     assert e.value.code == gv.GV_EINVAL
+
+
+def weighted_tiny(g, seed=4):
+    """The small graph with edge weights from {1/4, 1, 4, 9}: (offsets, adj, weights per adjacency entry)."""
+    rng = np.random.default_rng(seed)
+    w = rng.choice([0.25, 1.0, 4.0, 9.0], size=g["src"].size).astype(np.float32)
+    order = np.argsort(np.concatenate([g["src"], g["dst"]]), kind="stable")
+    return g["offsets"], g["adj"], np.ascontiguousarray(np.concatenate([w, w])[order])
+
+
+@pytest.mark.parametrize("threads", [1, 5])
+def test_library_weighted_producer_equals_oracle(gv, tiny_graph, threads):
+    """Walk tables of a weighted graph (weighted degrees, node table, one table per adjacency row) and the pools
+    walked with them (Sec. 4.3) are bit-identical to the oracle's, pseudo-shuffled or not, for any worker count."""
+    offsets, adj, weights = weighted_tiny(tiny_graph)
+    wdeg, *tables = gv.gv_build_walk_tables(offsets, weights)
+    ref_tables = oracle.walk_tables(offsets, weights)
+    assert np.array_equal(wdeg, oracle.weighted_degrees(offsets, weights))
+    for got, ref in zip(tables, ref_tables):
+        assert np.array_equal(got, ref)
+    for count, first_walk, L, s, seed in [(190 * 41 + 3, 0, 40, 5, 13), (7000, 2**36 + 5, 40, 5, 2**41 + 1), (999, 7, 6, 3, 2)]:
+        ref, ref_walks = oracle.augment_weighted(seed, offsets, adj, ref_tables, L, s, count, first_walk=first_walk)
+        for shuffle in (0, 1):
+            got, walks = gv.gv_augment_weighted(offsets, adj, tables, seed=seed, walk_length=L, window=s,
+                                                first_walk=first_walk, count=count, shuffle=shuffle, threads=threads)
+            assert walks == ref_walks
+            assert np.array_equal(got, oracle.pseudo_shuffle(ref, s) if shuffle else ref)
+    # unit weights: the steps are the unweighted producer's
+    ones = np.ones(adj.size, dtype=np.float32)
+    _, *unit = gv.gv_build_walk_tables(offsets, ones)
+    assert np.all(unit[2] == 0xFFFFFFFF)
+    for bad in (np.where(np.arange(adj.size) == 3, -1.0, 1.0), np.zeros(adj.size)):
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_build_walk_tables(offsets, bad.astype(np.float32))
+        assert e.value.code == gv.GV_EINVAL
