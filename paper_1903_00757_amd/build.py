@@ -52,5 +52,21 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, out_dir: str = 
     return lib
 
 
+MICROBENCH = os.path.join(HERE, "microbench_rows")
+
+
+def build_microbench() -> str:
+    """The stand-alone microbenchmark of row operations (csrc/microbench_rows.hip): an executable beside the library."""
+    tmp = MICROBENCH + f".{os.getpid()}.tmp"
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", os.path.join(CSRC, "microbench_rows.hip"), "-o", tmp]
+    done = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if done.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + done.stdout)
+    os.replace(tmp, MICROBENCH)
+    return MICROBENCH
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build_microbench())

@@ -751,14 +751,8 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
         // Under the orthogonal-block schedule the samples in flight all come from one block, where a
         // row's share is `partitions` times its share of the pool.
-#ifndef GV_TUNE_WARM
-#define GV_TUNE_WARM 0.1
-#endif
         const uint32_t B = ctx->cfg.partitions;
-#ifndef GV_TUNE_WARM_BLOCKS
-#define GV_TUNE_WARM_BLOCKS 1
-#endif
-        const double kInFlight = 8192.0 * (B > 0 && GV_TUNE_WARM_BLOCKS ? (double)B : 1.0), kWarmThreshold = GV_TUNE_WARM;
+        const double kInFlight = 8192.0 * (B > 0 ? (double)B : 1.0), kWarmThreshold = 0.1;
         const uint32_t kRanked = 0xFFFFu;
         auto hotter = [&](uint32_t x, uint32_t y) {
             const double dx = degree_of(x), dy = degree_of(y);

@@ -15,12 +15,6 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 constexpr int kBlock = 256;  // 4 waves per workgroup
-#ifndef GV_TUNE_BATCH
-#define GV_TUNE_BATCH 4
-#endif
-#ifndef GV_TUNE_GRID
-#define GV_TUNE_GRID 0
-#endif
 // Row traffic policies (gv_config.coherence).
 constexpr int kPlain = 0;        // cached loads and stores
 constexpr int kAgent = 1;        // device-scope loads and stores
@@ -425,7 +419,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
     // samples whose gathers are in flight together: bounded by the registers their rows take
-    constexpr int kBatch = kV * (kK + 1) <= 4 ? GV_TUNE_BATCH : (kV * (kK + 1) <= 12 ? 2 : 1);
+    constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
     // A held row trades with memory every four samples where four samples are gathered at once, every two
     // where rows are so long that one or two samples fill the registers: there an exchange is a small part of
     // a sample's traffic, and the shorter interval halves how far the run's scores lag behind the other
@@ -441,10 +435,6 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     static_assert(kSameShift < 32, "flag word");
     using Io = RowIo<kV, kCoherence, kFull>;
     __shared__ uint32_t s_word[kTile];
-#ifdef GV_TUNE_LDS_PAD
-    __shared__ uint32_t s_pad[GV_TUNE_LDS_PAD / 4];
-    if (a.count == 0xFFFFFFFFu) s_pad[threadIdx.x] = 1u;  // keeps the padding allocated
-#endif
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
@@ -571,10 +561,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             //   bit kBatch - 1 + d - 1 (d <= kBatch): a row of this sample is the stationary row of that sample
             // The row held when the chunk starts stands in for "the sample before sample 0".
             uint32_t clash = 0u;
-#ifndef GV_TUNE_NOCLASH
-#define GV_TUNE_NOCLASH 0
-#endif
-            if constexpr (kCoherence != kAtomicAgent && GV_TUNE_NOCLASH != 1) {
+            if constexpr (kCoherence != kAtomicAgent) {
                 auto from_before = [&](uint32_t x, int d) {  // x of the lane d places down
                     return (uint32_t)__builtin_amdgcn_ds_bpermute((lane - d) * 4, (int)x);
                 };
@@ -747,7 +734,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                     since_exchange = 0;
                 }
                 if constexpr (kCoherence != kAtomicAgent) {
-                    if (GV_TUNE_NOCLASH != 2 && held && ((batch[0].flags >> (kClashShift + kBatch - 1)) & 1u)) {
+                    if (held && ((batch[0].flags >> (kClashShift + kBatch - 1)) & 1u)) {
                         flush();
                         held = nullptr;
                     }
@@ -763,7 +750,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                             batch[b] = decode(i0 + b);
                             // earlier samples of the batch (b places at most), and the row held at its start
                             const uint32_t kEarlier = ((1u << b) - 1u) | 1u << (kBatch - 1 + b);
-                            if (GV_TUNE_NOCLASH != 2 && kCoherence != kAtomicAgent && ((batch[b].flags >> kClashShift) & kEarlier)) continue;
+                            if (kCoherence != kAtomicAgent && ((batch[b].flags >> kClashShift) & kEarlier)) continue;
                         }
                         fetch(batch[b], then, loaded[b], fresh[b]);
                         then = batch[b].stationary;
@@ -1078,8 +1065,7 @@ hipError_t launch_tiled_vk(const TrainArgs &a, uint32_t coherence, hipStream_t s
     // strides over the tiles.
     const uint32_t limit = hogwild_blocks(a.count, a.n);
     const uint32_t tiles = (a.count + tile - 1) / tile;
-    uint32_t blocks = limit >= 2048u || limit > tiles ? tiles : limit;
-    if (GV_TUNE_GRID > 0 && blocks > (uint32_t)GV_TUNE_GRID) blocks = GV_TUNE_GRID;
+    const uint32_t blocks = limit >= 2048u || limit > tiles ? tiles : limit;
     return a.dim == (uint32_t)(kWave * kV) ? launch_tiled_vkt<kV, kK, (int)tile, true>(a, coherence, blocks, stream)
                                            : launch_tiled_vkt<kV, kK, (int)tile, false>(a, coherence, blocks, stream);
 }

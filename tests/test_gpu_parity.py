@@ -1334,6 +1334,49 @@ def test_block_training_quality_matches_blocked_oracle(gv, policy):
     assert abs(auc["gpu"] - auc["blocked"]) <= 0.005
 
 
+def test_block_training_long_run_tracks_the_blocked_oracle(gv):
+    """Configuration 2 under the orthogonal-block schedule as the stored oracle run has it: 8 partitions, 4
+    episodes of 8 pools (2^27 samples each) redistributed into the 8 x 8 grid and trained block after block with
+    restricted negatives, learning rate decaying to zero over the 32 pools.  After every episode the evaluation
+    loss must be within 2 % of the oracle's, at the end the link-prediction AUC within 0.005.  (The plain
+    schedule's trajectory on the same pools is in long_run_c2.txt: the block schedule itself costs convergence,
+    2.803 against 2.613 after the first 8 pools, for the oracle and the library alike.)"""
+    import torch
+
+    s, reference = read_long_run_reference("c2-blocks")
+    n, src, dst = W.make_graph(s["graph"])
+    tr_s, tr_d, te_s, te_d = W.split_holdout(src, dst, s["holdout"], seed=s["holdout_seed"])
+    deg = W.degrees(n, tr_s, tr_d)
+    offsets, adj = W.csr_from_edges(n, tr_s, tr_d)
+    P, pools, d, B, E = s["pool"], s["pools"], s["dim"], s["partitions"], s["episode_pools"]
+    walks_per_pool = -(-P // 190)
+    eval_pool, _ = gv.gv_augment(offsets, adj, seed=s["eval_walk_seed"], count=s["eval_count"], threads=16)
+    eval_pool = eval_pool.copy()
+    na, nb = W.uniform_negative_pairs(n, te_s.size, seed=s["negative_pair_seed"])
+    checkpoints = {k: rest for k, *rest in reference}
+    assert pools in checkpoints and all(k % E == 0 for k in checkpoints)
+    with context_for(gv, dim=d, num_neg=s["num_neg"], neg_weight=s["neg_weight"], mode=gv.GV_MODE_HOGWILD,
+                     total_samples=P * pools, seed=s["train_seed"], pool_capacity=8, lr0=s["lr0"], partitions=B) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, s["init_seed"])
+        part = gv.gv_get_partitions(ctx, n, B)[0]
+        episode = np.empty((E * P, 2), dtype=np.uint32)
+        for first in range(0, pools, E):
+            for r in range(E):
+                gv.gv_augment(offsets, adj, seed=s["walk_seed"], first_walk=(first + r) * walks_per_pool, count=P,
+                              threads=16, out=episode[r * P:(r + 1) * P])
+            train_blocks(gv, ctx, part, B, episode, threads=16)
+            ref_loss, ref_auc, ref_nv, ref_nc = checkpoints[first + E]
+            loss = gv.gv_eval_loss(ctx, eval_pool, s["eval_seed"])
+            auc = gv.gv_link_prediction_auc(ctx, te_s, te_d, na, nb)
+            print(f"blocks long run after {first + E} pools: loss {loss:.4f} vs {ref_loss:.4f}; auc {auc:.4f} vs {ref_auc:.4f}",
+                  flush=True)
+            assert abs(loss - ref_loss) <= 0.02 * ref_loss
+        assert gv.gv_get_stats(ctx)["samples_trained"] == P * pools
+        assert abs(auc - checkpoints[pools][1]) <= 0.005
+
+
 def test_block_training_argument_errors(gv, tiny_graph):
     import torch
 
