@@ -141,7 +141,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "tiny", "c5-marginal"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "tiny", "c5-marginal", "c5"])
     ap.add_argument("--coherence", type=int, default=3, help="GV_COHERENCE_* of the asynchronous launches")
     ap.add_argument("--schedule", type=int, default=2, help="GV_SCHEDULE_* of the asynchronous launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -180,6 +180,19 @@ def main():
         edges = cfg["edges"]
         args.no_online = True
         log(f"degrees {args.workload}: n={n} ({time.perf_counter() - t0:.1f} s)")
+    elif cfg["graph"] == "chung_lu_on_device":
+        # the graph is built on the GPU with torch (sorting 3.6*10^9 adjacency entries on the host would take
+        # longer than everything else together) and handed to the library from host memory like any other
+        from workloads import device_graphs
+
+        off_t, adj_t = device_graphs.chung_lu_csr(cfg["n"], cfg["edges"], cfg["gamma"], cfg["number"], progress=log)
+        offsets, adj = device_graphs.to_host_csr(off_t, adj_t)
+        del off_t, adj_t
+        torch.cuda.empty_cache()
+        n, edges = cfg["n"], adj.size // 2
+        deg = np.diff(offsets).astype(np.uint32)
+        args.no_cpu_baseline = True  # the oracle's matrices of this size take minutes to initialise on the host
+        log(f"graph {args.workload}: n={n} edges={edges} max degree {deg.max()} ({time.perf_counter() - t0:.1f} s)")
     else:
         n, src, dst = W.make_graph(args.workload)
         deg = W.degrees(n, src, dst)

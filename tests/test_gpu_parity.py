@@ -1030,6 +1030,108 @@ def test_configuration_5_size_isolated_samples(gv):
             assert not gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=row).any()
 
 
+def test_configuration_5_as_stated_walks_and_training(gv):
+    """Configuration 5 with its graph: 6.6*10^7 nodes and 1.8*10^9 edges of the Chung-Lu kind (exponent 2.2), built on
+    the GPU by the input recipe and handed to the library from host memory (14.4 GB of adjacency).  The alias table
+    of the real degrees, the pools of the device producer and of the host producer (walks far beyond 2^32 included)
+    and the negatives are the oracle's bit for bit; every sample of a produced 2^22-sample pool whose three rows
+    nobody else names is exactly one oracle step from the initial embeddings (67.6 GB of rows)."""
+    import torch
+
+    from workloads import device_graphs
+
+    cfg = W.CONFIGS["c5"]
+    n, d, K, w, seed, T, count = cfg["n"], 128, 1, 5.0, 1234, 10_000_000_000, 1 << 22
+    L, s = W.configs.WALK_LENGTH, W.configs.WINDOW
+    first_g = 7_000_000_000
+    off_t, adj_t = device_graphs.chung_lu_csr(n, cfg["edges"], cfg["gamma"], cfg["number"],
+                                              progress=lambda text: print(text, flush=True))
+    # the recipe's own promises, checked where the arrays are: rows sorted, no loops, every edge in both rows
+    degree_t = off_t[1:] - off_t[:-1]
+    assert int(off_t[-1]) == adj_t.numel() and abs(adj_t.numel() // 2 - cfg["edges"]) < 1_000_000
+    for row in (int(torch.argmax(degree_t)), 12_345_678, n - 1):
+        lo, hi = int(off_t[row]), int(off_t[row + 1])
+        mine = adj_t[lo:hi].to(torch.int64)
+        assert bool((mine[1:] > mine[:-1]).all()) and not bool((mine == row).any())
+        for other in mine[:: max(1, mine.numel() // 50)].tolist():
+            theirs = adj_t[int(off_t[other]):int(off_t[other + 1])]
+            assert bool((theirs == row).any())
+    del degree_t
+    offsets, adj = device_graphs.to_host_csr(off_t, adj_t)
+    del off_t, adj_t
+    torch.cuda.empty_cache()
+    deg = np.diff(offsets).astype(np.uint32)
+    print(f"configuration 5: graph ready, {adj.size // 2} edges, largest degree {deg.max()}, "
+          f"{int((deg == 0).sum())} nodes without edge", flush=True)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=T, seed=seed,
+                     pool_capacity=8, lr0=LR0) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        got_t, got_a = gv.gv_get_alias(ctx, n)
+        assert np.array_equal(got_t, thresh) and np.array_equal(got_a, alias)
+        del got_t, got_a
+        gv.gv_set_adjacency(ctx, offsets, adj)
+        print("configuration 5: tables and adjacency on the device", flush=True)
+        buf = torch.empty((count, 2), dtype=torch.int32, device="cuda")
+        pool = None
+        for first_walk, size in ((0, count), ((1 << 33) + 5, 190 * 2000 + 17)):
+            gv.gv_augment_device(ctx, buf.data_ptr(), seed=505, first_walk=first_walk, count=size)
+            gv.gv_sync(ctx)
+            on_device = buf[:size].cpu().numpy().view(np.uint32)
+            expect, _ = oracle.augment(505, offsets, adj, L, s, size, first_walk=first_walk)
+            expect = oracle.pseudo_shuffle(expect, s)
+            assert np.array_equal(on_device, expect), first_walk
+            on_host, _ = gv.gv_augment(offsets, adj, seed=505, first_walk=first_walk, count=size, threads=16)
+            assert np.array_equal(on_host, expect), first_walk
+            if pool is None:
+                pool = expect
+        print("configuration 5: produced pools equal the oracle's", flush=True)
+        negs = oracle.draw_negatives(seed, first_g, count, K, thresh, alias)
+        assert np.array_equal(gv.gv_draw_negatives(ctx, first_g, 1 << 20, K), negs[:1 << 20])
+        # no sample of a walk pool is alone on its rows (a walk names each of its nodes several times): plant
+        # pairs of nodes that nothing else names at positions whose negative nothing else names
+        pool = pool.copy()
+        named = np.bincount(np.concatenate([pool.reshape(-1), negs.reshape(-1)]), minlength=n)
+        where = np.nonzero(named[negs[:, 0]] == 1)[0]
+        lonely = np.nonzero(named == 0)[0].astype(np.uint32)
+        planted = 1024
+        assert where.size >= planted and lonely.size >= 2 * planted
+        where = where[np.linspace(0, where.size - 1, planted).astype(np.int64)]
+        lonely = lonely[np.linspace(0, lonely.size - 1, 2 * planted).astype(np.int64)]  # from both ends of the matrices
+        pool[where, 0], pool[where, 1] = lonely[:planted], lonely[planted:]
+        del named
+        buf.copy_(torch.from_numpy(pool.view(np.int32)))
+        torch.cuda.synchronize()
+        gv.gv_init_embeddings(ctx, 9)
+        gv.gv_set_position(ctx, first_g)
+        gv.gv_train_device_pool(ctx, buf.data_ptr(), count)
+        gv.gv_sync(ctx)
+        stats = gv.gv_get_stats(ctx)
+        assert stats["samples_trained"] == first_g + count and stats["tiled_launches"] == 1
+        idx, cu, cc = singly_touched(pool, negs, n)
+        assert idx.size >= planted // 2, idx.size
+        rng = np.random.default_rng(0)
+        check = rng.choice(idx, size=300, replace=False)
+        worst = 0.0
+        for i in check:
+            u, v, z = int(pool[i, 0]), int(pool[i, 1]), int(negs[i, 0])
+            x0 = oracle.init_vertex_rows(9, u, 1, d)
+            sub_v, sub_c = x0.copy(), np.zeros((2, d), dtype=np.float32)
+            oracle.train(sub_v, sub_c, np.array([[0, 0]], dtype=np.uint32), K=1, first_g=first_g + int(i), T=T, lr0=LR0,
+                         lr_min_ratio=0.0, w=w, seed=seed, thresh=thresh[:2], alias=alias[:2],
+                         negatives=np.array([1], dtype=np.uint32))
+            got_x = gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d, row0=u)[0]
+            got_v = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=v)[0]
+            got_z = gv.gv_read_embeddings(ctx, gv.GV_CONTEXT, 1, d, row0=z)[0]
+            scale = np.abs(x0).max()
+            worst = max(worst, np.abs(got_x - sub_v[0]).max() / scale, np.abs(got_v - sub_c[0]).max() / scale,
+                        np.abs(got_z - sub_c[1]).max() / scale)
+            assert np.abs(got_v).max() > 0 and np.abs(got_z).max() > 0
+        print(f"configuration 5: {idx.size} isolated samples, {check.size} checked, worst rel. error {worst:.2e}")
+        assert worst <= 1e-5, worst
+
+
 # --------------------------------------------------------------------------- evaluation on the device
 @pytest.mark.parametrize("d,K,w", [(128, 1, 5.0), (96, 1, 5.0), (512, 5, 1.0), (64, 3, 2.0)])
 def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w):

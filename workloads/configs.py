@@ -22,7 +22,8 @@ CONFIGS = {
     # trained to its plateau (1600 samples per node), so that quality comparisons are stable
     "c4-small": dict(number=4, graph="planted_partition", n=5_000, communities=10, edges=50_000,
                      ratio=50.0, dim=128, num_neg=1, neg_weight=5.0, total_samples=8_000_000, pool=1 << 20),
-    "c5": dict(number=5, graph="chung_lu", n=66_000_000, edges=1_800_000_000, gamma=2.2, dim=128, num_neg=1,
+    # generated on the GPU (device_graphs.chung_lu_csr): far too large for the numpy recipe
+    "c5": dict(number=5, graph="chung_lu_on_device", n=66_000_000, edges=1_800_000_000, gamma=2.2, dim=128, num_neg=1,
                neg_weight=5.0, total_samples=10_000_000_000, pool=1 << 24),
 }
 # configuration 5 without its adjacency: Chung-Lu expected degrees for 6.6*10^7 nodes / 1.8*10^9 edges and pools
@@ -38,6 +39,8 @@ def make_graph(name: str, cache: bool = True):
     """Edge list ``(n, src, dst)`` of a named configuration (cached as .npz in
     the temp directory because the million-node graphs take a while)."""
     cfg = CONFIGS[name]
+    if cfg["graph"] in ("chung_lu_on_device", "expected_degrees"):
+        raise ValueError(f"{name}: no edge list in host memory; see device_graphs.chung_lu_csr / expected_degrees")
     seed = cfg.get("graph_seed", cfg["number"])
     path = os.path.join(tempfile.gettempdir(), f"gv_workload_{cfg['graph']}_{cfg['n']}_{seed}.npz")
     if cache and os.path.exists(path):
