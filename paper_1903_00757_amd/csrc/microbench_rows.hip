@@ -42,12 +42,17 @@ enum Op {
     kAddGroup,          // workgroup-scope fp32 atomic add
     kReadAgentAddAgent, // device-scope load, then device-scope atomic add
     kReadPlainAddAgent, // cached load, then device-scope atomic add (same lines)
+    kReadAgentNt,       // device-scope loads with the non-temporal hint
+    kRmwAgentNt,        // device-scope load and store, both with the non-temporal hint
+    kRmwAgentNtStore,   // device-scope load, device-scope store with the non-temporal hint
     kOps
 };
 static const char *kOpName[kOps] = {"read plain", "read device-scope", "rmw plain", "rmw device-scope", "rmw group-scope",
                                     "atomic add device-scope", "atomic add group-scope",
-                                    "device-scope read + atomic add", "plain read + atomic add"};
-static const double kOpBytes[kOps] = {512, 512, 1024, 1024, 1024, 512, 512, 1024, 1024};
+                                    "device-scope read + atomic add", "plain read + atomic add",
+                                    "read device-scope, non-temporal", "rmw device-scope, non-temporal",
+                                    "rmw device-scope, nt store only"};
+static const double kOpBytes[kOps] = {512, 512, 1024, 1024, 1024, 512, 512, 1024, 1024, 512, 1024, 1024};
 
 template <int kScope>
 __device__ __forceinline__ f2 load_scoped(const float *p) {
@@ -59,6 +64,23 @@ template <int kScope>
 __device__ __forceinline__ void store_scoped(float *p, f2 v) {
     const uint64_t bits = (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32);
     __hip_atomic_store((uint64_t *)p, bits, __ATOMIC_RELAXED, kScope);
+}
+
+// Device-scope accesses with the non-temporal hint (lines marked for early replacement in the caches): the
+// compiler offers no such combination, so the instructions are written out.  A load written this way is
+// invisible to the compiler's own wait counting: settle() waits for all of them and ties the registers to that
+// wait, so that no use can be scheduled before it.
+__device__ __forceinline__ uint64_t load_agent_nt(const float *p) {
+    uint64_t bits;
+    asm volatile("global_load_dwordx2 %0, %1, off sc1 nt" : "=v"(bits) : "v"(p) : "memory");
+    return bits;
+}
+__device__ __forceinline__ void store_agent_nt(float *p, f2 v) {
+    const uint64_t bits = (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32);
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(bits) : "memory");
+}
+__device__ __forceinline__ void settle(uint64_t &a, uint64_t &b, uint64_t &c, uint64_t &d) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : : "memory");
 }
 
 // Batches of kBatch rows per wave: all loads of a batch are issued before the first update, as in the trainer.
@@ -79,6 +101,17 @@ __global__ __launch_bounds__(256) void k_rows(float *table, const uint32_t *ids,
                 v[b] = load_scoped<__HIP_MEMORY_SCOPE_AGENT>(row[b] + lane * 2);
             if (kOp == kRmwGroup) v[b] = load_scoped<__HIP_MEMORY_SCOPE_WORKGROUP>(row[b] + lane * 2);
             if (kOp == kAddAgent || kOp == kAddGroup) v[b] = f2{0.f, 0.f};
+            if (kOp == kRmwAgentNtStore) v[b] = load_scoped<__HIP_MEMORY_SCOPE_AGENT>(row[b] + lane * 2);
+        }
+        if (kOp == kReadAgentNt || kOp == kRmwAgentNt) {
+            static_assert(kBatch == 4, "settle() takes four rows");
+            uint64_t bits[kBatch];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) bits[b] = load_agent_nt(row[b] + lane * 2);
+            settle(bits[0], bits[1], bits[2], bits[3]);
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b)
+                v[b] = f2{__uint_as_float((uint32_t)bits[b]), __uint_as_float((uint32_t)(bits[b] >> 32))};
         }
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
@@ -87,6 +120,7 @@ __global__ __launch_bounds__(256) void k_rows(float *table, const uint32_t *ids,
             if (kOp == kRmwPlain) *(f2 *)(row[b] + lane * 2) = next;
             if (kOp == kRmwAgent) store_scoped<__HIP_MEMORY_SCOPE_AGENT>(row[b] + lane * 2, next);
             if (kOp == kRmwGroup) store_scoped<__HIP_MEMORY_SCOPE_WORKGROUP>(row[b] + lane * 2, next);
+            if (kOp == kRmwAgentNt || kOp == kRmwAgentNtStore) store_agent_nt(row[b] + lane * 2, next);
             if (kOp == kAddAgent || kOp == kReadAgentAddAgent || kOp == kReadPlainAddAgent) {
                 (void)__hip_atomic_fetch_add(row[b] + lane, 1.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 (void)__hip_atomic_fetch_add(row[b] + 64 + lane, 1.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -130,6 +164,9 @@ static float time_any(int op, float *table, const uint32_t *ids, uint32_t count,
         case kAddAgent: return time_op<kAddAgent>(table, ids, count, sink, grid);
         case kAddGroup: return time_op<kAddGroup>(table, ids, count, sink, grid);
         case kReadAgentAddAgent: return time_op<kReadAgentAddAgent>(table, ids, count, sink, grid);
+        case kReadAgentNt: return time_op<kReadAgentNt>(table, ids, count, sink, grid);
+        case kRmwAgentNt: return time_op<kRmwAgentNt>(table, ids, count, sink, grid);
+        case kRmwAgentNtStore: return time_op<kRmwAgentNtStore>(table, ids, count, sink, grid);
         default: return time_op<kReadPlainAddAgent>(table, ids, count, sink, grid);
     }
 }
@@ -226,7 +263,7 @@ int main(int argc, char **argv) {
             CK(hipMemset(table, 0, (size_t)n * 512));
             CK(hipMalloc(&dids, (size_t)count * 4));
             CK(hipMemcpy(dids, ids.data(), (size_t)count * 4, hipMemcpyHostToDevice));
-            for (int op : {(int)kReadAgent, (int)kRmwAgent, (int)kRmwPlain}) {
+            for (int op : {(int)kReadAgent, (int)kRmwAgent, (int)kRmwPlain, (int)kRmwAgentNt}) {
                 const float ms = time_any(op, table, dids, count, sink, grid);
                 printf("table %5u MB  %-32s %.3f ms  %.3g rows/s  %.0f GB/s\n", mb, kOpName[op], ms, count / (ms * 1e-3),
                        count * kOpBytes[op] / (ms * 1e-3) / 1e9);
