@@ -103,6 +103,21 @@ def cpu_baseline(offsets, adj, deg, cfg, seed, samples_one_core, samples_per_thr
     out["all_cores"] = {"value": cores * samples_per_thread / dt, "unit": "positive samples/s", "cores": cores,
                         "kind": "oracle", "sample": f"{cores} threads x {samples_per_thread} samples of the same pool, the "
                         f"same loop run lock-free on shared matrices, {dt:.1f} s"}
+    # configuration 1 whole (2*10^6 samples on 10^4 nodes: matrices that fit the host caches)
+    tiny = W.CONFIGS["tiny"]
+    tn, tsrc, tdst = W.make_graph("tiny")
+    tdeg = W.degrees(tn, tsrc, tdst)
+    toff, tadj = W.csr_from_edges(tn, tsrc, tdst)
+    tpool, _ = oracle.augment(100 * tiny["number"], toff, tadj, W.configs.WALK_LENGTH, W.configs.WINDOW, tiny["pool"])
+    tpool = oracle.pseudo_shuffle(tpool, W.configs.WINDOW)
+    tt, ta = oracle.alias_build(oracle.degree_weights(tdeg))
+    tv, tc = oracle.init_embeddings(1, tn, tiny["dim"])
+    t0 = time.perf_counter()
+    oracle.train(tv, tc, tpool, first_g=0, K=tiny["num_neg"], T=tiny["total_samples"], lr0=0.025, lr_min_ratio=0.0,
+                 w=tiny["neg_weight"], seed=seed, thresh=tt, alias=ta)
+    dt = time.perf_counter() - t0
+    out["configuration_1"] = {"value": tpool.shape[0] / dt, "unit": "positive samples/s", "cores": 1, "kind": "oracle",
+                              "sample": f"all {tpool.shape[0]} samples of configuration 1, {dt:.1f} s"}
     return out
 
 
