@@ -47,8 +47,9 @@ def test_host_runtime_under_address_and_undefined_behaviour_sanitizers(tmp_path)
     """All host sources (producers, and the runtime behind the C boundary compiled by hipcc with the sanitizers
     on its host pass only); the kernels are linked unsanitized and never launched here."""
     exe = str(tmp_path / "driver_asan")
-    host_flags = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
-                  "-fno-omit-frame-pointer"]
+    # sanitizers on the host pass only; the device code is built as always
+    host_flags = "-Xarch_host -fsanitize=address -Xarch_host -fsanitize=undefined -Xarch_host -fno-omit-frame-pointer".split()
+    plain_flags = "-fsanitize=address -fsanitize=undefined -fno-gpu-sanitize -fno-omit-frame-pointer".split()
     common = [HIPCC, "-std=c++17", "-O1", "-g", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Xclang", "-target-feature",
               "-Xclang", "-packed-fp32-ops", *INCLUDES]
     objects = []
@@ -65,10 +66,8 @@ def test_host_runtime_under_address_and_undefined_behaviour_sanitizers(tmp_path)
         subprocess.run([*common, *flags, "-c", os.path.join(CSRC, src), "-o", obj], check=True, capture_output=True, text=True)
         objects.append(obj)
     driver_obj = str(tmp_path / "driver.o")
-    subprocess.run([HIPCC, "-std=c++17", "-O1", "-g", *INCLUDES, "-fsanitize=address", "-fsanitize=undefined",
-                    "-fno-gpu-sanitize", "-fno-omit-frame-pointer", "-c", DRIVER, "-o", driver_obj],
+    subprocess.run([HIPCC, "-std=c++17", "-O1", "-g", *INCLUDES, *plain_flags, "-c", DRIVER, "-o", driver_obj],
                    check=True, capture_output=True, text=True)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", driver_obj,
-           *objects, "-o", exe, "-lpthread"]
+    cmd = [HIPCC, "--offload-arch=gfx950", *plain_flags, driver_obj, *objects, "-o", exe, "-lpthread"]
     # the HIP runtime keeps process-lifetime allocations: leak checking is about the library's own calls only
     run_clean(cmd, exe, {"ASAN_OPTIONS": "detect_leaks=0:halt_on_error=1", "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1"})
