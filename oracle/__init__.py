@@ -61,6 +61,8 @@ def lib():
         L.orc_train.restype = None
         L.orc_train_ordered.argtypes = L.orc_train.argtypes + [u32p]
         L.orc_train_ordered.restype = None
+        L.orc_train_tracked.argtypes = L.orc_train_ordered.argtypes + [f64p]
+        L.orc_train_tracked.restype = None
         L.orc_zigzag_partition.argtypes = [C.c_uint64, u32p, C.c_uint32, u32p]
         L.orc_zigzag_partition.restype = None
         L.orc_partition_alias.argtypes = [C.c_uint64, u32p, C.c_uint32, u32p, u64p, u32p, u32p, u32p]
@@ -268,10 +270,11 @@ def train_blocked(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w
 
 
 def train(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, thresh, alias, negatives=None,
-          order=None):
+          order=None, return_loss=False):
     """In-place sequential SGD over ``pairs``; ``vertex``/``context`` must be
     C-contiguous float32 arrays of shape (n, d).  ``order``: the sequence in which the samples are taken
-    (indices into ``pairs``), pool order when None."""
+    (indices into ``pairs``), pool order when None.  ``return_loss``: return the sum over the samples of the
+    loss each of them saw before its step."""
     assert vertex.dtype == np.float32 and context.dtype == np.float32
     assert vertex.flags.c_contiguous and context.flags.c_contiguous
     pairs = _arr(pairs, np.uint32)
@@ -286,9 +289,12 @@ def train(vertex, context, pairs, *, K, first_g, T, lr0, lr_min_ratio, w, seed, 
         order = _arr(order, np.uint32)
         assert order.size == pairs.shape[0]
         orderp = _p(order, C.c_uint32)
-    lib().orc_train_ordered(_p(vertex, C.c_float), _p(context, C.c_float), n, d, K, _p(pairs, C.c_uint32),
+    seen = np.zeros(1, dtype=np.float64)
+    lib().orc_train_tracked(_p(vertex, C.c_float), _p(context, C.c_float), n, d, K, _p(pairs, C.c_uint32),
                             pairs.shape[0], first_g, T, lr0, lr_min_ratio, w, seed,
-                            _p(thresh, C.c_uint32), _p(alias, C.c_uint32), negp, orderp)
+                            _p(thresh, C.c_uint32), _p(alias, C.c_uint32), negp, orderp,
+                            _p(seen, C.c_double) if return_loss else None)
+    return float(seen[0]) if return_loss else None
 
 
 def loss(vertex, context, pairs, *, K, w, seed, thresh, alias, stream=STREAM_EVAL):

@@ -343,10 +343,11 @@ float orc_learning_rate(float lr0, float lr_min_ratio, uint64_t g, uint64_t T)
  * `negatives` may be NULL (then they are drawn here from stream 0) or hold K
  * indices per sample.                                                        */
 /* One positive sample at global position g: u, v, its K negatives in neg[1..K] (neg[0] = v).  Scratch
- * arrays of d doubles (dx, xu) and K + 1 doubles (coef) come from the caller.                          */
+ * arrays of d doubles (dx, xu) and K + 1 doubles (coef) come from the caller.  `loss` (may be NULL): the
+ * value of the loss above at the rows as the sample finds them is added to it.                          */
 static void train_sample(float *vertex, float *context, uint32_t d, uint32_t K, uint32_t u, const uint32_t *neg,
                          uint64_t g, uint64_t T, float lr0, float lr_min_ratio, float w,
-                         double *dx, double *xu, double *coef)
+                         double *dx, double *xu, double *coef, double *loss)
 {
     double lr = (double)orc_learning_rate(lr0, lr_min_ratio, g, T);
     float *x = vertex + (size_t)u * d;
@@ -355,6 +356,7 @@ static void train_sample(float *vertex, float *context, uint32_t d, uint32_t K, 
         double score = 0.0;
         for (uint32_t j = 0; j < d; ++j) score += (double)x[j] * (double)c[j];
         coef[k] = k == 0 ? lr * (1.0 - sigmoid(score)) : -lr * (double)w * sigmoid(score);
+        if (loss) *loss += k == 0 ? -log_sigmoid(score) : -(double)w * log_sigmoid(-score);
     }
     for (uint32_t j = 0; j < d; ++j) { xu[j] = (double)x[j]; dx[j] = 0.0; }
     for (uint32_t k = 0; k <= K; ++k) {
@@ -377,12 +379,15 @@ static void train_sample(float *vertex, float *context, uint32_t d, uint32_t K, 
 /* `order` (may be NULL = pool order): the sequence in which the samples are taken, order[k] = index into
  * pairs / negatives of the k-th sample trained; a sample keeps the position first_g + its index whatever
  * its turn (position decides its negatives and its learning rate).                                      */
-void orc_train_ordered(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
+/* `loss_sum` (may be NULL): receives the sum over the samples of the loss each of them saw before its step
+ * (the running training loss that a trainer reports while it works).                                    */
+void orc_train_tracked(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
                        const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
                        float lr0, float lr_min_ratio, float w, uint64_t seed,
                        const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives,
-                       const uint32_t *order)
+                       const uint32_t *order, double *loss_sum)
 {
+    double seen = 0.0;
     double *dx = (double *)malloc((size_t)d * sizeof(double));
     double *xu = (double *)malloc((size_t)d * sizeof(double));
     uint32_t *neg = (uint32_t *)malloc(((size_t)K + 1) * sizeof(uint32_t));
@@ -400,9 +405,21 @@ void orc_train_ordered(float *vertex, float *context, uint64_t n, uint32_t d, ui
                 neg[k + 1] = alias_draw(r, n, thresh, alias);
             }
         }
-        train_sample(vertex, context, d, K, pairs[2 * i], neg, g, T, lr0, lr_min_ratio, w, dx, xu, coef);
+        train_sample(vertex, context, d, K, pairs[2 * i], neg, g, T, lr0, lr_min_ratio, w, dx, xu, coef,
+                     loss_sum ? &seen : NULL);
     }
+    if (loss_sum) *loss_sum = seen;
     free(dx); free(xu); free(neg); free(coef);
+}
+
+void orc_train_ordered(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,
+                       const uint32_t *pairs, uint64_t count, uint64_t first_g, uint64_t T,
+                       float lr0, float lr_min_ratio, float w, uint64_t seed,
+                       const uint32_t *thresh, const uint32_t *alias, const uint32_t *negatives,
+                       const uint32_t *order)
+{
+    orc_train_tracked(vertex, context, n, d, K, pairs, count, first_g, T, lr0, lr_min_ratio, w, seed,
+                      thresh, alias, negatives, order, NULL);
 }
 
 void orc_train(float *vertex, float *context, uint64_t n, uint32_t d, uint32_t K,

@@ -186,6 +186,35 @@ def test_loss_closed_forms(tiny_graph, tiny_alias):
     assert abs(got - expect.mean()) < 1e-9 * abs(expect.mean())
 
 
+def test_running_loss_is_the_loss_each_sample_sees_before_its_step():
+    """The sum that training reports, against scipy's log-sigmoid on the rows saved before every step (a small
+    graph, so samples share rows and the sequence matters), and in closed form for the first sample."""
+    rng = np.random.default_rng(12)
+    n, d, K, w, count = 12, 8, 2, 3.0, 200
+    vertex = rng.standard_normal((n, d)).astype(np.float32)
+    context = rng.standard_normal((n, d)).astype(np.float32)
+    pairs = rng.integers(n, size=(count, 2)).astype(np.uint32)
+    negs = rng.integers(n, size=(count, K)).astype(np.uint32)
+    negs[3, 0] = pairs[3, 1]  # a negative that is the positive row: both terms count
+    kw = dict(K=K, T=1000, lr0=0.05, lr_min_ratio=0.0, w=w, seed=1, thresh=np.zeros(n, np.uint32),
+              alias=np.zeros(n, np.uint32))
+    expect = 0.0
+    v, c = vertex.copy(), context.copy()
+    for i in range(count):
+        x = v[pairs[i, 0]].astype(np.float64)
+        expect += -log_expit(x @ c[pairs[i, 1]].astype(np.float64))
+        for k in range(K):
+            expect += -w * log_expit(-(x @ c[negs[i, k]].astype(np.float64)))
+        assert oracle.train(v, c, pairs[i:i + 1], first_g=i, negatives=negs[i:i + 1], **kw) is None
+    v2, c2 = vertex.copy(), context.copy()
+    got = oracle.train(v2, c2, pairs, first_g=0, negatives=negs, return_loss=True, **kw)
+    assert abs(got - expect) < 1e-10 * expect
+    assert np.array_equal(v, v2) and np.array_equal(c, c2)  # asking for the sum changes nothing
+    zeros = np.zeros((n, d), dtype=np.float32)
+    first = oracle.train(vertex.copy(), zeros.copy(), pairs[:1], first_g=0, negatives=negs[:1], return_loss=True, **kw)
+    assert abs(first - (1 + w * K) * np.log(2.0)) < 1e-12
+
+
 def test_training_lowers_the_loss_it_descends(tiny_graph, tiny_alias):
     thresh, alias = tiny_alias
     g = tiny_graph
