@@ -100,6 +100,8 @@ typedef struct gv_config {
     uint32_t partitions;     /* 0, or the number B of partitions of the rows for the orthogonal-block
                                 schedule of Sec. 3.2 (2..GV_MAX_PARTITIONS): gv_build_alias then also
                                 partitions the nodes and builds one alias table per partition    */
+    uint32_t track_loss;     /* nonzero: every training launch also sums the loss its samples see before
+                                their step (gv_stats.train_loss_sum)                             */
 } gv_config;
 
 typedef struct gv_stats {
@@ -114,6 +116,11 @@ typedef struct gv_stats {
     uint64_t h2d_bytes;
     uint64_t tiled_launches;    /* asynchronous launches that took the tiled schedule            */
     uint64_t warm_rows;         /* rows that gv_build_alias classed as warm (see GV_SCHEDULE_AUTO) */
+    double train_loss_sum;      /* track_loss != 0: sum over the samples trained so far of the loss (Alg. 1 with
+                                   the logistic loss of negative sampling, as gv_eval_loss) each of them saw
+                                   at the rows it read, before its own step: the running training loss is
+                                   train_loss_sum / train_loss_samples.  Resolved by gv_sync.            */
+    uint64_t train_loss_samples;
 } gv_stats;
 
 /* Create a context on cfg->device (one GPU holds all rows: the single-GPU case of

@@ -41,7 +41,7 @@ class gv_config(C.Structure):
         ("mode", C.c_uint32),
         ("total_samples", C.c_uint64), ("seed", C.c_uint64), ("pool_capacity", C.c_uint64),
         ("device", C.c_int32), ("coherence", C.c_uint32), ("profile", C.c_uint32), ("schedule", C.c_uint32),
-        ("pool_slots", C.c_uint32), ("partitions", C.c_uint32),
+        ("pool_slots", C.c_uint32), ("partitions", C.c_uint32), ("track_loss", C.c_uint32),
     ]
 
 
@@ -50,6 +50,7 @@ class gv_stats(C.Structure):
         ("samples_trained", C.c_uint64), ("pools_trained", C.c_uint64), ("train_launches", C.c_uint64),
         ("batches", C.c_uint64), ("train_kernel_ms", C.c_double), ("timed_launches", C.c_uint64),
         ("h2d_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("tiled_launches", C.c_uint64), ("warm_rows", C.c_uint64),
+        ("train_loss_sum", C.c_double), ("train_loss_samples", C.c_uint64),
     ]
 
     def as_dict(self):
@@ -138,11 +139,11 @@ def _u32(a):
 
 def gv_create(*, dim, num_neg, lr0=0.025, lr_min_ratio=0.0, neg_weight=GV_NEG_WEIGHT_DEFAULT, mode=GV_MODE_HOGWILD,
               total_samples, seed=1234, pool_capacity, device=0, coherence=GV_COHERENCE_MIXED, profile=0,
-              schedule=GV_SCHEDULE_AUTO, pool_slots=0, partitions=0):
+              schedule=GV_SCHEDULE_AUTO, pool_slots=0, partitions=0, track_loss=0):
     cfg = gv_config(dim=dim, num_neg=num_neg, lr0=lr0, lr_min_ratio=lr_min_ratio, neg_weight=neg_weight, mode=mode,
                     total_samples=total_samples, seed=seed, pool_capacity=pool_capacity, device=device,
                     coherence=coherence, profile=profile, schedule=schedule, pool_slots=pool_slots,
-                    partitions=partitions)
+                    partitions=partitions, track_loss=track_loss)
     ctx = C.c_void_p()
     rc = load().gv_create(C.byref(cfg), C.byref(ctx))
     _check(None, rc)

@@ -78,6 +78,7 @@ struct gv_ctx {
     uint32_t *dev_adj = nullptr;
     uint64_t half_edges = 0;
     uint32_t *error_flag = nullptr;       // device
+    double *dev_loss = nullptr;           // device, cfg.track_loss: gv::kLossSlots running sums of the training loss
     uint32_t *negatives = nullptr;        // device scratch, deterministic mode / gv_draw_negatives
     uint64_t negatives_capacity = 0;      // in uint32 elements
     uint32_t *records = nullptr;          // device scratch of the tiled kernel: K + 3 words per sample of a launch
@@ -177,6 +178,13 @@ int sync_all(gv_ctx *ctx) {
     fold_spans(ctx);
     for (PoolSlot &s : ctx->slot)
         if (s.state == kTraining) s.state = kFree;
+    if (ctx->dev_loss) {
+        double slots[gv::kLossSlots];
+        GV_HIP(ctx, hipMemcpy(slots, ctx->dev_loss, sizeof slots, hipMemcpyDeviceToHost));
+        double total = 0.0;
+        for (double x : slots) total += x;
+        ctx->stats.train_loss_sum = total;
+    }
     uint32_t flag = 0;
     GV_HIP(ctx, hipMemcpy(&flag, ctx->error_flag, sizeof flag, hipMemcpyDeviceToHost));
     if (flag) {
@@ -290,6 +298,7 @@ gv::TrainArgs train_args(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t first_
     a.ranked = ctx->n > 20u * 0xFFFFu ? ctx->dev_ranked : nullptr;  // under 5 % of the nodes ranked
     a.warm_ranks = ctx->warm_ranks;
     a.error_flag = ctx->error_flag;
+    a.loss_slots = ctx->dev_loss;
     a.first_g = first_g;
     a.total = ctx->cfg.total_samples;
     a.seed = ctx->cfg.seed;
@@ -375,6 +384,7 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32
     }
     ctx->stats.train_launches += 1;
     ctx->stats.tiled_launches += tiled ? 1 : 0;
+    if (ctx->dev_loss) ctx->stats.train_loss_samples += count;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
 }
@@ -445,6 +455,7 @@ int train_deterministic(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *
     }
     ctx->stats.train_launches += starts.size() - 1;
     ctx->stats.batches += starts.size() - 1;
+    if (ctx->dev_loss) ctx->stats.train_loss_samples += count;
     if (timed) return end_span(ctx, ctx->compute, span);
     return GV_OK;
 }
@@ -593,6 +604,10 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
         GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
         GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
         GV_TRY(hipMemset(ctx->error_flag, 0, sizeof(uint32_t)));
+        if (cfg->track_loss) {
+            GV_TRY(hipMalloc((void **)&ctx->dev_loss, gv::kLossSlots * sizeof(double)));
+            GV_TRY(hipMemset(ctx->dev_loss, 0, gv::kLossSlots * sizeof(double)));
+        }
         const size_t pool_bytes = (size_t)cfg->pool_capacity * 2 * sizeof(uint32_t);
         for (PoolSlot &s : ctx->slot) {
             GV_TRY(hipHostMalloc((void **)&s.host, pool_bytes, hipHostMallocDefault));
@@ -631,6 +646,7 @@ void gv_destroy(gv_ctx *ctx) {
     if (ctx->records) (void)hipFree(ctx->records);
     if (ctx->eval_scratch) (void)hipFree(ctx->eval_scratch);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
+    if (ctx->dev_loss) (void)hipFree(ctx->dev_loss);
     if (ctx->copy) (void)hipStreamDestroy(ctx->copy);
     if (ctx->compute) (void)hipStreamDestroy(ctx->compute);
     delete ctx;

@@ -30,6 +30,8 @@ struct TrainArgs {
     uint32_t *records;        // tiled schedule: scratch of count x (K + 3) words, written and read by the launch
                               // (u, v, the K negatives, warm flags of the negatives)
     uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
+    double *loss_slots;       // null, or kLossSlots sums: every wave adds the losses its samples saw before their
+                              // steps to slot (workgroup number mod kLossSlots)
     uint64_t first_g;         // global position of pairs[0]
     uint64_t total;           // T of the learning-rate schedule
     uint64_t seed;            // Philox key of the negative stream
@@ -38,6 +40,8 @@ struct TrainArgs {
     uint32_t dim;             // d: row length in floats
     float lr0, lr_min_ratio, neg_weight;
 };
+
+constexpr uint32_t kLossSlots = 64;
 
 // Launch shapes are chosen here; both return the HIP error of the launch.
 hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,

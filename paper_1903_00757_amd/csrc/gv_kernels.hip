@@ -237,6 +237,18 @@ struct RowIo {
 
 __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
+// Running training loss (kernels instantiated with kTrack only): -log sigmoid(z) = log(1 + e^-z) for either
+// sign of z; a positive's score s contributes minus_log_sigmoid(s), a negative's w * minus_log_sigmoid(-s).
+// A wave sums what its samples saw in fp32 and hands the sum over every so often as one fp64 atomic add
+// (the values are wave-uniform: lane 0 adds).
+__device__ __forceinline__ float minus_log_sigmoid(float z) { return fmaxf(-z, 0.0f) + log1pf(__expf(-fabsf(z))); }
+__device__ __forceinline__ void hand_over_loss(double *slots, float &loss, int lane) {
+    if (lane == 0)
+        (void)__hip_atomic_fetch_add(slots + (blockIdx.x % kLossSlots), (double)loss, __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+    loss = 0.0f;
+}
+
 // One positive sample with its K negatives (Alg. 1, the Train calls; Sec. 2.1
 // scores; Sec. 4.3 negative weight): rows[0] is the positive context row v,
 // rows[1..K] the negatives.  All 1+K scores come from the rows as loaded, then
@@ -244,10 +256,12 @@ __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + __expf
 //   context[rows_k] += coef_k * vertex[u]
 // with coef_0 = lr (1 - sigmoid(s_0)), coef_k = -lr w sigmoid(s_k).  A context
 // row named more than once in the sample is written once with the summed
-// coefficient.  u and rows[] are wave-uniform.
-template <int kV, int kK, int kCoherence, bool kFull>
+// coefficient.  u and rows[] are wave-uniform.  kTrack: the sample's loss at the rows as loaded is added
+// to `loss`.
+template <int kV, int kK, int kCoherence, bool kFull, bool kTrack>
 __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__restrict__ context, uint32_t u,
-                                          const uint32_t (&rows)[kK + 1], float lr, float w, int lane, uint32_t D) {
+                                          const uint32_t (&rows)[kK + 1], float lr, float w, int lane, uint32_t D,
+                                          float &loss) {
     using Io = RowIo<kV, kCoherence, kFull>;
     float *xp = vertex + (size_t)u * D;
     float x[kV];
@@ -264,6 +278,7 @@ __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__r
         for (int j = 0; j < kV; ++j) partial = fmaf(x[j], c[k][j], partial);
         const float score = wave_sum(partial);
         coef[k] = k == 0 ? lr * (1.0f - sigmoid(score)) : -(lr * w) * sigmoid(score);
+        if constexpr (kTrack) loss += k == 0 ? minus_log_sigmoid(score) : w * minus_log_sigmoid(-score);
     }
 
     float dx[kV];
@@ -309,13 +324,15 @@ __device__ __forceinline__ void sgns_step(float *__restrict__ vertex, float *__r
 // consecutive samples: lane l reads sample l of the chunk (one coalesced 512 B
 // read), draws that sample's negatives and learning rate, and the wave then
 // walks the 64 samples in order, fetching each one's ids from the owning lane.
-template <int kV, int kK, int kCoherence, bool kFull>
+template <int kV, int kK, int kCoherence, bool kFull, bool kTrack>
 __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
     const uint32_t waves = gridDim.x * (kBlock / kWave);
     const uint32_t chunks = (a.count + kWave - 1) / kWave;
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
+    float loss = 0.0f;
+    uint32_t chunks_done = 0;
 
     for (uint32_t chunk = wave; chunk < chunks; chunk += waves) {
         const uint32_t base = chunk * kWave;
@@ -337,9 +354,12 @@ __global__ __launch_bounds__(kBlock) void k_train_hogwild(TrainArgs a) {
 #pragma unroll
             for (int k = 0; k < kK; ++k) rows[k + 1] = lane_value(neg[k], i);
             const float lr_i = __uint_as_float(lane_value(__float_as_uint(lr), i));
-            sgns_step<kV, kK, kCoherence, kFull>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane, a.dim);
+            sgns_step<kV, kK, kCoherence, kFull, kTrack>(a.vertex, a.context, u, rows, lr_i, a.neg_weight, lane, a.dim,
+                                                         loss);
         }
+        if (kTrack && (++chunks_done & 15u) == 0u) hand_over_loss(a.loss_slots, loss, lane);
     }
+    if constexpr (kTrack) hand_over_loss(a.loss_slots, loss, lane);
 }
 
 // Update of a row that is not held in registers: row += total * other.  Atomic adds keep
@@ -402,7 +422,7 @@ __device__ __forceinline__ void sort_tile(uint32_t *word) {
 // bit of the pair of context rows j1 < j2 (rows 1 .. K + 1 of a sample) in a sample's `same` word
 __host__ __device__ constexpr int pair_bit(int j1, int j2) { return (j1 - 1) * 6 + (j2 - 1); }
 
-template <int kV, int kK, int kCoherence, int kTile, bool kFull>
+template <int kV, int kK, int kCoherence, int kTile, bool kFull, bool kTrack>
 __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     const uint32_t D = a.dim;
     // One sort word per sample.  On top, 14 bits for its stationary row: the matrix, then either
@@ -439,6 +459,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint2 *__restrict__ pairs = (const uint2 *)a.pairs;
     const uint32_t tiles = (a.count + kTile - 1) / kTile;
+    float loss = 0.0f;  // kTrack: of the samples this wave has trained since it last handed its sum over
 
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint32_t tile_base = tile * kTile;
@@ -671,6 +692,8 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
                     for (int e = 0; e < kV; ++e) partial = fmaf(x[e], c[k][e], partial);
                     const float score = wave_sum(partial);
                     coef[k] = k == 0 ? cur.lr * (1.0f - sigmoid(score)) : -lrw * sigmoid(score);
+                    if constexpr (kTrack)
+                        loss += k == 0 ? minus_log_sigmoid(score) : a.neg_weight * minus_log_sigmoid(-score);
                 }
                 // context rows first (they take the vertex row as it was), each distinct row once
 #pragma unroll
@@ -777,6 +800,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             if (in_chunk < (uint32_t)kWave) break;
         }
         flush();
+        if constexpr (kTrack) hand_over_loss(a.loss_slots, loss, lane);
         __syncthreads();  // the next tile overwrites the LDS arrays
     }
 }
@@ -784,7 +808,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
 // Deterministic mode: wave i trains sample i of a batch whose samples share no
 // vertex row and no context row (Def. 1, Sec. 3.2: such samples commute), so the
 // result equals the sequential order up to fp32 rounding inside a sample.
-template <int kV, int kK, bool kFull>
+template <int kV, int kK, bool kFull, bool kTrack>
 __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t i = __builtin_amdgcn_readfirstlane((blockIdx.x * kBlock + threadIdx.x) / kWave);
@@ -799,7 +823,9 @@ __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
 #pragma unroll
     for (int k = 0; k < kK; ++k) rows[k + 1] = a.negatives[(size_t)i * kK + k];
     const float lr = learning_rate(a.lr0, a.lr_min_ratio, a.first_g + i, a.total);
-    sgns_step<kV, kK, kPlain, kFull>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim);
+    float loss = 0.0f;
+    sgns_step<kV, kK, kPlain, kFull, kTrack>(a.vertex, a.context, u, rows, lr, a.neg_weight, lane, a.dim, loss);
+    if constexpr (kTrack) hand_over_loss(a.loss_slots, loss, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -1020,20 +1046,27 @@ uint32_t hogwild_blocks(uint32_t count, uint32_t n) {
 }
 
 // A row that fills its lanes exactly (d = 64, 128, 256, 512) takes the kernels without per-lane bounds tests.
-template <int kV, int kK, bool kFull>
-hipError_t launch_hogwild_vkf(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
+template <int kV, int kK, bool kFull, bool kTrack>
+hipError_t launch_hogwild_vkft(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
     switch (coherence) {
         case kAgent:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAgent, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAgent, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
         case kAtomicAgent:
         case kMixed:  // the per-row choice exists in the tiled kernel only
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kAtomicAgent, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
             break;
         default:
-            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
+            hipLaunchKernelGGL((k_train_hogwild<kV, kK, kPlain, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
     }
     return hipGetLastError();
+}
+
+// the kernels that also sum the running loss are separate instantiations: the ones that do not carry none of it
+template <int kV, int kK, bool kFull>
+hipError_t launch_hogwild_vkf(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
+    return a.loss_slots ? launch_hogwild_vkft<kV, kK, kFull, true>(a, coherence, blocks, stream)
+                        : launch_hogwild_vkft<kV, kK, kFull, false>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -1044,15 +1077,21 @@ hipError_t launch_hogwild_vk(const TrainArgs &a, uint32_t coherence, hipStream_t
                                            : launch_hogwild_vkf<kV, kK, false>(a, coherence, blocks, stream);
 }
 
+template <int kV, int kK, int kTile, bool kFull, bool kTrack>
+hipError_t launch_tiled_vktt(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
+    if (coherence == kAgent)
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    else if (coherence == kMixed)
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile, kFull, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    return hipGetLastError();
+}
+
 template <int kV, int kK, int kTile, bool kFull>
 hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
-    if (coherence == kAgent)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAgent, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    else if (coherence == kMixed)
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kMixed, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    else
-        hipLaunchKernelGGL((k_train_tiled<kV, kK, kAtomicAgent, kTile, kFull>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    return hipGetLastError();
+    return a.loss_slots ? launch_tiled_vktt<kV, kK, kTile, kFull, true>(a, coherence, blocks, stream)
+                        : launch_tiled_vktt<kV, kK, kTile, kFull, false>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -1074,10 +1113,14 @@ template <int kV, int kK>
 hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
     const uint32_t blocks = (a.count + (kBlock / kWave) - 1) / (kBlock / kWave);
-    if (a.dim == (uint32_t)(kWave * kV))
-        hipLaunchKernelGGL((k_train_batch<kV, kK, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    else
-        hipLaunchKernelGGL((k_train_batch<kV, kK, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    const bool full = a.dim == (uint32_t)(kWave * kV);
+    if (a.loss_slots) {
+        if (full) hipLaunchKernelGGL((k_train_batch<kV, kK, true, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        else hipLaunchKernelGGL((k_train_batch<kV, kK, false, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    } else {
+        if (full) hipLaunchKernelGGL((k_train_batch<kV, kK, true, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
+        else hipLaunchKernelGGL((k_train_batch<kV, kK, false, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    }
     return hipGetLastError();
 }
 

@@ -39,12 +39,13 @@ def test_every_declared_entry_point_is_exported(gv):
 
 
 def test_config_struct_layout_matches_header(gv):
-    # the header's field order and natural alignment give a 72-byte struct
-    assert ctypes.sizeof(gv.binding.gv_config) == 72
+    # the header's field order and natural alignment give an 80-byte struct (76 bytes of fields)
+    assert ctypes.sizeof(gv.binding.gv_config) == 80
     assert gv.binding.gv_config.total_samples.offset == 24
     assert gv.binding.gv_config.device.offset == 48
     assert gv.binding.gv_config.pool_slots.offset == 64 and gv.binding.gv_config.partitions.offset == 68
-    assert ctypes.sizeof(gv.binding.gv_stats) == 80
+    assert gv.binding.gv_config.track_loss.offset == 72
+    assert ctypes.sizeof(gv.binding.gv_stats) == 96 and gv.binding.gv_stats.train_loss_sum.offset == 80
     # constants of the header and of the binding agree
     text = open(os.path.join(ROOT, "include", "gvhot.h")).read()
     assert float(re.search(r"#define GV_NEG_WEIGHT_DEFAULT \((-?[0-9.]+)f\)", text).group(1)) == gv.GV_NEG_WEIGHT_DEFAULT
