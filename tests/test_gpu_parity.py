@@ -1667,7 +1667,7 @@ def test_long_run_at_full_size_tracks_the_sequential_oracle(gv, name, policy):
 
 
 def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
-    """Configuration 4 as BASELINE states it: planted partition, 4*10^6 nodes in 400 communities, 4*10^7
+    """Configuration 4 at its stated size: planted partition, 4*10^6 nodes in 400 communities, 4*10^7
     edges, 1 % held out, d = 128, K = 1, 4*10^9 samples (238 pools of 2^24, learning rate decaying to zero);
     pools written in HBM by the device producer, default asynchronous policy.  The oracle's trajectory is
     stored (`tests/golden/long_run_c4.txt`, one CPU core for two hours); the evaluation loss must be within
