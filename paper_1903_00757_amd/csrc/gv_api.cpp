@@ -759,16 +759,17 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         // Hot ranks: the 65535 nodes of highest degree in falling order (ties by id); the rest share
         // the value 0xFFFF.  The tiled kernel keeps the row of lowest rank of a sample in registers.
         // A row is warm when, with kInFlight samples being processed at once (the order of magnitude of
-        // a full launch: several thousand waves, a few samples each), the expected number
+        // a full launch: 2048 waves at a time, each with the samples of one batch), the expected number
         // of other in-flight samples naming the same row (as a walk endpoint, share deg/sum(deg),
-        // or as a negative, share q/sum(q)) exceeds kWarmThreshold: the mixed policy then updates it with
+        // or as one of the K negatives, share q/sum(q) each) exceeds kWarmThreshold: the mixed policy then updates it with
         // atomic adds.  Colder rows are updated with plain device-scope stores, which can drop an
         // update only when two of the few samples naming such a row are in flight together.  The
         // share grows with the degree, so the warm rows are the first warm_ranks of the ranking.
         // Under the orthogonal-block schedule the samples in flight all come from one block, where a
         // row's share is `partitions` times its share of the pool.
         const uint32_t B = ctx->cfg.partitions;
-        const double kInFlight = 8192.0 * (B > 0 ? (double)B : 1.0), kWarmThreshold = 0.1;
+        const double kInFlight = 2048.0 * gv::samples_per_batch(ctx->cfg.dim, ctx->cfg.num_neg) * (B > 0 ? (double)B : 1.0),
+                     kWarmThreshold = 0.1;
         const uint32_t kRanked = 0xFFFFu;
         auto hotter = [&](uint32_t x, uint32_t y) {
             const double dx = degree_of(x), dy = degree_of(y);
@@ -788,7 +789,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
             const uint32_t i = order[r];
             rank[i] = (uint16_t)r;
             ranked_bits[i >> 5] |= 1u << (i & 31u);
-            const double share = (degree_sum > 0.0 ? degree_of(i) / degree_sum : 0.0) + q[i] / sum;
+            const double share = (degree_sum > 0.0 ? degree_of(i) / degree_sum : 0.0) + (double)ctx->cfg.num_neg * q[i] / sum;
             if (share * kInFlight > kWarmThreshold) warm_ranks = r + 1;
         }
         std::vector<uint4> table(n);

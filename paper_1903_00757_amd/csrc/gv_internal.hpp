@@ -84,5 +84,7 @@ struct AugmentArgs {
 hipError_t launch_augment(const AugmentArgs &a, hipStream_t stream);
 
 bool supported_shape(uint32_t dim, uint32_t num_neg);
+// samples whose rows one wave of the tiled kernel gathers together (4, or fewer where rows are long)
+uint32_t samples_per_batch(uint32_t dim, uint32_t num_neg);
 
 }  // namespace gv

@@ -419,6 +419,9 @@ __device__ __forceinline__ void sort_tile(uint32_t *word) {
     }
 }
 
+// samples whose gathers a wave of the tiled kernel has in flight together (V floats of a row per lane, K negatives)
+__host__ __device__ constexpr int tiled_batch(int V, int K) { return V * (K + 1) <= 4 ? 4 : (V * (K + 1) <= 12 ? 2 : 1); }
+
 // bit of the pair of context rows j1 < j2 (rows 1 .. K + 1 of a sample) in a sample's `same` word
 __host__ __device__ constexpr int pair_bit(int j1, int j2) { return (j1 - 1) * 6 + (j2 - 1); }
 
@@ -439,7 +442,7 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
     constexpr uint32_t kPerWave = kTile / (kBlock / kWave);
     static_assert(kPerWave % kWave == 0, "a wave walks whole 64-sample chunks");
     // samples whose gathers are in flight together: bounded by the registers their rows take
-    constexpr int kBatch = kV * (kK + 1) <= 4 ? 4 : (kV * (kK + 1) <= 12 ? 2 : 1);
+    constexpr int kBatch = tiled_batch(kV, kK);
     // A held row trades with memory every four samples where four samples are gathered at once, every two
     // where rows are so long that one or two samples fill the registers: there an exchange is a small part of
     // a sample's traffic, and the shorter interval halves how far the run's scores lag behind the other
@@ -1125,6 +1128,11 @@ hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
 }
 
 }  // namespace
+
+uint32_t samples_per_batch(uint32_t dim, uint32_t num_neg) {
+    const int V = dim <= 64 ? 1 : (dim <= 128 ? 2 : (dim <= 256 ? 4 : 8));  // as GV_DISPATCH below
+    return (uint32_t)tiled_batch(V, (int)num_neg);
+}
 
 bool supported_shape(uint32_t dim, uint32_t num_neg) {
     return dim >= 32 && dim <= 512 && dim % 32 == 0 && num_neg >= 1 && num_neg <= 5;
