@@ -82,62 +82,105 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
     // the walks): a row that is empty, runs backwards or past the end, or an entry >= n stops the
     // walk's worker and the call reports GV_EINVAL.
     std::atomic<bool> broken{false};
+    // A worker advances kGroup walks together, step by step: every step of a walk waits for the memory
+    // access of the step before it, and the chains of different walks overlap.
+    constexpr uint32_t kGroup = 16;
     std::vector<std::vector<uint32_t>> paths(workers);
-    for (auto &path : paths) path.resize((size_t)L + 1);
+    for (auto &path : paths) path.resize((size_t)kGroup * (L + 1));
     auto work = [&](uint32_t worker) {
-        std::vector<uint32_t> &path = paths[worker];
+        uint32_t *const path = paths[worker].data();  // walk k of the group: path[k * (L + 1) + t]
         const uint64_t lo = walks * worker / workers, hi = walks * (worker + 1) / workers;
-        for (uint64_t w = lo; w < hi; ++w) {
-            const Words r0 = philox(seed, first_walk + w, 0, kWalkStream);
+        for (uint64_t w0 = lo; w0 < hi; w0 += kGroup) {
+            const uint32_t group = (uint32_t)std::min<uint64_t>(kGroup, hi - w0);
             if (tables) {
-                // weighted graph: alias draw over the nodes, weights = weighted degrees
-                const uint64_t j = pick(r0, n);
-                path[0] = r0.w[2] < tables->node_thresh[j] ? (uint32_t)j : tables->node_alias[j];
-                if (path[0] >= n) {
-                    broken.store(true, std::memory_order_relaxed);
-                    return;
-                }
-            } else {
-                // departure: owner of a uniformly chosen half-edge = probability proportional to degree
-                const uint64_t e = pick(r0, half_edges);
-                const uint64_t *owner = std::upper_bound(host_offsets, host_offsets + n + 1, e) - 1;
-                if (owner < host_offsets || owner >= host_offsets + n) {  // offsets not ascending from 0
-                    broken.store(true, std::memory_order_relaxed);
-                    return;
-                }
-                path[0] = (uint32_t)(owner - host_offsets);
-            }
-            for (uint32_t t = 1; t <= L; ++t) {
-                const uint32_t x = path[t - 1];
-                const uint64_t begin = host_offsets[x], end = host_offsets[x + 1];
-                if (end <= begin || end > half_edges) {
-                    broken.store(true, std::memory_order_relaxed);
-                    return;
-                }
-                const Words r = philox(seed, first_walk + w, t, kWalkStream);
-                uint64_t at = pick(r, end - begin);
-                if (tables && !(r.w[2] < tables->nbr_thresh[begin + at])) {  // weighted step: the entry or its alias
-                    at = tables->nbr_alias[begin + at];
-                    if (at >= end - begin) {
+                for (uint32_t k = 0; k < group; ++k) {
+                    // weighted graph: alias draw over the nodes, weights = weighted degrees
+                    const Words r0 = philox(seed, first_walk + w0 + k, 0, kWalkStream);
+                    const uint64_t j = pick(r0, n);
+                    const uint32_t start = r0.w[2] < tables->node_thresh[j] ? (uint32_t)j : tables->node_alias[j];
+                    if (start >= n) {
                         broken.store(true, std::memory_order_relaxed);
                         return;
                     }
+                    path[(size_t)k * (L + 1)] = start;
                 }
-                const uint32_t next = host_adj[begin + at];
-                if (next >= n) {
-                    broken.store(true, std::memory_order_relaxed);
-                    return;
+            } else {
+                // departure: owner of a uniformly chosen half-edge = probability proportional to degree; the
+                // last node x with offsets[x] <= e, found by the group's binary searches side by side
+                uint64_t e[kGroup];
+                uint32_t first[kGroup], length[kGroup];  // the answer lies in first .. first + length - 1
+                for (uint32_t k = 0; k < group; ++k) {
+                    e[k] = pick(philox(seed, first_walk + w0 + k, 0, kWalkStream), half_edges);
+                    first[k] = 0;
+                    length[k] = n;
                 }
-                path[t] = next;
+                for (uint32_t span = n; span > 1; span -= span / 2)  // the longest search decides the number of turns
+                    for (uint32_t k = 0; k < group; ++k) {
+                        const uint32_t half = length[k] / 2;
+                        const bool right = half > 0 && host_offsets[first[k] + half] <= e[k];
+                        first[k] += right ? half : 0u;
+                        length[k] = half == 0 ? length[k] : (right ? length[k] - half : half);
+                    }
+                for (uint32_t k = 0; k < group; ++k) {
+                    if (!(host_offsets[first[k]] <= e[k] && e[k] < host_offsets[first[k] + 1])) {  // offsets not ascending
+                        broken.store(true, std::memory_order_relaxed);
+                        return;
+                    }
+                    path[(size_t)k * (L + 1)] = first[k];
+                }
             }
-            uint64_t t_global = w * per_walk;
-            for (uint32_t i = 0; i <= L; ++i)
-                for (uint32_t j = i + 1; j <= L && j - i <= s; ++j, ++t_global) {
-                    if (t_global >= count) return;
-                    const uint64_t at = shuffle == GV_SHUFFLE_PSEUDO ? block_start[t_global % s] + t_global / s : t_global;
-                    host_pairs[2 * at] = path[i];
-                    host_pairs[2 * at + 1] = path[j];
+            for (uint32_t t = 1; t <= L; ++t) {
+                // three passes over the group, so that its row bounds, and then its neighbours, are all
+                // requested from memory before the first of them is needed
+                uint64_t begin[kGroup], degree[kGroup], at[kGroup];
+                for (uint32_t k = 0; k < group; ++k) {
+                    const uint32_t x = path[(size_t)k * (L + 1) + t - 1];
+                    begin[k] = host_offsets[x];
+                    degree[k] = host_offsets[x + 1] - begin[k];
                 }
+                for (uint32_t k = 0; k < group; ++k) {
+                    if (degree[k] == 0 || begin[k] + degree[k] > half_edges || begin[k] + degree[k] < begin[k]) {
+                        broken.store(true, std::memory_order_relaxed);
+                        return;
+                    }
+                    const Words r = philox(seed, first_walk + w0 + k, t, kWalkStream);
+                    at[k] = pick(r, degree[k]);
+                    if (tables && !(r.w[2] < tables->nbr_thresh[begin[k] + at[k]])) {  // weighted step: the entry or its alias
+                        at[k] = tables->nbr_alias[begin[k] + at[k]];
+                        if (at[k] >= degree[k]) {
+                            broken.store(true, std::memory_order_relaxed);
+                            return;
+                        }
+                    }
+                    __builtin_prefetch(host_adj + begin[k] + at[k]);
+                }
+                for (uint32_t k = 0; k < group; ++k) {
+                    const uint32_t next = host_adj[begin[k] + at[k]];
+                    if (next >= n) {
+                        broken.store(true, std::memory_order_relaxed);
+                        return;
+                    }
+                    path[(size_t)k * (L + 1) + t] = next;
+                    __builtin_prefetch(host_offsets + next);
+                }
+            }
+            for (uint32_t k = 0; k < group; ++k) {
+                const uint32_t *const mine = path + (size_t)k * (L + 1);
+                uint64_t t_global = (w0 + k) * per_walk;
+                // sample t goes to block t mod s at offset t / s: both kept up to date by counting
+                uint64_t block = t_global % s, offset = t_global / s;
+                for (uint32_t i = 0; i <= L; ++i)
+                    for (uint32_t j = i + 1; j <= L && j - i <= s; ++j, ++t_global) {
+                        if (t_global >= count) return;
+                        const uint64_t at = shuffle == GV_SHUFFLE_PSEUDO ? block_start[block] + offset : t_global;
+                        host_pairs[2 * at] = mine[i];
+                        host_pairs[2 * at + 1] = mine[j];
+                        if (++block == s) {
+                            block = 0;
+                            ++offset;
+                        }
+                    }
+            }
         }
     };
     if (workers == 1) {
