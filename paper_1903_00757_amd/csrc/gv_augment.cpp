@@ -84,7 +84,7 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
     std::atomic<bool> broken{false};
     // A worker advances kGroup walks together, step by step: every step of a walk waits for the memory
     // access of the step before it, and the chains of different walks overlap.
-    constexpr uint32_t kGroup = 16;
+    constexpr uint32_t kGroup = 32;
     std::vector<std::vector<uint32_t>> paths(workers);
     for (auto &path : paths) path.resize((size_t)kGroup * (L + 1));
     auto work = [&](uint32_t worker) {
