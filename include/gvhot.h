@@ -266,7 +266,7 @@ int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_ad
                uint32_t threads, uint32_t *host_pairs, uint64_t *walks_used);
 
 /* The same producer on the device (Sec. 3.1, Alg. 2; the paper runs it on the host CPUs: a
- * host with few cores per GPU cannot feed this trainer, see gv_augment).
+ * host with few cores per GPU cannot feed this trainer once the adjacency leaves its caches).
  * gv_set_adjacency uploads the CSR adjacency of the graph given to gv_set_graph /
  * gv_set_degrees: host_offsets[n + 1] (offsets[0] = 0, row i has degree(i) entries),
  * host_adj[offsets[n]] with both directions of every edge; both are copied, the caller keeps
