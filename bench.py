@@ -295,7 +295,7 @@ def main():
             wall_o = time.perf_counter() - t0
             online["host_producer"] = {"value": steps * P / wall_o, "unit": "positive samples/s", "steps": steps,
                                        "host_threads": threads, "producer_alone": P / produce_s,
-                                       "note": "pools generated on the fly by gv_augment into the pinned slots; host-bound"}
+                                       "note": "pools generated on the fly by gv_augment into the pinned slots while the GPU trains the others"}
             log(f"online, host producer: {online['host_producer']['value']:.4g} samples/s end to end, producer alone "
                 f"{P / produce_s:.4g} samples/s on {threads} threads")
             # The same pipeline with the producer on the device (gv_augment_device): pool k+1 is written
