@@ -14,7 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgvhot.so")
-SOURCES = ["gv_kernels.hip", "gv_api.cpp", "gv_augment.cpp"]
+# (source, extra flags, object): the kernels are compiled twice, side by side (see the head of gv_kernels.hip)
+SOURCES = [("gv_kernels.hip", [], "gv_kernels.o"), ("gv_kernels.hip", ["-DGV_TRACK_LOSS=1"], "gv_kernels_tracked.o"),
+           ("gv_api.cpp", [], "gv_api.o"), ("gv_augment.cpp", [], "gv_augment.o")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Wall", "-Wextra", "-Wno-unused-parameter",
           # packed-fp32 instructions are kept out of the generated code on purpose
@@ -29,9 +31,9 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, out_dir: str = 
     os.makedirs(out_dir, exist_ok=True)
     objects = []
     procs = []
-    for src in SOURCES:
-        obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
-        cmd = [HIPCC, *COMMON, "-I", csrc, *extra_flags, "-c", os.path.join(csrc, src), "-o", obj]
+    for src, flags, name in SOURCES:
+        obj = os.path.join(out_dir, name)
+        cmd = [HIPCC, *COMMON, "-I", csrc, *extra_flags, *flags, "-c", os.path.join(csrc, src), "-o", obj]
         if src == "gv_api.cpp":  # uses the HIP vector types in its interface to the kernels
             cmd.insert(1, "-x")
             cmd.insert(2, "hip")

@@ -378,9 +378,11 @@ int train_hogwild(gv_ctx *ctx, const uint32_t *dev_pairs, uint64_t count, uint32
     }
     if (tiled) {
         a.records = fixed_records ? fixed_records : ctx->records;
-        GV_HIP(ctx, gv::launch_train_tiled(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
+        GV_HIP(ctx, (a.loss_slots ? gv::launch_train_tiled_tracked : gv::launch_train_tiled)(
+                        a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
     } else {
-        GV_HIP(ctx, gv::launch_train_hogwild(a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
+        GV_HIP(ctx, (a.loss_slots ? gv::launch_train_hogwild_tracked : gv::launch_train_hogwild)(
+                        a, ctx->cfg.dim, ctx->cfg.num_neg, coherence, ctx->compute));
     }
     ctx->stats.train_launches += 1;
     ctx->stats.tiled_launches += tiled ? 1 : 0;
@@ -451,7 +453,7 @@ int train_deterministic(gv_ctx *ctx, const uint32_t *dev_pairs, const uint32_t *
         const uint64_t lo = starts[b], hi = starts[b + 1];
         gv::TrainArgs a = train_args(ctx, dev_pairs + 2 * lo, ctx->next_g + lo, (uint32_t)(hi - lo));
         a.negatives = ctx->negatives + lo * K;
-        GV_HIP(ctx, gv::launch_train_batch(a, ctx->cfg.dim, K, ctx->compute));
+        GV_HIP(ctx, (a.loss_slots ? gv::launch_train_batch_tracked : gv::launch_train_batch)(a, ctx->cfg.dim, K, ctx->compute));
     }
     ctx->stats.train_launches += starts.size() - 1;
     ctx->stats.batches += starts.size() - 1;

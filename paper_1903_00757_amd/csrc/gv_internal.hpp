@@ -52,6 +52,13 @@ hipError_t launch_train_tiled(const TrainArgs &a, uint32_t dim, uint32_t num_neg
 // One wave per sample over samples [0, a.count): the caller guarantees that no
 // two of them share a vertex row or a context row (negatives included).
 hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);
+// The same three launches with kernels that also sum the running loss into a.loss_slots (which must be set for
+// these and null for the ones above).
+hipError_t launch_train_hogwild_tracked(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                        hipStream_t stream);
+hipError_t launch_train_tiled_tracked(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                      hipStream_t stream);
+hipError_t launch_train_batch_tracked(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream);
 // out[i*K + k] = negative k of positive sample first_g + i.
 hipError_t launch_draw_negatives(const uint4 *alias, uint32_t n, uint64_t seed, uint64_t first_g, uint64_t count,
                                  uint32_t num_neg, uint32_t *out, hipStream_t stream);

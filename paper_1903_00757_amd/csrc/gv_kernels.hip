@@ -5,7 +5,19 @@
 // gather or scatter is one fully coalesced request per 64 x 16 B, the dot product
 // is a per-lane partial followed by a cross-lane (DPP) reduction, and all node ids
 // and coefficients of the sample are wave-uniform scalars.
+//
+// The file is compiled twice, side by side: plainly, and with GV_TRACK_LOSS=1 into a second object that holds
+// nothing but the training kernels that also sum the running loss, under names ending in _tracked.
 #include "gv_internal.hpp"
+
+#ifndef GV_TRACK_LOSS
+#define GV_TRACK_LOSS 0
+#endif
+#if GV_TRACK_LOSS
+#define GV_TRAIN_NAME(name) name##_tracked
+#else
+#define GV_TRAIN_NAME(name) name
+#endif
 
 namespace gv {
 namespace {
@@ -831,6 +843,7 @@ __global__ __launch_bounds__(kBlock) void k_train_batch(TrainArgs a) {
     if constexpr (kTrack) hand_over_loss(a.loss_slots, loss, lane);
 }
 
+#if !GV_TRACK_LOSS
 // ---------------------------------------------------------------------------
 // Evaluation (no training runs meanwhile, so plain cached loads are fine).
 //
@@ -1033,6 +1046,8 @@ __global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
     }
 }
 
+#endif  // !GV_TRACK_LOSS
+
 // Persistent-style grid: enough workgroups to fill all 256 CUs at full occupancy; each
 // wave strides over the chunks.  The number of samples in flight is also kept below
 // |V|/32: every in-flight sample works on values that miss the updates of the others
@@ -1065,11 +1080,12 @@ hipError_t launch_hogwild_vkft(const TrainArgs &a, uint32_t coherence, uint32_t 
     return hipGetLastError();
 }
 
-// the kernels that also sum the running loss are separate instantiations: the ones that do not carry none of it
+// the kernels that also sum the running loss are separate instantiations (in an object of their own): the ones
+// that do not carry none of it
 template <int kV, int kK, bool kFull>
 hipError_t launch_hogwild_vkf(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
-    return a.loss_slots ? launch_hogwild_vkft<kV, kK, kFull, true>(a, coherence, blocks, stream)
-                        : launch_hogwild_vkft<kV, kK, kFull, false>(a, coherence, blocks, stream);
+    if ((a.loss_slots != nullptr) != (GV_TRACK_LOSS != 0)) return hipErrorInvalidValue;
+    return launch_hogwild_vkft<kV, kK, kFull, GV_TRACK_LOSS != 0>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -1093,8 +1109,8 @@ hipError_t launch_tiled_vktt(const TrainArgs &a, uint32_t coherence, uint32_t bl
 
 template <int kV, int kK, int kTile, bool kFull>
 hipError_t launch_tiled_vkt(const TrainArgs &a, uint32_t coherence, uint32_t blocks, hipStream_t stream) {
-    return a.loss_slots ? launch_tiled_vktt<kV, kK, kTile, kFull, true>(a, coherence, blocks, stream)
-                        : launch_tiled_vktt<kV, kK, kTile, kFull, false>(a, coherence, blocks, stream);
+    if ((a.loss_slots != nullptr) != (GV_TRACK_LOSS != 0)) return hipErrorInvalidValue;
+    return launch_tiled_vktt<kV, kK, kTile, kFull, GV_TRACK_LOSS != 0>(a, coherence, blocks, stream);
 }
 
 template <int kV, int kK>
@@ -1116,19 +1132,18 @@ template <int kV, int kK>
 hipError_t launch_batch_vk(const TrainArgs &a, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
     const uint32_t blocks = (a.count + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const bool full = a.dim == (uint32_t)(kWave * kV);
-    if (a.loss_slots) {
-        if (full) hipLaunchKernelGGL((k_train_batch<kV, kK, true, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
-        else hipLaunchKernelGGL((k_train_batch<kV, kK, false, true>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    } else {
-        if (full) hipLaunchKernelGGL((k_train_batch<kV, kK, true, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
-        else hipLaunchKernelGGL((k_train_batch<kV, kK, false, false>), dim3(blocks), dim3(kBlock), 0, stream, a);
-    }
+    if ((a.loss_slots != nullptr) != (GV_TRACK_LOSS != 0)) return hipErrorInvalidValue;
+    constexpr bool kTrack = GV_TRACK_LOSS != 0;
+    if (a.dim == (uint32_t)(kWave * kV))
+        hipLaunchKernelGGL((k_train_batch<kV, kK, true, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_train_batch<kV, kK, false, kTrack>), dim3(blocks), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
+#if !GV_TRACK_LOSS
 uint32_t samples_per_batch(uint32_t dim, uint32_t num_neg) {
     const int V = dim <= 64 ? 1 : (dim <= 128 ? 2 : (dim <= 256 ? 4 : 8));  // as GV_DISPATCH below
     return (uint32_t)tiled_batch(V, (int)num_neg);
@@ -1137,6 +1152,7 @@ uint32_t samples_per_batch(uint32_t dim, uint32_t num_neg) {
 bool supported_shape(uint32_t dim, uint32_t num_neg) {
     return dim >= 32 && dim <= 512 && dim % 32 == 0 && num_neg >= 1 && num_neg <= 5;
 }
+#endif  // !GV_TRACK_LOSS
 
 #define GV_DISPATCH_K(V, CALL)                 \
     switch (num_neg) {                         \
@@ -1155,26 +1171,27 @@ bool supported_shape(uint32_t dim, uint32_t num_neg) {
     if (dim <= 256) { GV_DISPATCH_K(4, CALL) }                              \
     GV_DISPATCH_K(8, CALL)
 
-hipError_t launch_train_hogwild(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
-                                hipStream_t stream) {
+hipError_t GV_TRAIN_NAME(launch_train_hogwild)(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                               hipStream_t stream) {
 #define GV_CALL(V, K) launch_hogwild_vk<V, K>(a, coherence, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }
 
-hipError_t launch_train_tiled(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
-                              hipStream_t stream) {
+hipError_t GV_TRAIN_NAME(launch_train_tiled)(const TrainArgs &a, uint32_t dim, uint32_t num_neg, uint32_t coherence,
+                                             hipStream_t stream) {
 #define GV_CALL(V, K) launch_tiled_vk<V, K>(a, coherence, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }
 
-hipError_t launch_train_batch(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream) {
+hipError_t GV_TRAIN_NAME(launch_train_batch)(const TrainArgs &a, uint32_t dim, uint32_t num_neg, hipStream_t stream) {
 #define GV_CALL(V, K) launch_batch_vk<V, K>(a, stream)
     GV_DISPATCH(GV_CALL)
 #undef GV_CALL
 }
 
+#if !GV_TRACK_LOSS
 template <int kV, int kK>
 hipError_t launch_eval_vk(const TrainArgs &a, double *total, hipStream_t stream) {
     if (a.count == 0) return hipSuccess;
@@ -1246,5 +1263,7 @@ hipError_t launch_augment(const AugmentArgs &a, hipStream_t stream) {
     hipLaunchKernelGGL(k_augment, dim3((uint32_t)blocks), dim3(kWalkBlock), 0, stream, a);
     return hipGetLastError();
 }
+
+#endif  // !GV_TRACK_LOSS
 
 }  // namespace gv

@@ -53,16 +53,18 @@ def test_host_runtime_under_address_and_undefined_behaviour_sanitizers(tmp_path)
     common = [HIPCC, "-std=c++17", "-O1", "-g", "--offload-arch=gfx950", "-munsafe-fp-atomics", "-Xclang", "-target-feature",
               "-Xclang", "-packed-fp32-ops", *INCLUDES]
     objects = []
-    sources = [("gv_api.cpp", ["-x", "hip", *host_flags]), ("gv_augment.cpp", host_flags)]
-    # the kernels are only linked, never launched: the object of the regular build will do when it is up to date
-    built = os.path.join(ROOT, "paper_1903_00757_amd", "_build", "gv_kernels.o")
+    sources = [("gv_api.cpp", ["-x", "hip", *host_flags], "gv_api.o"), ("gv_augment.cpp", host_flags, "gv_augment.o")]
+    # the kernels (two objects, see the head of gv_kernels.hip) are only linked, never launched: the objects of the
+    # regular build will do when they are up to date
     kernel_sources = [os.path.join(CSRC, f) for f in ("gv_kernels.hip", "gv_internal.hpp")]
-    if os.path.exists(built) and all(os.path.getmtime(built) >= os.path.getmtime(f) for f in kernel_sources):
-        objects.append(built)
-    else:
-        sources.append(("gv_kernels.hip", []))
-    for src, flags in sources:
-        obj = str(tmp_path / (src + ".o"))
+    for name, flags in (("gv_kernels.o", []), ("gv_kernels_tracked.o", ["-DGV_TRACK_LOSS=1"])):
+        built = os.path.join(ROOT, "paper_1903_00757_amd", "_build", name)
+        if os.path.exists(built) and all(os.path.getmtime(built) >= os.path.getmtime(f) for f in kernel_sources):
+            objects.append(built)
+        else:
+            sources.append(("gv_kernels.hip", flags, name))
+    for src, flags, name in sources:
+        obj = str(tmp_path / name)
         subprocess.run([*common, *flags, "-c", os.path.join(CSRC, src), "-o", obj], check=True, capture_output=True, text=True)
         objects.append(obj)
     driver_obj = str(tmp_path / "driver.o")
