@@ -598,24 +598,31 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             // The row held when the chunk starts stands in for "the sample before sample 0".
             uint32_t clash = 0u;
             if constexpr (kCoherence != kAtomicAgent) {
-                auto from_before = [&](uint32_t x, int d) {  // x of the lane d places down
+                // x of the lane d places down.  Every lane must take part in every exchange (a lane that is
+                // switched off hands out nothing): the exchanges stand alone, selections follow them.
+                auto from_before = [&](uint32_t x, int d) {
                     return (uint32_t)__builtin_amdgcn_ds_bpermute((lane - d) * 4, (int)x);
                 };
                 // run[d]: this sample and the d before it all have the same stationary row
-                const uint32_t prev_id = lane >= 1 ? from_before(stationary_id, 1) : carried_id;
-                const uint32_t prev_is_vertex = lane >= 1 ? from_before(is_vertex, 1) : carried_is_vertex;
+                const uint32_t id_before = from_before(stationary_id, 1), is_vertex_before = from_before(is_vertex, 1);
+                const uint32_t prev_id = lane >= 1 ? id_before : carried_id;
+                const uint32_t prev_is_vertex = lane >= 1 ? is_vertex_before : carried_is_vertex;
                 const uint32_t same_as_before = prev_id == stationary_id && prev_is_vertex == is_vertex ? 1u : 0u;
                 uint32_t run[kBatch + 1];
                 run[0] = 1u;
+                run[1] = same_as_before;
 #pragma unroll
-                for (int d = 1; d <= kBatch; ++d)
-                    run[d] = run[d - 1] & (d == 1 ? same_as_before : (lane >= d - 1 ? from_before(same_as_before, d - 1) : 0u));
+                for (int d = 2; d <= kBatch; ++d) {
+                    const uint32_t same_there = from_before(same_as_before, d - 1);
+                    run[d] = run[d - 1] & (lane >= d - 1 ? same_there : 0u);
+                }
 #pragma unroll
                 for (int d = 1; d <= kBatch; ++d) {
                     // the stationary row of the sample d before (the carried row for the sample "before sample 0")
                     const bool real = lane >= d;
-                    const uint32_t their_stationary = real ? from_before(stationary_id, d) : (lane == d - 1 ? carried_id : kNoRow);
-                    const uint32_t their_is_vertex = real ? from_before(is_vertex, d) : carried_is_vertex;
+                    const uint32_t stationary_there = from_before(stationary_id, d), is_vertex_there = from_before(is_vertex, d);
+                    const uint32_t their_stationary = real ? stationary_there : (lane == d - 1 ? carried_id : kNoRow);
+                    const uint32_t their_is_vertex = real ? is_vertex_there : carried_is_vertex;
                     bool names_their_stationary = false;
 #pragma unroll
                     for (int j = 0; j < kRows; ++j)

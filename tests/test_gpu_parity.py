@@ -474,7 +474,9 @@ def test_single_samples_with_repeated_rows(gv, policy):
 
 @pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
 @pytest.mark.parametrize("shape", ["shared context", "shared vertex", "interleaved runs"])
-def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape):
+@pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5)])  # the wave gathers 4, 2, 1 samples at once
+@pytest.mark.parametrize("count", [2, 3, 4])
+def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape, d, K, count):
     """Four samples that end up next to each other in one wave and share a cold row (one that the store
     policies update with plain device-scope stores).  The wave gathers several samples at once, so a later one
     must not be gathered before the earlier ones' updates of the shared row are out: nothing that the wave
@@ -484,12 +486,18 @@ def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape):
       shared vertex     (R, v_i): vertex[R] is the row the wave keeps in registers through the run
       interleaved runs  (a, .), (b, .), (a, .), (b, .) with a and b in one sort group: the register copy of
                         vertex[a] is written back when b takes over, and must be re-read when a returns
-    Uniform degrees and ids beyond the ranked range: every row is cold and vertex[u] is the row kept."""
-    n, d, K, w, seed, T, count = 100_000, 128, 1, 5.0, 41, 1000, 4
+    Uniform degrees and ids beyond the ranked range: the rows of u and v are cold; the negatives are what the
+    sampler draws, and where one of them has a rank, its row is the one the wave keeps and the shared row is
+    fetched and written back per sample (with 2 or 3 samples the one naming the row held by the sample before it
+    sits in lane 1 or 2 of the wave, where the comparison with the lanes before it has the fewest partners)."""
+    if shape == "interleaved runs" and count != 4:
+        pytest.skip("the interleaved shape has four samples")
+    n, w, seed, T = 100_000, 5.0 / K, 41, 1000
     deg = np.ones(n, dtype=np.uint32)
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     rng = np.random.default_rng(7)
-    negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias)[:, 0]
+    negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias).reshape(-1)
+    assert np.unique(negs).size == negs.size
     free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), negs)
     if shape == "shared context":
         shared = [free[0]]
