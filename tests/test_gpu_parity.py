@@ -531,6 +531,42 @@ def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape, d, K, count):
         assert np.abs(got[r] - ref[r]).max() <= 1e-4 * step + 1e-7, (shape, policy, int(r))
 
 
+@pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
+@pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5)])
+@pytest.mark.parametrize("trial", [0, 1, 2, 3])
+def test_random_sharing_of_cold_vertex_rows_is_exact(gv, policy, d, K, trial):
+    """As many samples as a row has room for (below), their u drawn at random from five cold nodes, every context row
+    (v and the negatives) a multiple of a unit vector of its own: a sample then moves vertex[u] along its own
+    coordinates only, so the five vertex rows must come out as the sequential oracle leaves them, whatever the order,
+    and whichever rows the wave happens to keep, gather together, put off or write back in between (the negatives
+    are what the sampler draws: some have a rank and become the row that is kept, some do not)."""
+    n, w, T = 100_000, 5.0 / K, 1000
+    count = min(64, d // (K + 1))
+    deg = np.ones(n, dtype=np.uint32)
+    thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
+    rng = np.random.default_rng(trial)
+    for seed in range(100 + 50 * trial, 150 + 50 * trial):  # the first seed whose negatives are all different nodes
+        negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias).reshape(-1)
+        if np.unique(negs).size == negs.size:
+            break
+    assert np.unique(negs).size == negs.size
+    free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), negs)
+    shared, partners = free[:5], free[5:5 + count]
+    pool = np.stack([rng.choice(shared, size=count), partners], axis=1).astype(np.uint32)
+    vertex, context = random_embeddings(n, d, seed=trial)
+    for j, r in enumerate(np.concatenate([partners, negs])):
+        context[r] = 0.0
+        context[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
+    got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, T, seed, policy)
+    ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, T, seed)
+    for r in shared:
+        if not (pool[:, 0] == r).any():
+            continue
+        step = np.abs(ref_v[r] - vertex[r]).max()
+        assert step > 1e-4
+        assert np.abs(got_v[r] - ref_v[r]).max() <= 1e-4 * step + 1e-7, (int(r), policy)
+
+
 def test_schedule_is_chosen_from_the_graph(gv, tiny_graph):
     """GV_SCHEDULE_AUTO: a graph with rows that concurrent samples share is trained with the tiled schedule, one
     without (4*10^5 nodes of equal degree: each is named by 2 of 8192 samples in flight with probability 0.04) in
