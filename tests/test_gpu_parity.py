@@ -533,39 +533,56 @@ def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape, d, K, count):
 
 @pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
 @pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5)])
-@pytest.mark.parametrize("trial", [0, 1])
-@pytest.mark.parametrize("samples", [2, 3, 5, 9, 64])
-def test_random_sharing_of_cold_vertex_rows_is_exact(gv, policy, d, K, trial, samples):
-    """A few samples, or as many as a row has room for, their u drawn at random from five cold nodes, every context row
-    (v and the negatives) a multiple of a unit vector of its own: a sample then moves vertex[u] along its own
-    coordinates only, so the five vertex rows must come out as the sequential oracle leaves them, whatever the order,
-    and whichever rows the wave happens to keep, gather together, put off or write back in between (the negatives
-    are what the sampler draws: some have a rank and become the row that is kept, some do not)."""
+@pytest.mark.parametrize("samples,trial", [(2, 0), (3, 0), (9, 0), (64, 0), (64, 1)])
+@pytest.mark.parametrize("kind", ["cold vertex", "warm vertex", "cold context", "warm context"])
+def test_random_sharing_of_a_few_rows_is_exact(gv, policy, d, K, trial, samples, kind):
+    """A few samples, or as many as a row has room for, that share a few rows at random, built so that the result
+    does not depend on their order: the rows that multiply a shared row are multiples of unit vectors of their own,
+    so a sample moves the shared row along its own coordinates only.  The shared rows must then come out as the
+    sequential oracle leaves them, whichever rows the wave happens to keep, gather together, put off, trade with
+    memory or write back in between.
+      ... vertex    u drawn from the shared nodes, v different for every sample; v and the negatives are unit rows
+      ... context   v drawn from the shared nodes, u different for every sample and a unit row
+      cold ...      shared nodes without a rank (ids beyond the ranked range: updated with stores under the store
+                    policies)
+      warm ...      shared nodes among the hottest ranks (exact grouping, runs in registers, atomic updates)
+    The negatives are what the sampler draws: some have a rank and become the row that is kept, some do not.
+    (POOL_ORDER, AGENT) runs the samples of a wave one after the other and is exact as well."""
     n, w, T = 100_000, 5.0 / K, 1000
     count = min(samples, d // (K + 1))
     deg = np.ones(n, dtype=np.uint32)
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     rng = np.random.default_rng(trial + 7 * samples)
-    for seed in range(100 + 50 * trial + 1000 * samples, 150 + 50 * trial + 1000 * samples):  # the first seed whose negatives are all different nodes
+    for seed in range(100 + 50 * trial + 1000 * samples, 150 + 50 * trial + 1000 * samples):
         negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias).reshape(-1)
-        if np.unique(negs).size == negs.size:
+        if np.unique(negs).size == negs.size:  # the first seed whose negatives are all different nodes
             break
     assert np.unique(negs).size == negs.size
     free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), negs)
-    shared, partners = free[:5] if count > 9 else free[:2], free[5:5 + count]
-    pool = np.stack([rng.choice(shared, size=count), partners], axis=1).astype(np.uint32)
+    hot = np.setdiff1d(np.arange(100, 200, dtype=np.uint32), negs)
+    shared = (free if kind.startswith("cold") else hot)[:5 if count > 9 else 2]
+    singles = free[5:5 + count]
+    drawn = rng.choice(shared, size=count).astype(np.uint32)
     vertex, context = random_embeddings(n, d, seed=trial)
-    for j, r in enumerate(np.concatenate([partners, negs])):
-        context[r] = 0.0
-        context[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
+    if kind.endswith("vertex"):
+        pool = np.stack([drawn, singles], axis=1)
+        for j, r in enumerate(np.concatenate([singles, negs])):
+            context[r] = 0.0
+            context[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
+    else:
+        pool = np.stack([singles, drawn], axis=1)
+        for j, r in enumerate(singles):
+            vertex[r] = 0.0
+            vertex[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
     got_v, got_c = hogwild_run(gv, n, deg, d, K, w, [pool], vertex, context, T, seed, policy)
     ref_v, ref_c = run_oracle(deg, K, w, [pool], vertex, context, T, seed)
+    got, ref, start = (got_v, ref_v, vertex) if kind.endswith("vertex") else (got_c, ref_c, context)
     for r in shared:
-        if not (pool[:, 0] == r).any():
+        if not (drawn == r).any():
             continue
-        step = np.abs(ref_v[r] - vertex[r]).max()
+        step = np.abs(ref[r] - start[r]).max()
         assert step > 1e-4
-        assert np.abs(got_v[r] - ref_v[r]).max() <= 1e-4 * step + 1e-7, (int(r), policy)
+        assert np.abs(got[r] - ref[r]).max() <= 1e-4 * step + 1e-7, (int(r), policy)
 
 
 def test_schedule_is_chosen_from_the_graph(gv, tiny_graph):
