@@ -533,9 +533,9 @@ def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape, d, K, count):
 
 @pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
 @pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5)])
-@pytest.mark.parametrize("samples,trial", [(2, 0), (3, 0), (9, 0), (64, 0), (64, 1)])
+@pytest.mark.parametrize("samples,trial,filler", [(2, 0, 0), (3, 0, 0), (9, 0, 0), (64, 0, 0), (64, 1, 0), (64, 0, 300)])
 @pytest.mark.parametrize("kind", ["cold vertex", "warm vertex", "cold context", "warm context"])
-def test_random_sharing_of_a_few_rows_is_exact(gv, policy, d, K, trial, samples, kind):
+def test_random_sharing_of_a_few_rows_is_exact(gv, policy, d, K, trial, samples, filler, kind):
     """A few samples, or as many as a row has room for, that share a few rows at random, built so that the result
     does not depend on their order: the rows that multiply a shared row are multiples of unit vectors of their own,
     so a sample moves the shared row along its own coordinates only.  The shared rows must then come out as the
@@ -547,30 +547,42 @@ def test_random_sharing_of_a_few_rows_is_exact(gv, policy, d, K, trial, samples,
                     policies)
       warm ...      shared nodes among the hottest ranks (exact grouping, runs in registers, atomic updates)
     The negatives are what the sampler draws: some have a rank and become the row that is kept, some do not.
+    `filler` unrelated samples (rows of their own) are mixed into the pool, so that the tile sort spreads the
+    related ones over several 64-sample chunks of the wave.
     (POOL_ORDER, AGENT) runs the samples of a wave one after the other and is exact as well."""
+    if filler and policy[0] == POOL_ORDER:
+        pytest.skip("in pool order the chunks of a larger pool go to different waves, whose stores may race")
     n, w, T = 100_000, 5.0 / K, 1000
     count = min(samples, d // (K + 1))
+    filler = min(filler, 300 // K)
+    total = count + filler
     deg = np.ones(n, dtype=np.uint32)
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
     rng = np.random.default_rng(trial + 7 * samples)
-    for seed in range(100 + 50 * trial + 1000 * samples, 150 + 50 * trial + 1000 * samples):
-        negs = oracle.draw_negatives(seed, 0, count, K, thresh, alias).reshape(-1)
-        if np.unique(negs).size == negs.size:  # the first seed whose negatives are all different nodes
+    where = np.sort(rng.permutation(total)[:count]) if filler else np.arange(count)  # places of the related samples
+    related = np.zeros(total, dtype=bool)
+    related[where] = True
+    for seed in range(100 + 50 * trial + 1000 * samples, 300 + 50 * trial + 1000 * samples):
+        all_negs = oracle.draw_negatives(seed, 0, total, K, thresh, alias)
+        negs = all_negs[related].reshape(-1)
+        # the first seed with which the related samples draw different nodes and the filler draws none of them
+        if np.unique(negs).size == negs.size and not np.isin(all_negs[~related], negs).any():
             break
-    assert np.unique(negs).size == negs.size
-    free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), negs)
-    hot = np.setdiff1d(np.arange(100, 200, dtype=np.uint32), negs)
+    assert np.unique(negs).size == negs.size and not np.isin(all_negs[~related], negs).any()
+    free = np.setdiff1d(np.arange(70_000, 90_000, dtype=np.uint32), all_negs)
+    hot = np.setdiff1d(np.arange(100, 200, dtype=np.uint32), all_negs)
     shared = (free if kind.startswith("cold") else hot)[:5 if count > 9 else 2]
     singles = free[5:5 + count]
     drawn = rng.choice(shared, size=count).astype(np.uint32)
     vertex, context = random_embeddings(n, d, seed=trial)
+    pool = np.stack([free[1000:1000 + total], free[2000:2000 + total]], axis=1)  # the filler: rows nobody else names
     if kind.endswith("vertex"):
-        pool = np.stack([drawn, singles], axis=1)
+        pool[where] = np.stack([drawn, singles], axis=1)
         for j, r in enumerate(np.concatenate([singles, negs])):
             context[r] = 0.0
             context[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
     else:
-        pool = np.stack([singles, drawn], axis=1)
+        pool[where] = np.stack([singles, drawn], axis=1)
         for j, r in enumerate(singles):
             vertex[r] = 0.0
             vertex[r, j] = rng.uniform(0.5, 2.0) * (1 if j % 2 else -1)
