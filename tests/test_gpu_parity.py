@@ -532,7 +532,7 @@ def test_samples_of_one_wave_sharing_a_cold_row(gv, policy, shape, d, K, count):
 
 
 @pytest.mark.parametrize("policy", [(TILED, AGENT), (TILED, MIXED), (TILED, ATOMIC), (POOL_ORDER, AGENT)])
-@pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5)])
+@pytest.mark.parametrize("d,K", [(128, 1), (128, 3), (512, 5), (96, 2)])  # (96, 2): rows that do not fill their lanes
 @pytest.mark.parametrize("samples,trial,filler", [(2, 0, 0), (3, 0, 0), (9, 0, 0), (64, 0, 0), (64, 1, 0), (64, 0, 300)])
 @pytest.mark.parametrize("kind", ["cold vertex", "warm vertex", "cold context", "warm context"])
 def test_random_sharing_of_a_few_rows_is_exact(gv, policy, d, K, trial, samples, filler, kind):
