@@ -770,8 +770,10 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         // Under the orthogonal-block schedule the samples in flight all come from one block, where a
         // row's share is `partitions` times its share of the pool.
         const uint32_t B = ctx->cfg.partitions;
-        const double kInFlight = 2048.0 * gv::samples_per_batch(ctx->cfg.dim, ctx->cfg.num_neg) * (B > 0 ? (double)B : 1.0),
-                     kWarmThreshold = 0.1;
+        // Where rows are so long that a wave gathers fewer than four samples at once, a sample's rows stay between
+        // their load and their store for longer (it moves several times the bytes): half the threshold.
+        const uint32_t per_batch = gv::samples_per_batch(ctx->cfg.dim, ctx->cfg.num_neg);
+        const double kInFlight = 2048.0 * per_batch * (B > 0 ? (double)B : 1.0), kWarmThreshold = per_batch >= 4 ? 0.1 : 0.05;
         const uint32_t kRanked = 0xFFFFu;
         auto hotter = [&](uint32_t x, uint32_t y) {
             const double dx = degree_of(x), dy = degree_of(y);
