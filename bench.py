@@ -165,6 +165,9 @@ def main():
     ap.add_argument("--blocked-partitions", type=int, default=0,
                     help="also time the orthogonal-block schedule (Sec. 3.2) with this many partitions")
     ap.add_argument("--episode-pools", type=int, default=8, help="pools per episode of the orthogonal-block leg")
+    ap.add_argument("--weighted", action="store_true",
+                    help="put edge weights from {1/4, 1, 4, 9} on the graph (Sec. 4.3): weighted walks, negatives from "
+                         "the weighted degree")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -214,15 +217,31 @@ def main():
         offsets, adj = W.csr_from_edges(n, src, dst)
         edges = src.size
         log(f"graph {args.workload}: n={n} edges={edges} ({time.perf_counter() - t0:.1f} s)")
+    weights = tables = None
+    if args.weighted:
+        if adj is None or cfg["graph"] == "chung_lu_on_device":
+            sys.exit("bench.py: --weighted needs a graph whose edge list is in host memory (c2, c3, c4, tiny)")
+        weights = W.csr_edge_weights(src, dst, seed=12)
+        tables = gv.gv_build_walk_tables(offsets, weights)[1:]
+        args.no_cpu_baseline = True  # the CPU leg is the one of the unweighted graph
 
     ctx = gv.gv_create(dim=dim, num_neg=K, neg_weight=w, mode=gv.GV_MODE_HOGWILD, total_samples=total,
                        seed=W.configs.TRAIN_SEED, pool_capacity=P, coherence=args.coherence, schedule=args.schedule,
                        profile=1, pool_slots=RING)
     online = {}
     try:
-        gv.gv_set_degrees(ctx, deg)
+        if weights is not None:
+            gv.gv_set_weighted_graph(ctx, offsets, adj, weights)  # also uploads adjacency and walk tables
+        else:
+            gv.gv_set_degrees(ctx, deg)
         gv.gv_build_alias(ctx, 0.75)
         gv.gv_init_embeddings(ctx, 1)
+
+        def produce(out, seed, first_walk):  # one pool from the host producer of this graph
+            if tables is not None:
+                gv.gv_augment_weighted(offsets, adj, tables, seed=seed, first_walk=first_walk, count=P, threads=threads, out=out)
+            else:
+                gv.gv_augment(offsets, adj, seed=seed, first_walk=first_walk, count=P, threads=threads, out=out)
 
         # Fill the ring once: RING distinct pools, written by the producer straight into the pinned slots.
         t0 = time.perf_counter()
@@ -232,8 +251,7 @@ def main():
             if adj is None:
                 np.copyto(slot, W.marginal_pool(deg, P, seed=100 * cfg["number"] + r))
             else:
-                gv.gv_augment(offsets, adj, seed=100 * cfg["number"], first_walk=r * walks_per_pool, count=P,
-                              threads=threads, out=slot)
+                produce(slot, 100 * cfg["number"], r * walks_per_pool)
             dev_pools.append(torch.from_numpy(slot.view(np.int32)).cuda())
             gv.gv_push_pool(ctx, slot, P)
             gv.gv_train_pool(ctx)  # the first RING steps double as warm-up of the streamed path
@@ -280,7 +298,7 @@ def main():
             gv.gv_sync(ctx)
             t0 = time.perf_counter()
             slot = gv.gv_acquire_pool_slot(ctx, P)
-            gv.gv_augment(offsets, adj, seed=900, first_walk=first, count=P, threads=threads, out=slot)
+            produce(slot, 900, first)
             produce_s = time.perf_counter() - t0
             gv.gv_push_pool(ctx, slot, P)
             t0 = time.perf_counter()
@@ -288,8 +306,7 @@ def main():
                 gv.gv_train_pool(ctx)
                 if i + 1 < steps:
                     slot = gv.gv_acquire_pool_slot(ctx, P)
-                    gv.gv_augment(offsets, adj, seed=900, first_walk=first + (i + 1) * walks_per_pool, count=P,
-                                  threads=threads, out=slot)
+                    produce(slot, 900, first + (i + 1) * walks_per_pool)
                     gv.gv_push_pool(ctx, slot, P)
             gv.gv_sync(ctx)
             wall_o = time.perf_counter() - t0
@@ -300,7 +317,8 @@ def main():
                 f"{P / produce_s:.4g} samples/s on {threads} threads")
             # The same pipeline with the producer on the device (gv_augment_device): pool k+1 is written
             # into the buffer that pool k-1 was trained from; producer and trainer share one stream.
-            gv.gv_set_adjacency(ctx, offsets, adj)
+            if weights is None:
+                gv.gv_set_adjacency(ctx, offsets, adj)
             bufs = dev_pools[:2]
             t0 = time.perf_counter()
             for i in range(8):
@@ -398,7 +416,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": head["wall_s"] / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {cfg['graph']} n={n} edges={edges}, d={dim}, K={K}, "
-                               f"neg_weight={w}, pools of 2^{int(np.log2(P))} samples "
+                               f"neg_weight={w}, " + ("edge weights from {1/4, 1, 4, 9}, " if args.weighted else "")
+                               + f"pools of 2^{int(np.log2(P))} samples "
                                + (f"streamed from {RING} pinned pools (host -> device copy overlapped with training)"
                                   if streamed_is_headline else
                                   f"resident in HBM ({RING} distinct pools cycled; the streamed rate is {gap * 100:.1f} % lower, "

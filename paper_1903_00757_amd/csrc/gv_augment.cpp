@@ -130,14 +130,15 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
                 }
             }
             for (uint32_t t = 1; t <= L; ++t) {
-                // three passes over the group, so that its row bounds, and then its neighbours, are all
-                // requested from memory before the first of them is needed
+                // passes over the group, so that its row bounds, then (weighted graph) its table entries, then its
+                // neighbours, are all requested from memory before the first of them is needed
                 uint64_t begin[kGroup], degree[kGroup], at[kGroup];
                 for (uint32_t k = 0; k < group; ++k) {
                     const uint32_t x = path[(size_t)k * (L + 1) + t - 1];
                     begin[k] = host_offsets[x];
                     degree[k] = host_offsets[x + 1] - begin[k];
                 }
+                uint32_t word[kGroup];  // weighted step: the random word that decides between an entry and its alias
                 for (uint32_t k = 0; k < group; ++k) {
                     if (degree[k] == 0 || begin[k] + degree[k] > half_edges || begin[k] + degree[k] < begin[k]) {
                         broken.store(true, std::memory_order_relaxed);
@@ -145,15 +146,25 @@ static int augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *hos
                     }
                     const Words r = philox(seed, first_walk + w0 + k, t, kWalkStream);
                     at[k] = pick(r, degree[k]);
-                    if (tables && !(r.w[2] < tables->nbr_thresh[begin[k] + at[k]])) {  // weighted step: the entry or its alias
-                        at[k] = tables->nbr_alias[begin[k] + at[k]];
-                        if (at[k] >= degree[k]) {
-                            broken.store(true, std::memory_order_relaxed);
-                            return;
-                        }
+                    word[k] = r.w[2];
+                    if (tables) {
+                        __builtin_prefetch(tables->nbr_thresh + begin[k] + at[k]);
+                        __builtin_prefetch(tables->nbr_alias + begin[k] + at[k]);
+                    } else {
+                        __builtin_prefetch(host_adj + begin[k] + at[k]);
                     }
-                    __builtin_prefetch(host_adj + begin[k] + at[k]);
                 }
+                if (tables)
+                    for (uint32_t k = 0; k < group; ++k) {
+                        if (!(word[k] < tables->nbr_thresh[begin[k] + at[k]])) {  // weighted step: the entry or its alias
+                            at[k] = tables->nbr_alias[begin[k] + at[k]];
+                            if (at[k] >= degree[k]) {
+                                broken.store(true, std::memory_order_relaxed);
+                                return;
+                            }
+                        }
+                        __builtin_prefetch(host_adj + begin[k] + at[k]);
+                    }
                 for (uint32_t k = 0; k < group; ++k) {
                     const uint32_t next = host_adj[begin[k] + at[k]];
                     if (next >= n) {

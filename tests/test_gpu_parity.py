@@ -712,7 +712,7 @@ def c2_workload():
     offsets, adj = W.csr_from_edges(n, src, dst)
     pool = W.walk_pool(offsets, adj, 1 << 24, 40, 5, seed=202)
     thresh, alias = oracle.alias_build(oracle.degree_weights(deg))
-    return dict(n=n, deg=deg, pool=pool, thresh=thresh, alias=alias)
+    return dict(n=n, deg=deg, pool=pool, thresh=thresh, alias=alias, src=src, dst=dst, offsets=offsets, adj=adj)
 
 
 def test_full_size_tables_and_negatives(gv, c2_workload):
@@ -1450,6 +1450,39 @@ def test_weighted_graph_end_to_end(gv, tiny_graph):
         with pytest.raises(gv.GvError) as e:
             gv.gv_set_weighted_graph(ctx, offsets, adj, bad)
         assert e.value.code == gv.GV_EINVAL
+
+
+def test_weighted_graph_at_the_size_of_configuration_2(gv, c2_workload):
+    """The graph of configuration 2 with edge weights from {1/4, 1, 4, 9} (10^7 adjacency entries, one alias table
+    per row): negative-sampling table, negatives, and the pools of the device producer and of the host producer are
+    the oracle's bit for bit, also for walk numbers beyond 2^33."""
+    import torch
+
+    c2 = c2_workload
+    n, offsets, adj = c2["n"], c2["offsets"], c2["adj"]
+    weights = W.csr_edge_weights(c2["src"], c2["dst"], seed=12)
+    wdeg = oracle.weighted_degrees(offsets, weights)
+    thresh, alias = oracle.alias_build(oracle.weights_pow34(wdeg))
+    tables = oracle.walk_tables(offsets, weights)
+    count = 1 << 20
+    with context_for(gv, dim=128, num_neg=1, total_samples=1 << 30, seed=1234, pool_capacity=8) as ctx:
+        gv.gv_set_weighted_graph(ctx, offsets, adj, weights)
+        gv.gv_build_alias(ctx, 0.75)
+        got_t, got_a = gv.gv_get_alias(ctx, n)
+        assert np.array_equal(got_t, thresh) and np.array_equal(got_a, alias)
+        assert np.array_equal(gv.gv_draw_negatives(ctx, 2**35, 1 << 18, 1), oracle.draw_negatives(1234, 2**35, 1 << 18, 1, thresh, alias))
+        buf = torch.empty((count, 2), dtype=torch.int32, device="cuda")
+        for first_walk, size in ((0, count), (2**33 + 11, 190 * 1000 + 3)):
+            gv.gv_augment_device(ctx, buf.data_ptr(), seed=202, first_walk=first_walk, count=size)
+            gv.gv_sync(ctx)
+            ref, _ = oracle.augment_weighted(202, offsets, adj, tables, 40, 5, size, first_walk=first_walk)
+            ref = oracle.pseudo_shuffle(ref, 5)
+            assert np.array_equal(buf[:size].cpu().numpy().view(np.uint32), ref), first_walk
+            host, _ = gv.gv_augment_weighted(offsets, adj, tables, seed=202, first_walk=first_walk, count=size, threads=16)
+            assert np.array_equal(host, ref), first_walk
+    # heavier edges are walked more often: the share of steps along weight-9 edges is far above their share of the edges
+    plain, _ = oracle.augment(202, offsets, adj, 40, 5, 190 * 1000)
+    assert not np.array_equal(plain, oracle.augment_weighted(202, offsets, adj, tables, 40, 5, 190 * 1000)[0])
 
 
 # --------------------------------------------------------------------------- orthogonal blocks

@@ -12,6 +12,7 @@ from .graphs import (  # noqa: F401
     planted_partition,
     degrees,
     csr_from_edges,
+    csr_edge_weights,
     split_holdout,
     uniform_negative_pairs,
 )

@@ -37,6 +37,14 @@ def csr_from_edges(n: int, src: np.ndarray, dst: np.ndarray):
     return offsets, adj
 
 
+def csr_edge_weights(src: np.ndarray, dst: np.ndarray, seed: int, values=(0.25, 1.0, 4.0, 9.0)):
+    """One weight per undirected edge, drawn uniformly from ``values``, laid out like the adjacency of
+    ``csr_from_edges`` (both directions of an edge carry its weight): ``float32[2m]``."""
+    ew = _rng(seed).choice(np.asarray(values, dtype=np.float32), size=src.size).astype(np.float32)
+    order = np.argsort(np.concatenate([src, dst]).astype(np.uint32), kind="stable")
+    return np.ascontiguousarray(np.concatenate([ew, ew])[order])
+
+
 def _dedupe_in_draw_order(a: np.ndarray, b: np.ndarray, n: int):
     """Drop self-loops and repeated undirected pairs, keeping first draws."""
     keep = a != b
