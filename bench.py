@@ -293,7 +293,7 @@ def main():
         if not args.no_online:
             # Online pipeline (Sec. 3.3): the host producer (parallel online augmentation with pseudo shuffle,
             # Sec. 3.1) fills one pinned slot while the GPU trains the others.
-            steps = max(3, args.steps // 8)
+            steps = max(8, args.steps // 2)
             first = RING * walks_per_pool
             gv.gv_sync(ctx)
             t0 = time.perf_counter()
