@@ -9,8 +9,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+_config = None
+
+
 def pytest_configure(config):
+    global _config
+    _config = config
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_runtest_logfinish(nodeid, location):
+    """The progress mark of every finished test leaves the process at once, also when the output is a pipe or a
+    file (a long run then shows that it is alive)."""
+    reporter = _config.pluginmanager.get_plugin("terminalreporter") if _config else None
+    writer = getattr(reporter, "_tw", None)
+    for stream in (getattr(writer, "_file", None), sys.stdout, sys.stderr):
+        try:
+            if stream is not None:
+                stream.flush()
+        except (OSError, ValueError):
+            pass
 
 
 @pytest.fixture(scope="session")
