@@ -258,7 +258,9 @@ int gv_draw_negatives_partitioned(gv_ctx *ctx, uint64_t first_g, uint64_t count,
  * the number of walks consumed.  A node without neighbours must not be reachable
  * (degree-proportional departure never starts at one).  The adjacency is checked where the
  * walks touch it: an empty or ill-formed row, or an entry >= n, gives GV_EINVAL (the pool
- * is then incomplete); GV_ENOMEM / GV_EHIP when workers cannot be set up.              */
+ * is then incomplete); GV_ENOMEM / GV_EHIP when workers cannot be set up.  An adjacency of
+ * gigabytes is best kept on huge pages (madvise MADV_HUGEPAGE before it is filled): every
+ * step of a walk is a random access into it.                                             */
 enum { GV_SHUFFLE_NONE = 0, GV_SHUFFLE_PSEUDO = 1 };
 #define GV_MAX_WINDOW (1u << 20) /* largest augmentation distance `window` the producers accept */
 int gv_augment(uint32_t n, const uint64_t *host_offsets, const uint32_t *host_adj, uint64_t seed,

@@ -105,6 +105,27 @@ def chung_lu_csr(n: int, num_edges: int, gamma: float, seed: int, device="cuda",
     return offsets, adj
 
 
+def _empty_on_huge_pages(count: int, dtype) -> np.ndarray:
+    """Uninitialised host array whose pages the kernel is asked to back with huge pages (random access into
+    gigabytes of adjacency otherwise misses the TLB at every step); a plain array where that is not on offer."""
+    import ctypes
+
+    out = np.empty(count, dtype=dtype)
+    try:
+        page = 1 << 21
+        start = (out.ctypes.data + page - 1) & ~(page - 1)
+        length = (out.ctypes.data + out.nbytes - start) & ~(page - 1)
+        if length > 0:
+            ctypes.CDLL(None, use_errno=True).madvise(ctypes.c_void_p(start), ctypes.c_size_t(length), 14)  # MADV_HUGEPAGE
+    except (OSError, AttributeError):
+        pass
+    return out
+
+
 def to_host_csr(offsets: torch.Tensor, adj: torch.Tensor):
-    """numpy views ``(offsets uint64[n + 1], adj uint32[...])`` of a CSR built above, in host memory."""
-    return offsets.cpu().numpy().view(np.uint64), adj.cpu().numpy().view(np.uint32)
+    """numpy arrays ``(offsets uint64[n + 1], adj uint32[...])`` of a CSR built above, in host memory."""
+    host_offsets = _empty_on_huge_pages(offsets.numel(), np.int64)
+    host_adj = _empty_on_huge_pages(adj.numel(), np.int32)
+    torch.from_numpy(host_offsets).copy_(offsets)
+    torch.from_numpy(host_adj).copy_(adj)
+    return host_offsets.view(np.uint64), host_adj.view(np.uint32)
