@@ -999,56 +999,87 @@ __device__ __forceinline__ uint64_t pick_below(uint4 r, uint64_t range) {
     return __umul64hi(((uint64_t)r.x << 32) | r.y, range);
 }
 
+// The pool position of sample number t (generation order): t itself, or, pseudo-shuffled, block t mod s at
+// offset t / s (block b holds the samples b, b + s, b + 2s, ...: the blocks before it hold
+// ceil((count - b') / s) samples each, i.e. the first count mod s blocks hold one more).
+__device__ __forceinline__ uint64_t place_of(uint64_t t, uint32_t s, uint64_t count, bool pseudo_shuffle) {
+    if (!pseudo_shuffle) return t;
+    const uint64_t b = t % s, q = t / s, whole = count / s, extra = count % s;
+    return b * whole + (b < extra ? b : extra) + q;
+}
+
 __global__ __launch_bounds__(kWalkBlock) void k_augment(AugmentArgs a) {
-    __shared__ uint32_t s_path[kMaxWalkLength + 1][kWalkBlock];  // a walk's nodes, one column per thread
-    const uint64_t w = (uint64_t)blockIdx.x * kWalkBlock + threadIdx.x;
-    if (w >= a.walks) return;
+    // a walk's nodes, one row per thread (65 words: the rows start in different banks)
+    __shared__ uint32_t s_path[kWalkBlock][kMaxWalkLength + 1];
+    // the pairs of a walk in order: i << 8 | j of pair number t (i < j <= i + s, in order of i then j)
+    __shared__ uint16_t s_pair[(kMaxWalkLength + 1) * kMaxWalkLength / 2];
+    const uint64_t w0 = (uint64_t)blockIdx.x * kWalkBlock, w = w0 + threadIdx.x;
     const uint32_t L = a.length, s = a.window;
-    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
-    const uint64_t walk = a.first_walk + w;
-    uint32_t x;
-    const uint4 r0 = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), 0u, 4u, k0, k1);
-    if (a.node_table) {
-        // weighted graph (Sec. 4.3): departure by an alias draw over the nodes, weights = weighted degrees
-        const uint32_t j = (uint32_t)pick_below(r0, a.n);
-        const uint2 entry = a.node_table[j];
-        x = r0.z < entry.x ? j : entry.y;
-    } else {
-        // departure: last node whose first half-edge is at or before the chosen one
-        const uint64_t e = pick_below(r0, a.half_edges);
-        uint32_t lo = 0, hi = a.n;  // offsets[lo] <= e < offsets[hi]
-        while (hi - lo > 1) {
-            const uint32_t mid = lo + (hi - lo) / 2;
-            if (a.offsets[mid] <= e) lo = mid; else hi = mid;
-        }
-        x = lo;
+    for (uint32_t i = threadIdx.x; i < L; i += kWalkBlock) {
+        uint32_t start = 0;  // pairs of the nodes before i
+        for (uint32_t before = 0; before < i; ++before) start += min(s, L - before);
+        for (uint32_t j = i + 1; j <= L && j - i <= s; ++j) s_pair[start + (j - i - 1)] = (uint16_t)(i << 8 | j);
     }
-    s_path[0][threadIdx.x] = x;
-    for (uint32_t t = 1; t <= L; ++t) {
-        const uint64_t begin = a.offsets[x], degree = a.offsets[x + 1] - begin;
-        const uint4 r = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), t, 4u, k0, k1);
-        uint64_t at = pick_below(r, degree);
-        if (a.nbr_table) {  // weighted step: alias draw over the row's edge weights
-            const uint2 entry = a.nbr_table[begin + at];
-            at = r.z < entry.x ? at : entry.y;
-        }
-        x = a.adj[begin + at];
-        s_path[t][threadIdx.x] = x;
-    }
-    uint64_t t_global = w * a.per_walk;
-    for (uint32_t i = 0; i <= L; ++i) {
-        const uint32_t from = s_path[i][threadIdx.x];
-        for (uint32_t j = i + 1; j <= L && j - i <= s; ++j, ++t_global) {
-            if (t_global >= a.count) return;
-            uint64_t at = t_global;
-            if (a.pseudo_shuffle) {
-                const uint64_t b = t_global % s, q = t_global / s;
-                // block b holds the samples b, b + s, b + 2s, ...: blocks before it hold
-                // ceil((count - b') / s) samples each
-                const uint64_t whole = a.count / s, extra = a.count % s;  // the first `extra` blocks hold one more
-                at = b * whole + (b < extra ? b : extra) + q;
+    if (w < a.walks) {
+        const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+        const uint64_t walk = a.first_walk + w;
+        uint32_t x;
+        const uint4 r0 = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), 0u, 4u, k0, k1);
+        if (a.node_table) {
+            // weighted graph (Sec. 4.3): departure by an alias draw over the nodes, weights = weighted degrees
+            const uint32_t j = (uint32_t)pick_below(r0, a.n);
+            const uint2 entry = a.node_table[j];
+            x = r0.z < entry.x ? j : entry.y;
+        } else {
+            // departure: last node whose first half-edge is at or before the chosen one
+            const uint64_t e = pick_below(r0, a.half_edges);
+            uint32_t lo = 0, hi = a.n;  // offsets[lo] <= e < offsets[hi]
+            while (hi - lo > 1) {
+                const uint32_t mid = lo + (hi - lo) / 2;
+                if (a.offsets[mid] <= e) lo = mid; else hi = mid;
             }
-            a.pairs[at] = make_uint2(from, s_path[j][threadIdx.x]);
+            x = lo;
+        }
+        s_path[threadIdx.x][0] = x;
+        for (uint32_t t = 1; t <= L; ++t) {
+            const uint64_t begin = a.offsets[x], degree = a.offsets[x + 1] - begin;
+            const uint4 r = philox4x32_10((uint32_t)walk, (uint32_t)(walk >> 32), t, 4u, k0, k1);
+            uint64_t at = pick_below(r, degree);
+            if (a.nbr_table) {  // weighted step: alias draw over the row's edge weights
+                const uint2 entry = a.nbr_table[begin + at];
+                at = r.z < entry.x ? at : entry.y;
+            }
+            x = a.adj[begin + at];
+            s_path[threadIdx.x][t] = x;
+        }
+    }
+    __syncthreads();
+    // The workgroup's walks cover the samples t_lo .. t_hi - 1 of the pool; the workgroup writes them together, a
+    // thread per sample, in the order of their places in the pool, so that neighbouring threads write
+    // neighbouring pairs (one thread writing its own walk's 190 pairs scatters 8-byte stores over the pool).
+    const uint32_t here = (uint32_t)min((uint64_t)kWalkBlock, a.walks - w0);
+    const uint64_t t_lo = w0 * a.per_walk;
+    const uint64_t t_hi = min(t_lo + (uint64_t)here * a.per_walk, a.count);
+    if (t_lo >= t_hi) return;
+    const uint32_t per_walk = (uint32_t)a.per_walk, span = (uint32_t)(t_hi - t_lo);
+    auto emit = [&](uint32_t t_rel, uint64_t place) {  // sample t_lo + t_rel goes to pairs[place]
+        const uint32_t walk = t_rel / per_walk, pair = s_pair[t_rel % per_walk];
+        a.pairs[place] = make_uint2(s_path[walk][pair >> 8], s_path[walk][pair & 0xFFu]);
+    };
+    if (!a.pseudo_shuffle) {
+        for (uint32_t t_rel = threadIdx.x; t_rel < span; t_rel += kWalkBlock) emit(t_rel, t_lo + t_rel);
+    } else if (s > span) {
+        for (uint32_t t_rel = threadIdx.x; t_rel < span; t_rel += kWalkBlock)
+            emit(t_rel, place_of(t_lo + t_rel, s, a.count, true));
+    } else {
+        // block after block: within block b the workgroup's samples are b + q s for consecutive q
+        const uint64_t q_lo = t_lo / s, whole = a.count / s, extra = a.count % s;
+        const uint32_t steps = (uint32_t)((t_hi - 1) / s - q_lo) + 1u;
+        const uint32_t all = s * steps;  // s <= span here: at most span + 2 s < 2^20 places to look at
+        for (uint32_t index = threadIdx.x; index < all; index += kWalkBlock) {
+            const uint32_t b = index / steps, q = index % steps;
+            const uint64_t t = (q_lo + q) * s + b;
+            if (t >= t_lo && t < t_hi) emit((uint32_t)(t - t_lo), b * whole + (b < extra ? b : extra) + q_lo + q);
         }
     }
 }

@@ -1305,6 +1305,7 @@ def test_device_loss_and_cosine_match_oracle(gv, tiny_graph, tiny_alias, d, K, w
 @pytest.mark.parametrize("L,s,count,first_walk,shuffle", [
     (40, 5, 190 * 300, 0, 0), (40, 5, 190 * 300, 0, 1), (40, 5, 57_123, 1000, 1), (40, 5, 7, 5, 1), (40, 5, 1, 0, 1),
     (40, 2, 40_000, 17, 1), (7, 7, 10_000, 3, 1), (3, 5, 9_999, 0, 1), (64, 5, 30_000, 2**33, 1), (1, 1, 500, 0, 0),
+    (40, 1000, 50, 0, 1), (40, 300, 100_000, 9, 1), (64, 64, 200_000, 0, 1), (64, 64, 200_000, 0, 0), (5, 3, 128 * 12 + 5, 0, 1),
 ])
 def test_device_producer_writes_the_oracle_pool(gv, tiny_graph, L, s, count, first_walk, shuffle):
     """gv_augment_device fills device memory with exactly the pool of the oracle's augmentation
