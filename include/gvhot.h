@@ -39,6 +39,11 @@ extern "C" {
 typedef struct gv_ctx gv_ctx;
 
 enum { GV_OK = 0, GV_EINVAL = -1, GV_ENOMEM = -2, GV_ESTATE = -3, GV_EHIP = -4 };
+/* HOGWILD: asynchronous SGD (Sec. 4.3), thousands of samples in flight; it relies on concurrent samples rarely
+ *   sharing rows (Def. 1, Sec. 3.2) and is not meant for graphs on which a single node takes part in a large
+ *   share of all samples (a star): those train in DETERMINISTIC mode.
+ * DETERMINISTIC: samples in pool order, cut into batches without shared rows; equals sequential SGD up to
+ *   fp32 rounding inside a sample.                                                                       */
 enum { GV_MODE_HOGWILD = 0, GV_MODE_DETERMINISTIC = 1 };
 enum { GV_VERTEX = 0, GV_CONTEXT = 1 };
 /* How embedding rows travel between compute units and memory while an
