@@ -347,7 +347,8 @@ int gv_link_prediction_auc(gv_ctx *ctx, const uint32_t *host_edge_first, const u
                            uint64_t num_others, double *auc);
 
 /* Wait for all queued device work of the context; folds event timings into the
- * statistics; reports samples that named an id >= n (GV_EINVAL, once).
+ * statistics; reports samples that named an id >= n (GV_EINVAL, once), and training that has
+ * diverged: an embedding row holding NaN met by an asynchronous tiled launch (GV_ESTATE, once).
  * (Housekeeping, no passage.)                                                   */
 int gv_sync(gv_ctx *ctx);
 /* Counters of the context so far.  (Diagnostic hook, no passage.)               */

@@ -185,11 +185,14 @@ int sync_all(gv_ctx *ctx) {
         for (double x : slots) total += x;
         ctx->stats.train_loss_sum = total;
     }
-    uint32_t flag = 0;
-    GV_HIP(ctx, hipMemcpy(&flag, ctx->error_flag, sizeof flag, hipMemcpyDeviceToHost));
-    if (flag) {
+    uint32_t flag[2] = {0, 0};
+    GV_HIP(ctx, hipMemcpy(flag, ctx->error_flag, sizeof flag, hipMemcpyDeviceToHost));
+    if (flag[0] || flag[1]) {
         GV_HIP(ctx, hipMemset(ctx->error_flag, 0, sizeof flag));
-        return fail(ctx, GV_EINVAL, "a trained pool named a node id >= n (%u); those samples were skipped", ctx->n);
+        if (flag[0])
+            return fail(ctx, GV_EINVAL, "a trained pool named a node id >= n (%u); those samples were skipped", ctx->n);
+        return fail(ctx, GV_ESTATE, "training has diverged: an embedding row holds NaN (asynchronous mode on a graph "
+                    "where one node takes part in a large share of all samples? see GV_MODE_HOGWILD)");
     }
     return GV_OK;
 }
@@ -225,7 +228,7 @@ void free_matrices(gv_ctx *ctx) {
 // Takes over the degrees of a new graph: allocates the matrices (cleared) and the per-node tables.
 int adopt_degrees(gv_ctx *ctx, uint32_t n, std::vector<uint32_t> &&deg) {
     int rc = sync_all(ctx);
-    if (rc != GV_OK && rc != GV_EINVAL) return rc;
+    if (rc != GV_OK && rc != GV_EINVAL && rc != GV_ESTATE) return rc;  // reports about pools already trained do not stop this call
     free_matrices(ctx);
     ctx->n = 0;
     const size_t bytes = (size_t)n * ctx->cfg.dim * sizeof(float);
@@ -604,8 +607,8 @@ int gv_create(const gv_config *cfg, gv_ctx **out) {
         }
         GV_TRY(hipStreamCreateWithFlags(&ctx->compute, hipStreamNonBlocking));
         GV_TRY(hipStreamCreateWithFlags(&ctx->copy, hipStreamNonBlocking));
-        GV_TRY(hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t)));
-        GV_TRY(hipMemset(ctx->error_flag, 0, sizeof(uint32_t)));
+        GV_TRY(hipMalloc((void **)&ctx->error_flag, 2 * sizeof(uint32_t)));
+        GV_TRY(hipMemset(ctx->error_flag, 0, 2 * sizeof(uint32_t)));
         if (cfg->track_loss) {
             GV_TRY(hipMalloc((void **)&ctx->dev_loss, gv::kLossSlots * sizeof(double)));
             GV_TRY(hipMemset(ctx->dev_loss, 0, gv::kLossSlots * sizeof(double)));
@@ -842,7 +845,7 @@ int gv_build_alias(gv_ctx *ctx, double power) {
         order.shrink_to_fit();
 
         rc = sync_all(ctx);
-        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (rc != GV_OK && rc != GV_EINVAL && rc != GV_ESTATE) return rc;  // reports about pools already trained do not stop this call
         GV_HIP(ctx, hipMemcpy(ctx->alias, table.data(), (size_t)n * sizeof(uint4), hipMemcpyHostToDevice));
         GV_HIP(ctx, hipMemcpy(ctx->dev_rank, rank.data(), (size_t)n * sizeof(uint16_t), hipMemcpyHostToDevice));
         GV_HIP(ctx, hipMemcpy(ctx->dev_ranked, ranked_bits.data(), ranked_bits.size() * sizeof(uint32_t),
@@ -890,7 +893,7 @@ int gv_init_embeddings(gv_ctx *ctx, uint64_t seed) {
         int rc = need_graph(ctx);
         if (rc) return rc;
         rc = sync_all(ctx);
-        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (rc != GV_OK && rc != GV_EINVAL && rc != GV_ESTATE) return rc;  // reports about pools already trained do not stop this call
         GV_HIP(ctx, gv::launch_init_vertex(ctx->vertex, ctx->n, ctx->cfg.dim, seed, ctx->compute));
         GV_HIP(ctx, hipMemsetAsync(ctx->context, 0, (size_t)ctx->n * ctx->cfg.dim * sizeof(float), ctx->compute));
         GV_HIP(ctx, hipStreamSynchronize(ctx->compute));
@@ -917,7 +920,7 @@ int gv_set_embeddings(gv_ctx *ctx, int which, const float *host_rows, uint64_t r
         if (rows == 0) return GV_OK;
         if (!host_rows) return fail(ctx, GV_EINVAL, "null input");
         rc = sync_all(ctx);
-        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (rc != GV_OK && rc != GV_EINVAL && rc != GV_ESTATE) return rc;  // reports about pools already trained do not stop this call
         GV_HIP(ctx, hipMemcpy(base, host_rows, rows * ctx->cfg.dim * sizeof(float), hipMemcpyHostToDevice));
         return GV_OK;
     });
@@ -1172,7 +1175,7 @@ int gv_set_adjacency(gv_ctx *ctx, const uint64_t *host_offsets, const uint32_t *
             if (host_adj[e] >= n)
                 return fail(ctx, GV_EINVAL, "adjacency entry %llu names node id >= n", (unsigned long long)e);
         rc = sync_all(ctx);
-        if (rc != GV_OK && rc != GV_EINVAL) return rc;
+        if (rc != GV_OK && rc != GV_EINVAL && rc != GV_ESTATE) return rc;  // reports about pools already trained do not stop this call
         if (ctx->wdegree.size() == n)
             return fail(ctx, GV_ESTATE, "the graph is weighted: gv_set_weighted_graph has uploaded its adjacency already");
         if (ctx->dev_offsets) (void)hipFree(ctx->dev_offsets);

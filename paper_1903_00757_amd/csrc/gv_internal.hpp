@@ -29,7 +29,8 @@ struct TrainArgs {
                               // (see gv_build_alias)
     uint32_t *records;        // tiled schedule: scratch of count x (K + 3) words, written and read by the launch
                               // (u, v, the K negatives, warm flags of the negatives)
-    uint32_t *error_flag;     // set to 1 when a sample names a node id >= n (sample skipped)
+    uint32_t *error_flag;     // two words: [0] set to 1 when a sample names a node id >= n (sample skipped), [1] set
+                              // to 1 when the tiled kernel meets a row that holds NaN (training has diverged)
     double *loss_slots;       // null, or kLossSlots sums: every wave adds the losses its samples saw before their
                               // steps to slot (workgroup number mod kLossSlots)
     uint64_t first_g;         // global position of pairs[0]

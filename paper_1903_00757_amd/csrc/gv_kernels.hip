@@ -821,6 +821,8 @@ __global__ __launch_bounds__(kBlock) void k_train_tiled(TrainArgs a) {
             }
             if (in_chunk < (uint32_t)kWave) break;
         }
+        // a row that is no number any more: training has diverged (reported by the next synchronising call)
+        if (held && !(y[0] == y[0])) a.error_flag[1] = 1u;
         flush();
         if constexpr (kTrack) hand_over_loss(a.loss_slots, loss, lane);
         __syncthreads();  // the next tile overwrites the LDS arrays

@@ -1823,3 +1823,35 @@ def test_configuration_4_at_full_size_tracks_the_sequential_oracle(gv):
         stats = gv.gv_get_stats(ctx)
         assert stats["samples_trained"] == P * last
         assert stats["warm_rows"] == 0 and stats["tiled_launches"] == 0  # the default schedule went pool-order
+
+
+def test_divergence_is_reported(gv):
+    """A star (every sample names the hub) is not what asynchronous mode is for: the tiled policies drive the hub
+    rows to NaN, and the next synchronising call says so instead of handing back NaN silently; deterministic mode
+    trains the same pool to the oracle's embeddings."""
+    n, d, K, w, seed, total = 10_001, 128, 1, 5.0, 1234, 1 << 20
+    src = np.zeros(n - 1, dtype=np.uint32)
+    dst = np.arange(1, n, dtype=np.uint32)
+    deg = W.degrees(n, src, dst)
+    offsets, adj = W.csr_from_edges(n, src, dst)
+    pool, _ = oracle.augment(7, offsets, adj, 40, 5, total)
+    pool = oracle.pseudo_shuffle(pool, 5)
+    with context_for(gv, dim=d, num_neg=K, neg_weight=w, total_samples=total, seed=seed, pool_capacity=total, lr0=LR0,
+                     schedule=TILED, coherence=ATOMIC) as ctx:
+        gv.gv_set_degrees(ctx, deg)
+        gv.gv_build_alias(ctx, 0.75)
+        gv.gv_init_embeddings(ctx, 1)
+        gv.gv_push_pool(ctx, pool)
+        gv.gv_train_pool(ctx)
+        with pytest.raises(gv.GvError) as e:
+            gv.gv_sync(ctx)
+        assert e.value.code == gv.GV_ESTATE and "diverged" in str(e.value)
+        gv.gv_sync(ctx)  # reported once
+        assert not np.isfinite(gv.gv_read_embeddings(ctx, gv.GV_VERTEX, 1, d)).all()
+    short = pool[:20_000]
+    vertex, context = oracle.init_embeddings(1, n, d)
+    got_v, got_c, _ = run_deterministic(gv, n, deg, d, K, w, [short], vertex, context, total, seed)
+    ref_v, ref_c = run_oracle(deg, K, w, [short], vertex, context, total, seed)
+    for got, ref in ((got_v, ref_v), (got_c, ref_c)):
+        fro, mx = rel_errors(got, ref)
+        assert fro <= 1e-5 and mx <= 1e-4, (fro, mx)
